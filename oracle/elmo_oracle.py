@@ -1,0 +1,382 @@
+"""CPU oracle for the ELMO classifier-head training step (TEST INFRASTRUCTURE ONLY).
+
+This module is the slow, plain, FP64 statement of what the head's hot path computes.  It is
+imported only by the tests, by the smoke check and by the benchmark's CPU-baseline leg.  It
+shares no code, tables or constants with the HIP library and never calls it; the product path
+never calls this module.
+
+What is computed follows the paper (ELMO, arxiv 2510.11168):
+
+* number formats and quantisation error                     -- Section 3 "Floating-point formats"
+* stochastic rounding SR(x)                                  -- Section 3, Eq. (1)
+* Kahan-compensated accumulation                             -- Section 3, the three-line recurrence
+* classifier logit gradient  G = sigmoid(Z) - Y, InputGrad = G W, grad W = G^T X
+                                                             -- Appendix "Background of Skipping
+                                                                Loss Computation"
+* order of operations of one head step (logits from the E4M3 cast of X, sigmoid, minus one at
+  the positives, input gradient from the not-yet-updated weights, then the fused
+  gradient + SGD + stochastic-rounding update with FP32 arithmetic)
+                                                             -- Algorithm 1 and Section 4.3
+* momentum-free SGD for the head                             -- Section 4.2
+* Kahan compensation kept in BF16 for head weights           -- Appendix "Precision Recovery"
+* top-k of the score vector                                  -- Appendix, definition of P@k
+
+Label chunking (Section 4.2) does not appear here: every label's logit, gradient row and weight
+update depend only on that label's own weight row, so the chunked and unchunked results are the
+same numbers and the oracle is written unchunked.
+
+Readings taken where the paper is silent (each is repeated at the function that applies it):
+
+* E4M3 is the OCP "FN" flavour (bias 7, largest finite 448, no infinities, one NaN code per
+  sign); finite values beyond the largest finite value clip to it (the paper's "clipping error").
+* BF16 likewise clips finite overflow to its largest finite value.
+* Random numbers: Philox4x32-10 (Salmon et al., SC'11).  key = (seed low, seed high 32 bits);
+  counter = (block low, block high, step low, step high) with block = e // 8 for the flat
+  element index e = label * d + column of the whole [L, d] weight matrix.  The four output words
+  hold eight 16-bit fields; element e uses field e % 8 (field f = word f // 2, low half first).
+* The 16-bit field r decides the rounding by add-and-truncate on the magnitude: the 16 most
+  significant dropped bits of |t| plus r carry into the kept bits or not.  For BF16 (16 dropped
+  bits of an FP32 value) this is Eq. (1) exactly.  For E4M3 (20 dropped bits in the normal range)
+  the probability is Eq. (1)'s rounded down to a multiple of 2^-16.
+* Rounding acts on sign and magnitude separately; a result that rounds to zero keeps its sign.
+* The weight gradient is summed over the batch with no 1/B factor (Algorithm 1, fuse_update).
+* grad W uses the BF16 inputs X, the logits use the E4M3 cast of X (Algorithm 1).
+* With both Kahan and SR enabled, SR is the rounding of s + y and the compensation captures the
+  (random) rounding error; compensation is stored round-to-nearest-even in BF16.
+* The FP32 update arithmetic is two separately rounded operations, lr * g then w - (lr * g).
+
+Parity pins: every function below is pinned by a CPU test against something other than itself
+(published Philox vectors, torch's CPU casts, exhaustive enumeration of the random field,
+closed forms, finite differences, brute force).  The one exception:
+
+* training dynamics / end accuracy (P@k on the paper's datasets): parity unpinned -- the
+  datasets and encoders are not available.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+BF16 = 0
+E4M3 = 1
+
+FLAG_SR = 1
+FLAG_KAHAN = 2
+
+_U32 = np.uint64(0xFFFFFFFF)
+
+# --------------------------------------------------------------------------------------------
+# Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3")
+# --------------------------------------------------------------------------------------------
+
+
+def philox4x32_10(ctr, key):
+    """Philox4x32 with 10 rounds.
+
+    ctr: array [..., 4] of 32-bit words, key: array [..., 2] (broadcastable).  Returns uint32
+    [..., 4].  Each round multiplies words 0 and 2 by the two Philox multipliers, and the new
+    counter is (hi(m1*c2)^c1^k0, lo(m1*c2), hi(m0*c0)^c3^k1, lo(m0*c0)); the key is bumped by
+    the two Weyl constants after every round.
+    """
+    ctr = np.asarray(ctr, dtype=np.uint64)
+    key = np.asarray(key, dtype=np.uint64)
+    c0, c1, c2, c3 = (ctr[..., i] & _U32 for i in range(4))
+    k0, k1 = key[..., 0] & _U32, key[..., 1] & _U32
+    m0 = np.uint64(0xD2511F53)
+    m1 = np.uint64(0xCD9E8D57)
+    w0 = np.uint64(0x9E3779B9)
+    w1 = np.uint64(0xBB67AE85)
+    s32 = np.uint64(32)
+    for _ in range(10):
+        p0 = m0 * c0
+        p1 = m1 * c2
+        c0, c1, c2, c3 = ((p1 >> s32) ^ c1 ^ k0) & _U32, p1 & _U32, ((p0 >> s32) ^ c3 ^ k1) & _U32, p0 & _U32
+        k0 = (k0 + w0) & _U32
+        k1 = (k1 + w1) & _U32
+    out = np.stack(np.broadcast_arrays(c0, c1, c2, c3), axis=-1)
+    return out.astype(np.uint32)
+
+
+def sr_fields(seed: int, step: int, elem):
+    """16-bit random field of each flat element index in `elem` (any integer array).
+
+    Reading (paper names no generator): block = e // 8 is the low 64 bits of the Philox
+    counter, the step is the high 64 bits, the seed is the key; field e % 8 of the 128 output
+    bits, counted from the low half of word 0.
+    """
+    elem = np.asarray(elem, dtype=np.uint64)
+    blk = elem >> np.uint64(3)
+    fld = (elem & np.uint64(7)).astype(np.int64)
+    ctr = np.stack(
+        [
+            blk & _U32,
+            blk >> np.uint64(32),
+            np.full(blk.shape, step & 0xFFFFFFFF, dtype=np.uint64),
+            np.full(blk.shape, (step >> 32) & 0xFFFFFFFF, dtype=np.uint64),
+        ],
+        axis=-1,
+    )
+    key = np.array([seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF], dtype=np.uint64)
+    words = philox4x32_10(ctr, key).astype(np.uint64)
+    w = np.take_along_axis(words, (fld >> 1)[..., None], axis=-1)[..., 0]
+    return ((w >> (np.uint64(16) * (fld & 1).astype(np.uint64))) & np.uint64(0xFFFF)).astype(np.uint32)
+
+
+# --------------------------------------------------------------------------------------------
+# Formats (Section 3, "Floating-point formats"): BF16 = 8 exponent / 7 mantissa bits,
+# E4M3 = 4 exponent / 3 mantissa bits.
+# --------------------------------------------------------------------------------------------
+
+
+def decode_bf16(bits):
+    """BF16 bit patterns (uint16) -> float64, exactly (BF16 is the top half of an FP32)."""
+    b = np.asarray(bits).astype(np.uint32) << np.uint32(16)
+    return b.view(np.float32).astype(np.float64)
+
+
+def decode_e4m3(codes):
+    """E4M3 codes (uint8) -> float64: (-1)^s 2^(e-7) (1 + m/8); e = 0 is subnormal, 2^-6 m/8;
+    e = 15, m = 7 is NaN (OCP flavour, no infinities)."""
+    c = np.asarray(codes).astype(np.int64)
+    s = (c >> 7) & 1
+    e = (c >> 3) & 15
+    m = c & 7
+    mag = np.where(e == 0, m * 2.0**-9, (8 + m) * np.exp2((e - 10).astype(np.float64)))
+    mag = np.where((e == 15) & (m == 7), np.nan, mag)
+    return np.where(s == 1, -mag, mag)
+
+
+def decode(bits, fmt):
+    return decode_bf16(bits) if fmt == BF16 else decode_e4m3(bits)
+
+
+def _split_f32(t):
+    t = np.array(t, dtype=np.float32)  # contiguous copy, keeps the shape (also 0-d)
+    u = t.view(np.uint32)
+    return u >> np.uint32(31), u & np.uint32(0x7FFFFFFF)
+
+
+def round_bf16(t, r=None):
+    """FP32 -> BF16 bits.  r is None: round to nearest, ties to even.  Otherwise r holds the
+    16-bit random fields and the result is SR(t) of Eq. (1): the 16 dropped bits plus r carry
+    into the kept part with probability (dropped bits) / 2^16 = (t - floor) / (ceil - floor).
+    Finite overflow clips to the largest finite BF16; NaN stays NaN."""
+    sign, mag = _split_f32(t)
+    mag64 = mag.astype(np.uint64)
+    if r is None:
+        add = np.uint64(0x7FFF) + ((mag64 >> np.uint64(16)) & np.uint64(1))
+    else:
+        add = np.asarray(r, dtype=np.uint64)
+    q = (mag64 + add) >> np.uint64(16)
+    q = np.minimum(q, np.uint64(0x7F7F))
+    q = np.where(mag > np.uint32(0x7F800000), np.uint64(0x7FC0), q)
+    return ((sign.astype(np.uint64) << np.uint64(15)) | q).astype(np.uint16)
+
+
+def round_e4m3(t, r=None):
+    """FP32 -> E4M3 code.  r None: round to nearest even.  Otherwise SR with a 16-bit field.
+
+    The grid F of Eq. (1) is the set of finite E4M3 values.  Below 2^-6 the grid is uniform with
+    spacing 2^-9 (subnormals), so |t| 2^9 is rounded as a fixed-point number; from 2^-6 upwards
+    each binade has eight steps.  The position of |t| between its grid neighbours is taken to 16
+    fractional bits (lower bits dropped) and added to r; a carry rounds away from zero.
+    Finite overflow clips to 448; NaN maps to the NaN code."""
+    sign, mag = _split_f32(t)
+    a = mag.view(np.float32).astype(np.float64)  # |t| exactly
+    nan = mag > np.uint32(0x7F800000)
+    a = np.where(nan, 0.0, np.minimum(a, 2.0**127))  # infinities clip like any overflow
+    sub = a < 2.0**-6
+    # exponent of the binade (frexp: a = f 2^e with f in [0.5, 1)) and the grid spacing there
+    ex = np.where(sub, -6.0, np.frexp(a)[1].astype(np.float64) - 1.0)
+    gap = np.exp2(ex - 3.0)  # 2^-9 in the subnormal range
+    pos = a / gap  # exact: power-of-two scaling of an FP32 value
+    lo = np.floor(pos)
+    frac = pos - lo
+    if r is None:
+        up = (frac > 0.5) | ((frac == 0.5) & (np.mod(lo, 2.0) == 1.0))
+    else:
+        f16 = np.floor(frac * 65536.0)
+        up = (f16 + np.asarray(r, dtype=np.float64)) >= 65536.0
+    val = (lo + up) * gap
+    val = np.minimum(val, 448.0)
+    # encode the (representable) magnitude
+    e2 = np.frexp(val)[1].astype(np.float64) - 1.0
+    normal = val >= 2.0**-6
+    e_field = np.where(normal, e2 + 7.0, 0.0)
+    m_field = np.where(normal, val / np.exp2(e2) * 8.0 - 8.0, val * 512.0)
+    code = (e_field * 8 + m_field).astype(np.int64)
+    code = np.where(nan, 0x7F, code)
+    return ((sign.astype(np.int64) << 7) | code).astype(np.uint8)
+
+
+def quantize(t, fmt, r=None):
+    return round_bf16(t, r) if fmt == BF16 else round_e4m3(t, r)
+
+
+# --------------------------------------------------------------------------------------------
+# The head step (Algorithm 1; gradients from the appendix on skipping the loss)
+# --------------------------------------------------------------------------------------------
+
+
+def csr_to_dense(indptr, indices, n_cols, col_ids=None):
+    """Dense 0/1 matrix Y[B, n] of the positives.  col_ids (ascending global label ids) selects
+    the columns; None means all n_cols labels."""
+    B = len(indptr) - 1
+    if col_ids is None:
+        Y = np.zeros((B, n_cols), dtype=np.float64)
+        for i in range(B):
+            Y[i, indices[indptr[i]:indptr[i + 1]]] = 1.0
+        return Y
+    col_ids = np.asarray(col_ids, dtype=np.int64)
+    Y = np.zeros((B, len(col_ids)), dtype=np.float64)
+    for i in range(B):
+        row = np.asarray(indices[indptr[i]:indptr[i + 1]], dtype=np.int64)
+        pos = np.searchsorted(col_ids, row)
+        ok = (pos < len(col_ids))
+        ok[ok] &= col_ids[pos[ok]] == row[ok]
+        Y[i, pos[ok]] = 1.0
+    return Y
+
+
+def sigmoid(z):
+    """1 / (1 + e^-z), evaluated without overflow for large |z|."""
+    z = np.asarray(z, dtype=np.float64)
+    ez = np.exp(-np.abs(z))
+    return np.where(z >= 0, 1.0 / (1.0 + ez), ez / (1.0 + ez))
+
+
+def logits_inputs(X_bits, fmt):
+    """Decoded inputs of the logits product: in E4M3 mode the BF16 inputs are first cast to E4M3
+    (round to nearest even), in BF16 mode they are used as they are (Algorithm 1; Section 4.1)."""
+    X = decode_bf16(X_bits)
+    if fmt == E4M3:
+        return decode_e4m3(round_e4m3(X.astype(np.float32)))
+    return X
+
+
+def logits(W_bits, X_bits, fmt):
+    """Z[B, n] = Xq W^T in FP64 for the given weight rows."""
+    return logits_inputs(X_bits, fmt) @ decode(W_bits, fmt).T
+
+
+def logit_gradient(Z, Y):
+    """G = sigmoid(Z) - Y, the 'classifier logit gradient'."""
+    return sigmoid(Z) - Y
+
+
+def bce_loss(Z, Y):
+    """Sum over all (sample, label) of softplus(z) - y z, whose derivative w.r.t. Z is G."""
+    return float(np.sum(np.maximum(Z, 0.0) + np.log1p(np.exp(-np.abs(Z))) - Y * Z))
+
+
+def update_rows(W_bits, comp_bits, dW, lr, fmt, flags, seed, step, elem):
+    """Fused SGD update of weight elements (Algorithm 1, fuse_update; Section 3 Kahan).
+
+    W_bits/comp_bits/dW/elem have the same shape; elem holds the flat element indices that pick
+    the random fields.  FP32 arithmetic, each operation rounded once:
+        g = fl(dW); u = fl(lr g)
+      plain : t = fl(w - u);                      w' = Q(t)
+      Kahan : y = fl(-u - c); t = fl(w + y);      w' = Q(t);  c' = RNE_BF16(fl(fl(w' - w) - y))
+    Q is SR (flag SR) or round-to-nearest-even.  Returns (W_bits', comp_bits' or None).
+    """
+    f32 = np.float32
+    w = decode(W_bits, fmt).astype(f32)  # exact
+    g = np.asarray(dW, dtype=np.float64).astype(f32)
+    u = (f32(lr) * g).astype(f32)
+    r = sr_fields(seed, step, elem) if (flags & FLAG_SR) else None
+    if flags & FLAG_KAHAN:
+        c = decode_bf16(comp_bits).astype(f32)
+        y = ((-u) - c).astype(f32)
+        t = (w + y).astype(f32)
+        Wn = quantize(t, fmt, r)
+        wn = decode(Wn, fmt).astype(f32)
+        with np.errstate(invalid="ignore"):
+            cn = ((wn - w).astype(f32) - y).astype(f32)
+        return Wn, round_bf16(cn)
+    t = (w - u).astype(f32)
+    return quantize(t, fmt, r), None
+
+
+def head_step(W_bits, comp_bits, X_bits, indptr, indices, lr, seed, step, fmt, flags,
+              label_ids=None, d_total=None):
+    """One training step of the head on the given weight rows.
+
+    W_bits [n, d] (uint16 BF16 patterns or uint8 E4M3 codes), comp_bits [n, d] uint16 or None,
+    X_bits [B, d] uint16 (BF16), CSR positives over global label ids.  label_ids gives the global
+    label id of each row of W_bits (None: rows are labels 0..n-1); it selects the positives and
+    the random fields, so a subset of rows gives exactly the rows of the full result.
+
+    Returns dict with Z, G (FP64, [B, n]), dX_partial = G W_old (FP64, [B, d]; the full input
+    gradient when all labels are given), dW = G^T X (FP64), W_new, comp_new, loss.
+    """
+    W_bits = np.asarray(W_bits)
+    n, d = W_bits.shape
+    if label_ids is None:
+        label_ids = np.arange(n, dtype=np.int64)
+    label_ids = np.asarray(label_ids, dtype=np.int64)
+    Wd = decode(W_bits, fmt)
+    X = decode_bf16(X_bits)
+    Xq = logits_inputs(X_bits, fmt)
+    Z = Xq @ Wd.T
+    Y = csr_to_dense(indptr, indices, None, col_ids=label_ids)
+    G = logit_gradient(Z, Y)
+    dX = G @ Wd            # weights before the update (the update comes later in Algorithm 1)
+    dW = G.T @ X           # BF16 inputs, summed over the batch, no 1/B
+    elem = label_ids[:, None] * np.int64(d) + np.arange(d, dtype=np.int64)[None, :]
+    Wn, cn = update_rows(W_bits, comp_bits, dW, lr, fmt, flags, seed, step, elem)
+    return dict(Z=Z, G=G, dX_partial=dX, dW=dW, W_new=Wn, comp_new=cn, loss=bce_loss(Z, Y))
+
+
+def input_gradient_rows(W_bits, X_bits, indptr, indices, fmt, rows, block=65536):
+    """Rows `rows` of the full input gradient dX = (sigmoid(Xq W^T) - Y) W over all labels,
+    streaming the weight rows in blocks so that millions of labels fit in memory.  Also returns
+    the logits of those rows, Z[len(rows), L]."""
+    rows = np.asarray(rows, dtype=np.int64)
+    L, d = W_bits.shape
+    Xq = logits_inputs(np.asarray(X_bits)[rows], fmt)
+    sub_ptr = [0]
+    sub_idx = []
+    for i in rows:
+        sub_idx.append(np.asarray(indices[indptr[i]:indptr[i + 1]], dtype=np.int64))
+        sub_ptr.append(sub_ptr[-1] + len(sub_idx[-1]))
+    sub_idx = np.concatenate(sub_idx) if sub_idx else np.zeros(0, np.int64)
+    dX = np.zeros((len(rows), d), dtype=np.float64)
+    Z = np.empty((len(rows), L), dtype=np.float64)
+    for l0 in range(0, L, block):
+        l1 = min(L, l0 + block)
+        Wd = decode(W_bits[l0:l1], fmt)
+        z = Xq @ Wd.T
+        Y = csr_to_dense(sub_ptr, sub_idx, None, col_ids=np.arange(l0, l1))
+        dX += logit_gradient(z, Y) @ Wd
+        Z[:, l0:l1] = z
+    return dX, Z
+
+
+def topk(Z, k):
+    """Indices and scores of the k largest entries of each row of Z, ordered by (score
+    descending, label id ascending) -- the top_k of the P@k definition."""
+    Z = np.asarray(Z, dtype=np.float64)
+    ids = np.arange(Z.shape[1])
+    idx = np.empty((Z.shape[0], k), dtype=np.int64)
+    for i in range(Z.shape[0]):
+        order = np.lexsort((ids, -Z[i]))
+        idx[i] = order[:k]
+    return idx, np.take_along_axis(Z, idx, axis=1)
+
+
+def kahan_sum_stream(s_bits, c_bits, addends, fmt):
+    """Apply the Kahan recurrence of Section 3 repeatedly to one stored value: s in `fmt`,
+    c in BF16, each v of `addends` added with FP32 arithmetic and round-to-nearest storage.
+    Returns the final (s_bits, c_bits).  Used by the tests of the recurrence."""
+    f32 = np.float32
+    s_bits = np.asarray(s_bits)
+    c_bits = np.asarray(c_bits)
+    for v in addends:
+        s = decode(s_bits, fmt).astype(f32)
+        c = decode_bf16(c_bits).astype(f32)
+        y = (f32(v) - c).astype(f32)
+        t = (s + y).astype(f32)
+        s_new_bits = quantize(t, fmt)
+        s_new = decode(s_new_bits, fmt).astype(f32)
+        c_bits = round_bf16(((s_new - s).astype(f32) - y).astype(f32))
+        s_bits = s_new_bits
+    return s_bits, c_bits

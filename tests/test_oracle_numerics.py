@@ -1,0 +1,270 @@
+"""Pins of the oracle's number formats, random fields, stochastic rounding and Kahan recurrence
+against things other than the oracle itself: the published Philox vectors, torch's CPU casts,
+exhaustive enumeration of the 16-bit random field, closed forms."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import elmo_oracle as o
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------------------- Philox
+def _kat_rows():
+    rows = []
+    with open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                rows.append([int(x, 16) for x in line.split()])
+    return rows
+
+
+def test_philox_known_answers():
+    rows = _kat_rows()
+    assert len(rows) == 3
+    for r in rows:
+        out = o.philox4x32_10(r[0:4], r[4:6])
+        assert [int(x) for x in out] == r[6:10]
+
+
+def test_philox_vectorised_matches_scalar_calls():
+    rng = np.random.default_rng(5)
+    ctr = rng.integers(0, 2**32, size=(17, 4), dtype=np.uint64)
+    key = rng.integers(0, 2**32, size=(2,), dtype=np.uint64)
+    batch = o.philox4x32_10(ctr, key)
+    for i in range(17):
+        assert np.array_equal(batch[i], o.philox4x32_10(ctr[i], key))
+
+
+def test_sr_field_layout():
+    """Element e takes 16-bit field e % 8 of block e // 8; counter = (block, step), key = seed."""
+    seed = 0x0123456789ABCDEF
+    step = 0x1122334455667788
+    e = np.array([0, 1, 2, 7, 8, 15, 8 * (2**33 + 5) + 3], dtype=np.uint64)
+    got = o.sr_fields(seed, step, e)
+    for ei, gi in zip(e.tolist(), got.tolist()):
+        blk, f = divmod(ei, 8)
+        words = o.philox4x32_10(
+            [blk & 0xFFFFFFFF, blk >> 32, step & 0xFFFFFFFF, step >> 32],
+            [seed & 0xFFFFFFFF, seed >> 32])
+        w = int(words[f // 2])
+        assert gi == (w >> (16 * (f % 2))) & 0xFFFF
+
+
+def test_sr_fields_change_with_seed_and_step_and_look_uniform():
+    e = np.arange(1 << 20, dtype=np.uint64)
+    a = o.sr_fields(0, 0, e)
+    assert not np.array_equal(a, o.sr_fields(0, 1, e))
+    assert not np.array_equal(a, o.sr_fields(1, 0, e))
+    assert np.array_equal(a, o.sr_fields(0, 0, e))
+    hist = np.bincount(a >> 8, minlength=256).astype(np.float64)   # 256 cells, df = 255
+    chi2 = np.sum((hist - len(e) / 256) ** 2 / (len(e) / 256))
+    assert 160 < chi2 < 370          # roughly +-4.5 sigma around 255
+    assert abs(a.mean() - 32767.5) < 5 * 65536 / np.sqrt(12 * len(e))
+
+
+# ----------------------------------------------------------------------------- formats
+def test_e4m3_decode_closed_form_and_torch():
+    codes = np.arange(256, dtype=np.uint8)
+    got = o.decode_e4m3(codes)
+    ref = torch.from_numpy(codes).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    assert np.array_equal(np.isnan(got), np.isnan(ref))
+    assert np.array_equal(got[~np.isnan(got)], ref[~np.isnan(ref)])
+    # hand values: the paper quotes the exponent range [-9, 8]: smallest 2^-9, largest 1.75 * 2^8
+    assert got[0x01] == 2.0**-9 and got[0x7E] == 448.0 and got[0x08] == 2.0**-6
+    assert got[0x38] == 1.0 and got[0xB8] == -1.0 and np.isnan(got[0x7F]) and np.isnan(got[0xFF])
+    assert np.signbit(got[0x80]) and got[0x80] == 0.0
+
+
+def test_bf16_decode_is_top_half_of_fp32():
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    ref = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(torch.float64).numpy()
+    got = o.decode_bf16(bits)
+    ok = ~np.isnan(ref)
+    assert np.array_equal(np.isnan(got), ~ok) and np.array_equal(got[ok], ref[ok])
+
+
+def _spread_f32(n, lo, hi, seed):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal(n) * np.exp(rng.uniform(lo, hi, n))).astype(np.float32)
+
+
+def test_rne_bf16_matches_torch_cast():
+    x = np.concatenate([_spread_f32(1 << 21, -85, 85, 1),
+                        np.array([0.0, -0.0, 1e-40, -1e-45, 3.3e38], dtype=np.float32)])
+    ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    finite = np.isfinite(torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy())
+    got = o.round_bf16(x)
+    assert np.array_equal(got[finite], ref[finite])
+    # every mantissa pattern of one binade, including all ties
+    u = (np.uint32(0x3F800000) + np.arange(1 << 23, dtype=np.uint32)).view(np.float32)
+    ref = torch.from_numpy(u).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(o.round_bf16(u), ref)
+
+
+def test_rne_bf16_hand_cases():
+    f = np.float32
+    # spacing at 1 is 2^-7: 1 + 2^-8 is a tie -> even (1.0); 1 + 3*2^-8 is a tie -> 1 + 2^-6
+    cases = {1.0 + 2.0**-8: 0x3F80, 1.0 + 3 * 2.0**-8: 0x3F82, 1.0 + 2.0**-8 + 2.0**-20: 0x3F81,
+             -(1.0 + 2.0**-8): 0xBF80}
+    for x, want in cases.items():
+        assert int(o.round_bf16(f(x))) == want
+    # finite overflow clips to the largest finite value (reading: clipping error), NaN stays NaN
+    assert int(o.round_bf16(f(3.4e38))) == 0x7F7F
+    assert int(o.round_bf16(f(-np.inf))) == 0xFF7F
+    assert (int(o.round_bf16(f(np.nan))) & 0x7FFF) == 0x7FC0
+
+
+def test_rne_e4m3_matches_torch_cast_where_torch_is_finite():
+    x = np.concatenate([_spread_f32(1 << 21, -14, 6.2, 2),
+                        np.array([0.0, -0.0, 2.0**-10, 3 * 2.0**-10, 2.0**-6, 448, 464, -464, 1e-30],
+                                 dtype=np.float32)])
+    x = x[np.abs(x) <= 464]
+    ref = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(o.round_e4m3(x), ref)
+
+
+def test_rne_e4m3_roundtrip_ties_and_clipping():
+    codes = np.arange(256, dtype=np.uint8)
+    finite = (codes & 0x7F) != 0x7F
+    v = o.decode_e4m3(codes[finite]).astype(np.float32)
+    assert np.array_equal(o.round_e4m3(v), codes[finite])
+    f = np.float32
+    assert int(o.round_e4m3(f(2.0**-10))) == 0x00          # tie between 0 and 2^-9 -> even (0)
+    assert int(o.round_e4m3(f(3 * 2.0**-10))) == 0x02      # tie between 1 and 2 steps -> 2
+    assert int(o.round_e4m3(f(1.0625))) == 0x38            # tie 1.0 / 1.125 -> even mantissa
+    assert int(o.round_e4m3(f(1.1875))) == 0x3A            # tie 1.125 / 1.25 -> 1.25
+    assert int(o.round_e4m3(f(-0.0))) == 0x80
+    assert int(o.round_e4m3(f(-1e-9))) == 0x80             # rounds to zero, keeps its sign
+    assert int(o.round_e4m3(f(1e9))) == 0x7E and int(o.round_e4m3(f(-np.inf))) == 0xFE
+    assert int(o.round_e4m3(f(465.0))) == 0x7E             # clips (torch's cast gives NaN here)
+    assert (int(o.round_e4m3(f(np.nan))) & 0x7F) == 0x7F
+    # upper end of the subnormal range rounds up into the first normal code
+    assert int(o.round_e4m3(f(2.0**-6 - 2.0**-12))) == 0x08
+
+
+# ----------------------------------------------------------------------------- SR, Eq. (1)
+def _grid(fmt):
+    if fmt == o.E4M3:
+        c = np.arange(0x7F, dtype=np.uint8)
+        return np.sort(o.decode_e4m3(c))
+    raise ValueError
+
+
+def _neighbours_e4m3(a):
+    g = _grid(o.E4M3)
+    hi = g[np.searchsorted(g, a, side="left")]
+    lo = g[np.searchsorted(g, a, side="right") - 1]
+    return lo, hi
+
+
+ALL_R = np.arange(65536, dtype=np.uint32)
+
+
+@pytest.mark.parametrize("t", [0.3, -0.3, 0.0123, 1.0 + 2.0**-10, 300.1, 2.0**-6 + 2.0**-13,
+                               2.0**-9 * 0.37, -(2.0**-9) * 5.62, 440.0, 1e-5])
+def test_sr_e4m3_enumeration_over_all_fields(t):
+    t = np.float32(t)
+    a = abs(float(t))
+    lo, hi = _neighbours_e4m3(a)
+    out = o.decode_e4m3(o.round_e4m3(np.full(65536, t, np.float32), ALL_R))
+    mags = np.abs(out)
+    assert set(np.unique(mags).tolist()) <= {lo, hi}             # only the two neighbours
+    assert np.all(np.signbit(out) == np.signbit(t))
+    p = (a - lo) / (hi - lo)
+    ups = int(np.sum(mags == hi))
+    assert ups == int(np.floor(p * 65536))                       # Eq. (1), to 16 bits, rounded down
+    # increasing r can only turn a round-down into a round-up
+    assert np.all(np.diff((mags == hi).astype(np.int8)) >= 0)
+
+
+@pytest.mark.parametrize("t", [0.3, -0.02, 1.0 + 2.0**-9, 3.0e38, 1e-39, -7.77e-12, 123456.7])
+def test_sr_bf16_enumeration_is_eq1_exactly(t):
+    t = np.float32(t)
+    bits = o.round_bf16(np.full(65536, t, np.float32), ALL_R)
+    out = o.decode_bf16(bits)
+    lo_bits = np.uint16(np.float32(t).view(np.uint32) >> 16)
+    lo = float(o.decode_bf16(lo_bits))
+    hi = float(o.decode_bf16(np.uint16(lo_bits + 1)))
+    assert set(np.unique(out).tolist()) <= {lo, hi}
+    p = (float(t) - lo) / (hi - lo)                               # exact in FP64
+    assert int(np.sum(out == hi)) == int(round(p * 65536)) and p * 65536 == round(p * 65536)
+
+
+def test_sr_leaves_representable_values_alone_and_clips():
+    codes = np.arange(256, dtype=np.uint8)
+    codes = codes[(codes & 0x7F) != 0x7F]
+    v = o.decode_e4m3(codes).astype(np.float32)
+    for r in (0, 1, 0x8000, 0xFFFF):
+        assert np.array_equal(o.round_e4m3(v, np.full(v.shape, r, np.uint32)), codes)
+    b = np.array([0x0000, 0x8000, 0x3F80, 0x0001, 0x7F7F, 0xC2F7], dtype=np.uint16)
+    vb = o.decode_bf16(b).astype(np.float32)
+    for r in (0, 0xFFFF):
+        assert np.array_equal(o.round_bf16(vb, np.full(vb.shape, r, np.uint32)), b)
+    # beyond the largest finite value every draw clips to it
+    assert set(o.round_e4m3(np.full(65536, 460.0, np.float32), ALL_R).tolist()) == {0x7E}
+    assert set(o.round_bf16(np.full(65536, 3.4e38, np.float32), ALL_R).tolist()) == {0x7F7F}
+
+
+@pytest.mark.parametrize("fmt,x", [(o.E4M3, 0.3), (o.E4M3, -0.0123), (o.E4M3, 2.0**-9 * 2.3),
+                                   (o.E4M3, 437.0), (o.BF16, 0.7123456), (o.BF16, -1.00001e-3),
+                                   (o.BF16, 5.4321e20)])
+def test_sr_mean_over_1e6_philox_draws_within_3_sigma(fmt, x):
+    x = np.float32(x)
+    n = 1_000_000
+    r = o.sr_fields(12345, 7, np.arange(n, dtype=np.uint64))
+    out = o.decode(o.quantize(np.full(n, x, np.float32), fmt, r), fmt)
+    vals = np.unique(out)
+    assert len(vals) == 2
+    gap = vals[1] - vals[0]
+    p = (float(x) - vals[0]) / gap
+    sigma = gap * np.sqrt(p * (1 - p) / n)
+    assert abs(out.mean() - float(x)) < 3 * sigma
+
+
+# ----------------------------------------------------------------------------- Kahan
+def test_kahan_special_case_exact_sum_has_zero_compensation():
+    s = o.round_bf16(np.float32(1.0))
+    s2, c2 = o.kahan_sum_stream(s, np.uint16(0), [0.5], o.BF16)
+    assert float(o.decode_bf16(s2).item()) == 1.5 and float(o.decode_bf16(c2).item()) == 0.0
+
+
+def test_small_updates_cancel_under_rne_but_kahan_tracks_them():
+    """Section 4.1: an update below half the spacing is cancelled by round-to-nearest.  With the
+    compensation term of Section 3 the stored pair (s, c) follows the true sum."""
+    for fmt, s0, v, n in [(o.BF16, 1.0, 2.0**-10, 10_000), (o.E4M3, 0.25, 2.0**-8, 100)]:
+        s_bits = o.quantize(np.float32(s0), fmt)
+        # plain round-to-nearest accumulation: bit-identical after 10^4 updates
+        sb = s_bits
+        for _ in range(50):
+            sb = o.quantize((o.decode(sb, fmt).astype(np.float32) + np.float32(v)).astype(np.float32), fmt)
+        assert sb == s_bits
+        sk, ck = o.kahan_sum_stream(s_bits, np.uint16(0), [v] * n, fmt)
+        true = s0 + n * v
+        sv = float(np.asarray(o.decode(sk, fmt)).item())
+        est = sv - float(np.asarray(o.decode_bf16(ck)).item())
+        ulp = {o.BF16: 2.0**-7, o.E4M3: 2.0**-3}[fmt] * 2 ** np.floor(np.log2(true))
+        assert abs(sv - true) <= ulp            # s itself within one spacing
+        assert abs(est - true) <= ulp * 2.0**-6                        # s - c far closer
+
+
+def test_kahan_random_walk_error_stays_bounded():
+    rng = np.random.default_rng(3)
+    v = (rng.standard_normal(4000) * 1e-3).astype(np.float32)
+    s_bits, c_bits = o.kahan_sum_stream(o.round_bf16(np.float32(0.5)), np.uint16(0), v, o.BF16)
+    true = 0.5 + np.sum(v.astype(np.float64))
+    s = float(np.asarray(o.decode_bf16(s_bits)).item())
+    c = float(np.asarray(o.decode_bf16(c_bits)).item())
+    ulp_s = 2.0**-7 * 2 ** np.floor(np.log2(abs(true)))
+    assert abs(s - true) <= ulp_s
+    # c is itself stored in BF16: each step loses at most half a spacing of c (|c| <= ulp_s / 2)
+    assert abs((s - c) - true) <= 4000 * (ulp_s / 2) * 2.0**-8
+    # without compensation the same stream drifts by many spacings or stalls
+    sb = o.round_bf16(np.float32(0.5))
+    for x in v:
+        sb = o.round_bf16((o.decode_bf16(sb).astype(np.float32) + x).astype(np.float32))
+    assert abs(float(np.asarray(o.decode_bf16(sb)).item()) - true) > abs(s - c - true)
