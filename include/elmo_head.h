@@ -1,0 +1,118 @@
+/* C ABI of the MI355X (gfx950) ELMO classifier-head library.
+ *
+ * The library implements the hot path of ELMO (arxiv 2510.11168): the label-chunked training
+ * step of a linear extreme-classification head whose weights live only in BF16 or FP8-E4M3,
+ * with the weight gradient fused into the SGD update (Algorithm 1 "Float8 XMC classifier",
+ * Sections 4.1-4.3), stochastic rounding (Section 3, Eq. 1), optional Kahan compensation in
+ * BF16 (Section 3; Appendix "Precision Recovery"), and the top-k scoring needed by P@k
+ * (Appendix, definition of P@k).
+ *
+ * General rules
+ *  - Every pointer named W, comp, workspace, X, indptr, indices, dX_out, loss_out, idx_out,
+ *    score_out, src, dst is a DEVICE pointer owned by the caller; the library never allocates or
+ *    frees device memory and never synchronises the device (exception: ELMO_VALIDATE, below).
+ *  - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the null stream);
+ *    results are valid once the stream has reached that point.  Calls on one head must not
+ *    overlap in time: they share its workspace.
+ *  - Return value: 0 success; -1 invalid argument; -2 unsupported format/flag; -3 HIP runtime
+ *    error; -4 invalid label data found by a previous validated step.  elmo_last_error() gives
+ *    the text for the calling thread.
+ *  - All matrices are row-major and densely packed.
+ */
+#ifndef ELMO_HEAD_H
+#define ELMO_HEAD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct elmo_head elmo_head_t; /* opaque, host-side */
+
+/* Storage format of the classifier weights (Section 4.1 pure 16-bit; Section 4.3 8-bit).
+ * ELMO_FP8_E4M3 is the OCP "FN" flavour: bias 7, largest finite value 448, no infinities. */
+enum { ELMO_BF16 = 0, ELMO_FP8_E4M3 = 1 };
+
+/* ELMO_SR: the update rounds with stochastic rounding (Eq. 1), otherwise to nearest even.
+ * ELMO_KAHAN: a BF16 compensation buffer of the shape of W carries the rounding error of every
+ *             update into the next one (the recurrence of Section 3 with s = w, v = -lr*grad).
+ * ELMO_VALIDATE: each step checks the label data on the device (ids inside [0, L), ascending
+ *             within a row) and the NEXT call on the head reads that flag back (one blocking
+ *             4-byte copy) and fails with -4 if it was raised. */
+enum { ELMO_SR = 1u, ELMO_KAHAN = 2u, ELMO_VALIDATE = 4u };
+
+typedef struct {
+  uint32_t flags;         /* ELMO_SR | ELMO_KAHAN | ELMO_VALIDATE */
+  int32_t max_B;          /* largest batch any step / top-k call will use (>= 1) */
+  int64_t max_nnz;        /* largest number of positives in one batch (>= 1) */
+  void* W;                /* [L, d] weights in weight_dtype, updated in place by every step */
+  size_t W_bytes;
+  void* comp;             /* [L, d] BF16 compensation, required iff ELMO_KAHAN, start at zero */
+  size_t comp_bytes;
+  void* workspace;        /* scratch; contents need not survive between calls */
+  size_t workspace_bytes;
+} elmo_head_opts;
+
+/* Bytes of the three buffers a head needs.  workspace = one chunk's logit-gradient buffer
+ * (chunk x round_up(max_B, 64) BF16 values, the paper's per-chunk logits buffer of Section 4.4)
+ * plus O(max_B * d) staging for the inputs and the input-gradient partial sums, plus the
+ * per-batch label index.  Any of the three output pointers may be NULL. */
+int elmo_head_sizes(int64_t L, int32_t d, int weight_dtype, int64_t chunk, int32_t max_B,
+                    int64_t max_nnz, uint32_t flags, size_t* W_bytes, size_t* comp_bytes,
+                    size_t* workspace_bytes);
+
+/* Bytes of the logit / logit-gradient buffer for `batch` samples and `labels` labels held in
+ * 16 bits, batch * labels * 2 -- the quantity Section 4.4 divides by the number of chunks. */
+size_t elmo_logit_buffer_bytes(int64_t batch, int64_t labels);
+
+/* Create a head over caller-owned buffers.  Requirements: L >= 1; d a positive multiple of 128;
+ * chunk a positive multiple of 128 (the labels processed per pass, Section 4.2 "chunking"; it need
+ * not divide L, the last chunk is short); buffers at least as large as elmo_head_sizes says and
+ * 256-byte aligned.  Launches nothing.  *out receives the handle. */
+int elmo_head_create(int64_t L, int32_t d, int weight_dtype, int64_t chunk,
+                     const elmo_head_opts* opts, elmo_head_t** out);
+
+/* One training step of the head (Algorithm 1, XMC_update):
+ *   for each chunk c of labels:  Z = Xq W_c^T ; G = sigmoid(Z) - Y_c ; dX += G W_c (old W_c);
+ *                                W_c <- Q(W_c - lr * G^T X)   (fused, FP32 arithmetic)
+ * X      [B, d] BF16 inputs (the encoder's output).  With FP8 weights the logits use X rounded
+ *        to E4M3 (nearest even); the weight gradient always uses the BF16 X.
+ * indptr [B+1], indices [nnz] int32: CSR of the positive label ids of each sample; within a row
+ *        ids are distinct, ascending, in [0, L); nnz == indptr[B] <= max_nnz.
+ * lr     learning rate; the gradient is summed over the batch (no 1/B).
+ * seed, step: select the stochastic-rounding stream (Philox4x32-10, key = seed, counter =
+ *        (flat element index / 8, step); element l*d+j uses 16-bit field (l*d+j) % 8).  The
+ *        updated weights depend on (seed, step) only -- not on chunk or launch geometry.
+ * dX_out [B, d] BF16 input gradient, or NULL.  loss_out: one float, the summed BCE loss
+ *        sum(softplus(z) - y z) over the batch and all labels, or NULL. */
+int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const int32_t* indptr,
+                   const int32_t* indices, int64_t nnz, float lr, uint64_t seed, uint64_t step,
+                   void* dX_out, float* loss_out, void* hip_stream);
+
+/* Top-k scoring (the top_k of the P@k definition): for each of the B rows of X the k labels with
+ * the largest logit over all L labels, ordered by (logit descending, label id ascending).
+ * idx_out [B, k] int32, score_out [B, k] float (either may be NULL).  1 <= k <= min(L, 128). */
+int elmo_head_topk(elmo_head_t* h, const void* X, int32_t B, int32_t k, int32_t* idx_out,
+                   float* score_out, void* hip_stream);
+
+int elmo_head_destroy(elmo_head_t* h);
+
+/* Text of the last error on the calling thread; never NULL. */
+const char* elmo_last_error(void);
+
+/* Test hooks for the bit-exactness clause of the parity contract.
+ * elmo_quantize: dst[i] = Q(src[i]) for i in [0, n): dtype ELMO_BF16 writes uint16, ELMO_FP8_E4M3
+ * writes uint8; mode 0 = round to nearest even, mode 1 = stochastic rounding with the field of
+ * flat element index first_elem + i (same stream as elmo_head_step).  src: device FP32. */
+int elmo_quantize(const float* src, int64_t n, int dtype, int mode, uint64_t seed, uint64_t step,
+                  uint64_t first_elem, void* dst, void* hip_stream);
+
+/* Host-side Philox4x32-10 (Salmon et al., SC'11) as used for the rounding fields. */
+void elmo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ELMO_HEAD_H */

@@ -44,6 +44,11 @@ Readings taken where the paper is silent (each is repeated at the function that 
 * With both Kahan and SR enabled, SR is the rounding of s + y and the compensation captures the
   (random) rounding error; compensation is stored round-to-nearest-even in BF16.
 * The FP32 update arithmetic is two separately rounded operations, lr * g then w - (lr * g).
+* The logit gradient G is held in BF16: Section 4.4 keeps the per-chunk logit / logit-gradient
+  buffer in 16 bits for BF16 and FP8 training alike, and Algorithm 1 forms sigmoid and the "-1" in
+  that buffer.  Here Z stays FP64 and G = sigmoid(Z) - Y is rounded once, to nearest even, to
+  BF16 before it enters the two products; both products then run in FP64.  `g_exact=True` skips
+  that one rounding (used to pin the formulas by finite differences).
 
 Parity pins: every function below is pinned by a CPU test against something other than itself
 (published Philox vectors, torch's CPU casts, exhaustive enumeration of the random field,
@@ -133,16 +138,22 @@ def decode_bf16(bits):
     return b.view(np.float32).astype(np.float64)
 
 
+def _e4m3_value(c):
+    """Value of one E4M3 code by the format's definition."""
+    s, e, m = (c >> 7) & 1, (c >> 3) & 15, c & 7
+    if e == 15 and m == 7:
+        return float("nan")
+    mag = m * 2.0**-9 if e == 0 else (8 + m) * 2.0 ** (e - 10)
+    return -mag if s else mag
+
+
+_E4M3_VALUES = np.array([_e4m3_value(c) for c in range(256)], dtype=np.float64)
+
+
 def decode_e4m3(codes):
     """E4M3 codes (uint8) -> float64: (-1)^s 2^(e-7) (1 + m/8); e = 0 is subnormal, 2^-6 m/8;
-    e = 15, m = 7 is NaN (OCP flavour, no infinities)."""
-    c = np.asarray(codes).astype(np.int64)
-    s = (c >> 7) & 1
-    e = (c >> 3) & 15
-    m = c & 7
-    mag = np.where(e == 0, m * 2.0**-9, (8 + m) * np.exp2((e - 10).astype(np.float64)))
-    mag = np.where((e == 15) & (m == 7), np.nan, mag)
-    return np.where(s == 1, -mag, mag)
+    e = 15, m = 7 is NaN (OCP flavour, no infinities).  The 256 values are tabulated once."""
+    return _E4M3_VALUES[np.asarray(codes).astype(np.uint8)]
 
 
 def decode(bits, fmt):
@@ -170,6 +181,15 @@ def round_bf16(t, r=None):
     q = np.minimum(q, np.uint64(0x7F7F))
     q = np.where(mag > np.uint32(0x7F800000), np.uint64(0x7FC0), q)
     return ((sign.astype(np.uint64) << np.uint64(15)) | q).astype(np.uint16)
+
+
+def bf16_grid_f64(x):
+    """float64 -> nearest BF16 value (ties to even), returned as float64; one rounding straight
+    from FP64.  Used for values of modest magnitude (the logit gradient lies in (-1, 1))."""
+    x = np.asarray(x, dtype=np.float64)
+    _, e = np.frexp(x)                       # |x| = f 2^e, f in [0.5, 1)
+    ulp = np.exp2(np.maximum(e - 1, -126).astype(np.float64) - 7.0)
+    return np.rint(x / ulp) * ulp
 
 
 def round_e4m3(t, r=None):
@@ -258,9 +278,11 @@ def logits(W_bits, X_bits, fmt):
     return logits_inputs(X_bits, fmt) @ decode(W_bits, fmt).T
 
 
-def logit_gradient(Z, Y):
-    """G = sigmoid(Z) - Y, the 'classifier logit gradient'."""
-    return sigmoid(Z) - Y
+def logit_gradient(Z, Y, g_exact=False):
+    """G = sigmoid(Z) - Y, the 'classifier logit gradient', held in BF16 (Section 4.4): one
+    round-to-nearest-even of the FP64 value.  g_exact=True returns the unrounded FP64 values."""
+    G = sigmoid(Z) - Y
+    return G if g_exact else bf16_grid_f64(G)
 
 
 def bce_loss(Z, Y):
@@ -297,7 +319,7 @@ def update_rows(W_bits, comp_bits, dW, lr, fmt, flags, seed, step, elem):
 
 
 def head_step(W_bits, comp_bits, X_bits, indptr, indices, lr, seed, step, fmt, flags,
-              label_ids=None, d_total=None):
+              label_ids=None, g_exact=False):
     """One training step of the head on the given weight rows.
 
     W_bits [n, d] (uint16 BF16 patterns or uint8 E4M3 codes), comp_bits [n, d] uint16 or None,
@@ -318,7 +340,7 @@ def head_step(W_bits, comp_bits, X_bits, indptr, indices, lr, seed, step, fmt, f
     Xq = logits_inputs(X_bits, fmt)
     Z = Xq @ Wd.T
     Y = csr_to_dense(indptr, indices, None, col_ids=label_ids)
-    G = logit_gradient(Z, Y)
+    G = logit_gradient(Z, Y, g_exact)
     dX = G @ Wd            # weights before the update (the update comes later in Algorithm 1)
     dW = G.T @ X           # BF16 inputs, summed over the batch, no 1/B
     elem = label_ids[:, None] * np.int64(d) + np.arange(d, dtype=np.int64)[None, :]
@@ -326,7 +348,7 @@ def head_step(W_bits, comp_bits, X_bits, indptr, indices, lr, seed, step, fmt, f
     return dict(Z=Z, G=G, dX_partial=dX, dW=dW, W_new=Wn, comp_new=cn, loss=bce_loss(Z, Y))
 
 
-def input_gradient_rows(W_bits, X_bits, indptr, indices, fmt, rows, block=65536):
+def input_gradient_rows(W_bits, X_bits, indptr, indices, fmt, rows, block=65536, g_exact=False):
     """Rows `rows` of the full input gradient dX = (sigmoid(Xq W^T) - Y) W over all labels,
     streaming the weight rows in blocks so that millions of labels fit in memory.  Also returns
     the logits of those rows, Z[len(rows), L]."""
@@ -346,7 +368,7 @@ def input_gradient_rows(W_bits, X_bits, indptr, indices, fmt, rows, block=65536)
         Wd = decode(W_bits[l0:l1], fmt)
         z = Xq @ Wd.T
         Y = csr_to_dense(sub_ptr, sub_idx, None, col_ids=np.arange(l0, l1))
-        dX += logit_gradient(z, Y) @ Wd
+        dX += logit_gradient(z, Y, g_exact) @ Wd
         Z[:, l0:l1] = z
     return dX, Z
 

@@ -1,0 +1,353 @@
+// C ABI of the ELMO classifier-head library (see include/elmo_head.h) and its chunk scheduler.
+#include "../../include/elmo_head.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "kernels.h"
+#include "topk.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define ELMO_HIP(call)                                                                       \
+  do {                                                                                       \
+    hipError_t e_ = (call);                                                                  \
+    if (e_ != hipSuccess) return fail(-3, "%s failed: %s", #call, hipGetErrorString(e_));    \
+  } while (0)
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+// Workspace plan: byte offsets of every region (Section 4.2/4.4: only one chunk's logit-gradient
+// buffer is ever alive; everything else is O(max_B * d) or O(L / 128) integers).
+struct Plan {
+  int64_t L; int d; int fmt; int64_t chunk; int maxB; int64_t max_nnz; uint32_t flags;
+  int Bp_max, tiles_b_max, ntiles;      // padded batch, batch tiles, 128-label tiles of the whole head
+  int dx_rows;                          // rows of FP32 input-gradient partials (slices x padded batch)
+  size_t off_xq, off_xt, off_g, off_dx, off_loss, off_cnt, off_ptr, off_cur, off_pos, off_flag, off_topk, total;
+  size_t W_bytes, comp_bytes;
+};
+
+int make_plan(int64_t L, int d, int fmt, int64_t chunk, int maxB, int64_t max_nnz, uint32_t flags, Plan& p) {
+  if (L < 1) return fail(-1, "L must be >= 1 (got %lld)", (long long)L);
+  if (L > (int64_t)1 << 31) return fail(-1, "L must fit 31 bits (got %lld)", (long long)L);
+  if (d < 128 || d % 128 != 0) return fail(-1, "d must be a positive multiple of 128 (got %d)", d);
+  if (chunk < 128 || chunk % 128 != 0) return fail(-1, "chunk must be a positive multiple of 128 (got %lld)", (long long)chunk);
+  if (chunk > ((int64_t)1 << 30)) return fail(-1, "chunk too large (got %lld)", (long long)chunk);
+  if (maxB < 1 || maxB > 65536) return fail(-1, "max_B must be in [1, 65536] (got %d)", maxB);
+  if (max_nnz < 1 || max_nnz > ((int64_t)1 << 30)) return fail(-1, "max_nnz must be in [1, 2^30] (got %lld)", (long long)max_nnz);
+  if (fmt != ELMO_BF16 && fmt != ELMO_FP8_E4M3) return fail(-2, "unsupported weight_dtype %d", fmt);
+  if (flags & ~(uint32_t)(ELMO_SR | ELMO_KAHAN | ELMO_VALIDATE)) return fail(-2, "unknown flag bits 0x%x", flags);
+  p.L = L; p.d = d; p.fmt = fmt; p.chunk = chunk; p.maxB = maxB; p.max_nnz = max_nnz; p.flags = flags;
+  p.Bp_max = round_up(maxB, 64);
+  p.tiles_b_max = (p.Bp_max + 127) / 128;
+  p.ntiles = (int)((L + 127) / 128);
+  const int tiles_j = d / 128;
+  p.dx_rows = std::min(65536 / tiles_j + 128 * p.tiles_b_max + 128, 64 * 128 * p.tiles_b_max);
+  const int64_t chunk_eff = std::min<int64_t>(chunk, (L + 127) / 128 * 128);
+  size_t o = 0;
+  p.off_xq = o;  o += align256(fmt == ELMO_FP8_E4M3 ? (size_t)p.Bp_max * d : 0);
+  p.off_xt = o;  o += align256((size_t)d * p.Bp_max * 2);
+  p.off_g = o;   o += align256((size_t)chunk_eff * p.Bp_max * 2);
+  p.off_dx = o;  o += align256((size_t)p.dx_rows * d * 4);
+  p.off_loss = o; o += align256((size_t)p.ntiles * p.tiles_b_max * 4);
+  p.off_cnt = o; o += align256((size_t)(p.ntiles + 1) * 4);
+  p.off_ptr = o; o += align256((size_t)(p.ntiles + 1) * 4);
+  p.off_cur = o; o += align256((size_t)(p.ntiles + 1) * 4);
+  p.off_pos = o; o += align256((size_t)max_nnz * 8);
+  p.off_flag = o; o += 256;
+  p.off_topk = o; o += align256(elmo::topk_scratch_bytes(p.Bp_max, chunk_eff));
+  p.total = o;
+  p.W_bytes = (size_t)L * d * (fmt == ELMO_FP8_E4M3 ? 1 : 2);
+  p.comp_bytes = (flags & ELMO_KAHAN) ? (size_t)L * d * 2 : 0;
+  return 0;
+}
+
+int check_launch(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(-3, "launch of %s failed: %s", what, hipGetErrorString(e));
+  return 0;
+}
+
+}  // namespace
+
+struct elmo_head {
+  Plan p;
+  char* W; char* comp; char* ws;
+  bool validated_step_pending;
+};
+
+extern "C" {
+
+const char* elmo_last_error(void) { return g_err; }
+
+size_t elmo_logit_buffer_bytes(int64_t batch, int64_t labels) {
+  return (batch < 0 || labels < 0) ? 0 : (size_t)batch * (size_t)labels * 2;
+}
+
+int elmo_head_sizes(int64_t L, int32_t d, int weight_dtype, int64_t chunk, int32_t max_B, int64_t max_nnz,
+                    uint32_t flags, size_t* W_bytes, size_t* comp_bytes, size_t* workspace_bytes) {
+  Plan p;
+  const int rc = make_plan(L, d, weight_dtype, chunk, max_B, max_nnz, flags, p);
+  if (rc) return rc;
+  if (W_bytes) *W_bytes = p.W_bytes;
+  if (comp_bytes) *comp_bytes = p.comp_bytes;
+  if (workspace_bytes) *workspace_bytes = p.total;
+  return 0;
+}
+
+int elmo_head_create(int64_t L, int32_t d, int weight_dtype, int64_t chunk, const elmo_head_opts* opts,
+                     elmo_head_t** out) {
+  if (!opts || !out) return fail(-1, "opts and out must not be NULL");
+  Plan p;
+  const int rc = make_plan(L, d, weight_dtype, chunk, opts->max_B, opts->max_nnz, opts->flags, p);
+  if (rc) return rc;
+  if (!opts->W || opts->W_bytes < p.W_bytes) return fail(-1, "W buffer missing or smaller than %zu bytes", p.W_bytes);
+  if ((opts->flags & ELMO_KAHAN) && (!opts->comp || opts->comp_bytes < p.comp_bytes))
+    return fail(-1, "ELMO_KAHAN needs a compensation buffer of %zu bytes", p.comp_bytes);
+  if (!opts->workspace || opts->workspace_bytes < p.total) return fail(-1, "workspace missing or smaller than %zu bytes", p.total);
+  if (((uintptr_t)opts->W | (uintptr_t)opts->workspace | (uintptr_t)opts->comp) & 255)
+    return fail(-1, "W, comp and workspace must be 256-byte aligned");
+  elmo_head* h = new (std::nothrow) elmo_head;
+  if (!h) return fail(-3, "out of host memory");
+  h->p = p;
+  h->W = (char*)opts->W;
+  h->comp = (opts->flags & ELMO_KAHAN) ? (char*)opts->comp : nullptr;
+  h->ws = (char*)opts->workspace;
+  h->validated_step_pending = false;
+  *out = h;
+  return 0;
+}
+
+int elmo_head_destroy(elmo_head_t* h) {
+  if (!h) return fail(-1, "NULL head");
+  delete h;
+  return 0;
+}
+
+void elmo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  elmo::U4 c{ctr[0], ctr[1], ctr[2], ctr[3]};
+  c = elmo::philox4x32_10(c, key[0], key[1]);
+  out[0] = c.x; out[1] = c.y; out[2] = c.z; out[3] = c.w;
+}
+
+int elmo_quantize(const float* src, int64_t n, int dtype, int mode, uint64_t seed, uint64_t step,
+                  uint64_t first_elem, void* dst, void* hip_stream) {
+  if (n < 0 || (n > 0 && (!src || !dst))) return fail(-1, "bad src/dst/n");
+  if (dtype != ELMO_BF16 && dtype != ELMO_FP8_E4M3) return fail(-2, "unsupported dtype %d", dtype);
+  if (mode != 0 && mode != 1) return fail(-1, "mode must be 0 (nearest) or 1 (stochastic)");
+  if (n == 0) return 0;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int grid = (int)std::min<int64_t>((n + elmo::kThreads - 1) / elmo::kThreads, 256 * 16);
+  if (dtype == ELMO_BF16) {
+    if (mode) elmo::k_quantize<elmo::FMT_BF16, true><<<grid, elmo::kThreads, 0, st>>>(src, n, seed, step, first_elem, dst);
+    else elmo::k_quantize<elmo::FMT_BF16, false><<<grid, elmo::kThreads, 0, st>>>(src, n, seed, step, first_elem, dst);
+  } else {
+    if (mode) elmo::k_quantize<elmo::FMT_E4M3, true><<<grid, elmo::kThreads, 0, st>>>(src, n, seed, step, first_elem, dst);
+    else elmo::k_quantize<elmo::FMT_E4M3, false><<<grid, elmo::kThreads, 0, st>>>(src, n, seed, step, first_elem, dst);
+  }
+  return check_launch("k_quantize");
+}
+
+}  // extern "C"
+
+namespace {
+
+int poll_validation(elmo_head* h) {
+  if (!(h->p.flags & ELMO_VALIDATE) || !h->validated_step_pending) return 0;
+  int flag = 0;
+  ELMO_HIP(hipMemcpy(&flag, h->ws + h->p.off_flag, sizeof flag, hipMemcpyDeviceToHost));
+  h->validated_step_pending = false;
+  if (flag) return fail(-4, "the previous step found invalid label data (code %d: 1 = bad indptr, 2 = id out of range or not ascending)", flag);
+  return 0;
+}
+
+template <bool FP8, bool LOSS>
+void launch_logits(hipStream_t st, int grid, const char* Xa, int a_rows, const char* Wc, int n, int d, int Bp, int B,
+                   uint16_t* Gt, const int* binptr, const int2* pos, int tile0, float* loss_slots) {
+  elmo::k_logits<FP8, LOSS><<<grid, elmo::kThreads, elmo::kLogitsSmem, st>>>(Xa, a_rows, Wc, n, d, Bp, B, Gt, binptr, pos,
+                                                                             tile0, loss_slots);
+}
+
+template <int FMT>
+void launch_update(hipStream_t st, int grid, bool sr, bool kahan, const char* Gt, const char* XT, char* Wc, uint16_t* Cc,
+                   int n, int d, int Bp, float lr, uint64_t seed, uint64_t step, uint64_t elem0) {
+#define ELMO_UPD(SR_, KA_) \
+  elmo::k_update<FMT, SR_, KA_><<<grid, elmo::kThreads, elmo::kUpdateSmem, st>>>(Gt, XT, Wc, Cc, n, d, Bp, lr, seed, step, elem0)
+  if (sr && kahan) ELMO_UPD(true, true);
+  else if (sr) ELMO_UPD(true, false);
+  else if (kahan) ELMO_UPD(false, true);
+  else ELMO_UPD(false, false);
+#undef ELMO_UPD
+}
+
+// Opt in to more than 64 KiB of dynamic LDS for the tile kernels (done once per process).
+int raise_lds_limits() {
+  static bool done = false;
+  if (done) return 0;
+#define ELMO_ATTR(k, bytes) ELMO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))
+  ELMO_ATTR((elmo::k_logits<true, true>), elmo::kLogitsSmem);
+  ELMO_ATTR((elmo::k_logits<true, false>), elmo::kLogitsSmem);
+  ELMO_ATTR((elmo::k_logits<false, true>), elmo::kLogitsSmem);
+  ELMO_ATTR((elmo::k_logits<false, false>), elmo::kLogitsSmem);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, true, true>), elmo::kUpdateSmem);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, true, false>), elmo::kUpdateSmem);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, false, true>), elmo::kUpdateSmem);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, false, false>), elmo::kUpdateSmem);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, true, true>), elmo::kUpdateSmem);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, true, false>), elmo::kUpdateSmem);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, false, true>), elmo::kUpdateSmem);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, false, false>), elmo::kUpdateSmem);
+  ELMO_ATTR((elmo::k_topk_chunk<true>), elmo::kTopkSmem);
+  ELMO_ATTR((elmo::k_topk_chunk<false>), elmo::kTopkSmem);
+#undef ELMO_ATTR
+  done = true;
+  return 0;
+}
+
+}  // namespace
+
+extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const int32_t* indptr, const int32_t* indices,
+                              int64_t nnz, float lr, uint64_t seed, uint64_t step, void* dX_out, float* loss_out,
+                              void* hip_stream) {
+  if (!h) return fail(-1, "NULL head");
+  const Plan& p = h->p;
+  if (!X || !indptr) return fail(-1, "X and indptr must not be NULL");
+  if (B < 1 || B > p.maxB) return fail(-1, "B = %d outside [1, max_B = %d]", B, p.maxB);
+  if (nnz < 0 || nnz > p.max_nnz) return fail(-1, "nnz = %lld outside [0, max_nnz = %lld]", (long long)nnz, (long long)p.max_nnz);
+  if (nnz > 0 && !indices) return fail(-1, "indices must not be NULL when nnz > 0");
+  if (int rc = poll_validation(h)) return rc;
+  if (int rc = raise_lds_limits()) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const bool fp8 = p.fmt == ELMO_FP8_E4M3;
+  const int d = p.d, Bp = round_up(B, 64), Bp128 = round_up(Bp, 128);
+  const int tiles_b = Bp128 / 128, tiles_j = d / 128;
+
+  uint8_t* Xq = fp8 ? (uint8_t*)(h->ws + p.off_xq) : nullptr;
+  uint16_t* XT = (uint16_t*)(h->ws + p.off_xt);
+  uint16_t* Gt = (uint16_t*)(h->ws + p.off_g);
+  float* dXacc = (float*)(h->ws + p.off_dx);
+  float* loss_slots = (float*)(h->ws + p.off_loss);
+  int* cnt = (int*)(h->ws + p.off_cnt);
+  int* ptr = (int*)(h->ws + p.off_ptr);
+  int* cur = (int*)(h->ws + p.off_cur);
+  int2* pos = (int2*)(h->ws + p.off_pos);
+  int* flag = (p.flags & ELMO_VALIDATE) ? (int*)(h->ws + p.off_flag) : nullptr;
+
+  // label slices of the input-gradient product: enough workgroups to fill 256 CUs twice over
+  int S = std::max(1, (512 + tiles_b * tiles_j - 1) / (tiles_b * tiles_j));
+  S = std::min(S, p.dx_rows / Bp128);
+  S = std::max(1, std::min(S, 64));
+
+  // ---- step set-up: inputs, zeroed partial sums, label index
+  {
+    const size_t n = (size_t)Bp * d;
+    elmo::k_prep_x<<<(int)std::min<size_t>((n + 255) / 256, 4096), elmo::kThreads, 0, st>>>((const uint16_t*)X, B, Bp, d, Xq, XT);
+    if (int rc = check_launch("k_prep_x")) return rc;
+    if (dX_out) {
+      const size_t w = (size_t)S * Bp128 * d;
+      elmo::k_fill_u32<<<(int)std::min<size_t>((w + 255) / 256, 4096), elmo::kThreads, 0, st>>>((uint32_t*)dXacc, w, 0u);
+      if (int rc = check_launch("k_fill_u32")) return rc;
+    }
+    elmo::k_fill_u32<<<(p.ntiles + 1 + 255) / 256, elmo::kThreads, 0, st>>>((uint32_t*)cnt, (size_t)p.ntiles + 1, 0u);
+    if (int rc = check_launch("k_fill_u32")) return rc;
+    if (flag) {
+      elmo::k_fill_u32<<<1, elmo::kThreads, 0, st>>>((uint32_t*)flag, 1, 0u);
+      if (int rc = check_launch("k_fill_u32")) return rc;
+    }
+    elmo::k_label_hist<<<(B + 255) / 256, elmo::kThreads, 0, st>>>(indptr, indices, B, p.L, nnz, cnt, flag);
+    if (int rc = check_launch("k_label_hist")) return rc;
+    elmo::k_label_scan<<<1, 1024, 0, st>>>(cnt, p.ntiles, ptr, cur);
+    if (int rc = check_launch("k_label_scan")) return rc;
+    elmo::k_label_scatter<<<(B + 255) / 256, elmo::kThreads, 0, st>>>(indptr, indices, B, p.L, nnz, cur, pos);
+    if (int rc = check_launch("k_label_scatter")) return rc;
+    if (flag) h->validated_step_pending = true;
+  }
+
+  // ---- chunk schedule (Section 4.2): forward, backward and update of one label chunk at a time
+  const size_t esz = fp8 ? 1 : 2;
+  const char* Xa = fp8 ? (const char*)Xq : (const char*)X;
+  const int a_rows = fp8 ? Bp : B;
+  for (int64_t c0 = 0; c0 < p.L; c0 += p.chunk) {
+    const int n = (int)std::min<int64_t>(p.chunk, p.L - c0);
+    const int tiles_l = (n + 127) / 128;
+    char* Wc = h->W + (size_t)c0 * d * esz;
+    uint16_t* Cc = h->comp ? (uint16_t*)h->comp + (size_t)c0 * d : nullptr;
+    const int tile0 = (int)(c0 / 128);
+    {
+      const int grid = tiles_l * tiles_b;
+      if (fp8) {
+        if (loss_out) launch_logits<true, true>(st, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots);
+        else launch_logits<true, false>(st, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots);
+      } else {
+        if (loss_out) launch_logits<false, true>(st, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots);
+        else launch_logits<false, false>(st, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots);
+      }
+      if (int rc = check_launch("k_logits")) return rc;
+    }
+    if (dX_out) {
+      const int grid = tiles_b * tiles_j * S;
+      const int smem = 2 * (64 * 256 + 64 * (fp8 ? 128 : 256));
+      if (fp8) elmo::k_dx<true><<<grid, elmo::kThreads, smem, st>>>((const char*)Gt, Wc, dXacc, n, d, Bp, Bp128, S);
+      else elmo::k_dx<false><<<grid, elmo::kThreads, smem, st>>>((const char*)Gt, Wc, dXacc, n, d, Bp, Bp128, S);
+      if (int rc = check_launch("k_dx")) return rc;
+    }
+    {
+      const int grid = tiles_l * tiles_j;
+      const bool sr = p.flags & ELMO_SR, kahan = p.flags & ELMO_KAHAN;
+      const uint64_t elem0 = (uint64_t)c0 * (uint64_t)d;
+      if (fp8) launch_update<elmo::FMT_E4M3>(st, grid, sr, kahan, (const char*)Gt, (const char*)XT, Wc, Cc, n, d, Bp, lr, seed, step, elem0);
+      else launch_update<elmo::FMT_BF16>(st, grid, sr, kahan, (const char*)Gt, (const char*)XT, Wc, Cc, n, d, Bp, lr, seed, step, elem0);
+      if (int rc = check_launch("k_update")) return rc;
+    }
+  }
+
+  if (dX_out || loss_out) {
+    const size_t n = (size_t)B * d;
+    const int grid = dX_out ? (int)std::min<size_t>((n + 255) / 256, 4096) : 1;
+    elmo::k_finalize<<<grid, elmo::kThreads, 0, st>>>(dXacc, S, Bp128, B, d, (uint16_t*)dX_out, loss_slots,
+                                                     p.ntiles * tiles_b, loss_out);
+    if (int rc = check_launch("k_finalize")) return rc;
+  }
+  return 0;
+}
+
+extern "C" int elmo_head_topk(elmo_head_t* h, const void* X, int32_t B, int32_t k, int32_t* idx_out, float* score_out,
+                              void* hip_stream) {
+  if (!h) return fail(-1, "NULL head");
+  const Plan& p = h->p;
+  if (!X) return fail(-1, "X must not be NULL");
+  if (B < 1 || B > p.maxB) return fail(-1, "B = %d outside [1, max_B = %d]", B, p.maxB);
+  if (k < 1 || k > elmo::kTopkMaxK || k > p.L) return fail(-1, "k = %d outside [1, min(L, %d)]", k, elmo::kTopkMaxK);
+  if (int rc = poll_validation(h)) return rc;
+  if (int rc = raise_lds_limits()) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const bool fp8 = p.fmt == ELMO_FP8_E4M3;
+  const int d = p.d, Bp = round_up(B, 64);
+  uint8_t* Xq = fp8 ? (uint8_t*)(h->ws + p.off_xq) : nullptr;
+  uint16_t* XT = (uint16_t*)(h->ws + p.off_xt);
+  {
+    const size_t n = (size_t)Bp * d;
+    elmo::k_prep_x<<<(int)std::min<size_t>((n + 255) / 256, 4096), elmo::kThreads, 0, st>>>((const uint16_t*)X, B, Bp, d, Xq, XT);
+    if (int rc = check_launch("k_prep_x")) return rc;
+  }
+  const char* Xa = fp8 ? (const char*)Xq : (const char*)X;
+  const int a_rows = fp8 ? Bp : B;
+  return elmo::topk_run(st, fp8, Xa, a_rows, h->W, p.L, d, p.chunk, B, Bp, k, h->ws + p.off_topk, idx_out, score_out, g_err,
+                        sizeof g_err);
+}

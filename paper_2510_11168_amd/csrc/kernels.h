@@ -1,0 +1,546 @@
+// HIP kernels of the ELMO head step for gfx950 (Algorithm 1 of the paper, one label chunk at a
+// time): logits + sigmoid-BCE gradient epilogue, input-gradient product, fused weight-gradient +
+// SGD + Kahan + stochastic-rounding update, and the small per-step helpers around them.
+#pragma once
+#include "numerics.h"
+#include "tiles.h"
+
+namespace elmo {
+
+// ---------------------------------------------------------------------------------------------
+// Small helpers
+// ---------------------------------------------------------------------------------------------
+__device__ inline uint32_t pack2_bf16(float a, float b) {   // hardware round-to-nearest-even
+  bf16x2 v;
+  v[0] = (__bf16)a;
+  v[1] = (__bf16)b;
+  return __builtin_bit_cast(uint32_t, v);
+}
+__device__ inline float sigmoidf_fast(float z) { return __frcp_rn(1.0f + __expf(-z)); }
+__device__ inline float softplusf_fast(float z) { return fmaxf(z, 0.0f) + __logf(1.0f + __expf(-fabsf(z))); }
+
+__device__ inline float block_sum(float v, float* red /*>= 4 floats of LDS*/) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  if (lane == 0) red[w] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+__global__ void __launch_bounds__(kThreads) k_fill_u32(uint32_t* __restrict__ p, size_t n, uint32_t v) {
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (size_t)gridDim.x * kThreads) p[i] = v;
+}
+
+// Step set-up of the inputs (Algorithm 1: "X.t().to(float8_e4m3fn)"): the E4M3 cast Xq [Bp, d]
+// used by the logits product and the transposed BF16 copy XT [d, Bp] used by the weight-gradient
+// product; rows B..Bp-1 are zero padding.
+__global__ void __launch_bounds__(kThreads) k_prep_x(const uint16_t* __restrict__ X, int B, int Bp, int d,
+                                                     uint8_t* __restrict__ Xq, uint16_t* __restrict__ XT) {
+  const size_t n = (size_t)Bp * d;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (size_t)gridDim.x * kThreads) {
+    const int b = (int)(i / d), j = (int)(i % d);
+    const uint32_t bits = b < B ? X[i] : 0u;
+    if (Xq) Xq[i] = (uint8_t)e4m3_rne(bf16_decode(bits));
+    XT[(size_t)j * Bp + b] = (uint16_t)bits;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Per-batch label index: the positives (CSR by sample) regrouped by 128-label tile, so that the
+// logits epilogue of a tile finds its few positives with two loads (Algorithm 1 filters the
+// COO pairs of each chunk; here the filter is a counting sort done once per step).
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kThreads) k_label_hist(const int* __restrict__ indptr, const int* __restrict__ indices,
+                                                         int B, int64_t L, int64_t nnz, int* __restrict__ cnt,
+                                                         int* __restrict__ bad) {
+  const int b = blockIdx.x * kThreads + threadIdx.x;
+  if (b >= B) return;
+  const int p0 = indptr[b], p1 = indptr[b + 1];
+  if (p0 < 0 || p1 < p0 || p1 > nnz) { if (bad) atomicOr(bad, 1); return; }
+  int prev = -1;
+  for (int p = p0; p < p1; ++p) {
+    const int l = indices[p];
+    if (l < 0 || l >= L || l <= prev) { if (bad) atomicOr(bad, 2); if (l < 0 || l >= L) continue; }
+    prev = l;
+    atomicAdd(&cnt[l >> 7], 1);
+  }
+}
+// Exclusive scan of cnt[0..nb) into ptr[0..nb] (ptr[nb] = total) and cur[0..nb) = ptr. One workgroup.
+__global__ void __launch_bounds__(1024) k_label_scan(const int* __restrict__ cnt, int nb, int* __restrict__ ptr, int* __restrict__ cur) {
+  __shared__ int part[1024];
+  __shared__ int carry_s;
+  if (threadIdx.x == 0) carry_s = 0;
+  __syncthreads();
+  for (int base = 0; base < nb; base += 1024) {
+    const int i = base + threadIdx.x;
+    const int v = i < nb ? cnt[i] : 0;
+    part[threadIdx.x] = v;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+      const int t = threadIdx.x >= o ? part[threadIdx.x - o] : 0;
+      __syncthreads();
+      part[threadIdx.x] += t;
+      __syncthreads();
+    }
+    const int carry = carry_s;
+    const int excl = carry + part[threadIdx.x] - v;
+    if (i < nb) { ptr[i] = excl; cur[i] = excl; }
+    __syncthreads();
+    if (threadIdx.x == 1023) carry_s = carry + part[1023];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) ptr[nb] = carry_s;
+}
+__global__ void __launch_bounds__(kThreads) k_label_scatter(const int* __restrict__ indptr, const int* __restrict__ indices,
+                                                            int B, int64_t L, int64_t nnz, int* __restrict__ cur,
+                                                            int2* __restrict__ pos) {
+  const int b = blockIdx.x * kThreads + threadIdx.x;
+  if (b >= B) return;
+  const int p0 = indptr[b], p1 = indptr[b + 1];
+  if (p0 < 0 || p1 < p0 || p1 > nnz) return;
+  for (int p = p0; p < p1; ++p) {
+    const int l = indices[p];
+    if (l < 0 || l >= L) continue;
+    const int slot = atomicAdd(&cur[l >> 7], 1);
+    if (slot < nnz) pos[slot] = make_int2(l, b);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Logits + fused epilogue (Algorithm 1: matmul_fp8, sigmoid_, "-= 1" at the positives).
+// One workgroup computes a 128 (samples) x 128 (labels) tile of Z = Xq W_c^T with FP32
+// accumulation over the full embedding width, then G = sigmoid(Z) - Y, and stores G^T[l][b] as
+// BF16 (labels x batch, the layout the paper's logits buffer has).  Z never reaches memory.
+// FP8: both operands E4M3, v_mfma_f32_32x32x64_f8f6f4.  BF16: v_mfma_f32_32x32x16_bf16.
+// ---------------------------------------------------------------------------------------------
+constexpr int kZPitch = 132;                                   // floats per staged row
+constexpr int kLogitsSmem = 128 * kZPitch * 4 + 128 * 4 * 4 + 16;   // stage + positives mask + reduce
+static_assert(kLogitsSmem >= 4 * 128 * 128, "main-loop buffers must fit the epilogue's LDS");
+
+template <bool FP8, bool LOSS>
+__global__ void __launch_bounds__(kThreads, 2)
+k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, int n, int d, int Bp, int B,
+         uint16_t* __restrict__ Gt, const int* __restrict__ binptr, const int2* __restrict__ pos, int tile0,
+         float* __restrict__ loss_slots) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
+  const int tiles_b = (Bp + 127) >> 7;
+  const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
+  const int lt = wg / tiles_b, bt = wg % tiles_b;
+  const int b0 = bt << 7, l0 = lt << 7;
+  const size_t rowb = (size_t)d * (FP8 ? 1 : 2);
+  const int nk = (int)(rowb >> 7);
+
+  TileLoader<128, 128> la, lb;
+  const char* ga = Xa + (size_t)b0 * rowb;
+  const char* gb = Wc + (size_t)l0 * rowb;
+  const int va = a_rows - b0, vb = n - l0;
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  la.load(ga, rowb, va, tid);
+  lb.load(gb, rowb, vb, tid);
+  la.store(smem, tid);
+  lb.store(smem + 16384, tid);
+  __syncthreads();
+  for (int ks = 0; ks < nk; ++ks) {
+    const char* sa = smem + (ks & 1) * 32768;
+    const char* sb = sa + 16384;
+    if (ks + 1 < nk) {
+      la.load(ga + (size_t)(ks + 1) * 128, rowb, va, tid);
+      lb.load(gb + (size_t)(ks + 1) * 128, rowb, vb, tid);
+    }
+    if (FP8) {
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        i32x8 a[2], b[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) a[i] = frag_fp8(sa, wm * 64 + 32 * i, kk, lane);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) b[j] = frag_fp8(sb, wn * 64 + 32 * j, kk, lane);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 0, 0, 0, 0, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        bf16x8 a[2], b[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) a[i] = frag_bf16(sa, wm * 64 + 32 * i, kk, lane);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) b[j] = frag_bf16(sb, wn * 64 + 32 * j, kk, lane);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+      }
+    }
+    if (ks + 1 < nk) {
+      char* da = smem + ((ks + 1) & 1) * 32768;
+      la.store(da, tid);
+      lb.store(da + 16384, tid);
+    }
+    __syncthreads();
+  }
+
+  // ---- epilogue: stage Z^T (labels x samples) in LDS as FP32
+  float* zs = reinterpret_cast<float*>(smem);
+  uint32_t* ym = reinterpret_cast<uint32_t*>(smem + 128 * kZPitch * 4);
+  float* red = reinterpret_cast<float*>(smem + 128 * kZPitch * 4 + 128 * 4 * 4);
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int l = wn * 64 + 32 * j + (lane & 31);
+        const int b = wm * 64 + 32 * i + 8 * q + 4 * (lane >> 5);
+        f32x4 z;
+        z[0] = acc[i][j][4 * q]; z[1] = acc[i][j][4 * q + 1]; z[2] = acc[i][j][4 * q + 2]; z[3] = acc[i][j][4 * q + 3];
+        *reinterpret_cast<f32x4*>(zs + l * kZPitch + b) = z;
+      }
+  for (int i = tid; i < 128 * 4; i += kThreads) ym[i] = 0u;
+  __syncthreads();
+
+  // ---- positives of this label tile that fall into this batch tile
+  float loss = 0.0f;
+  {
+    const int gt = tile0 + lt;
+    const int p0 = binptr[gt], p1 = binptr[gt + 1];
+    for (int p = p0 + tid; p < p1; p += kThreads) {
+      const int2 e = pos[p];
+      const int lr_ = e.x - (gt << 7), br = e.y - b0;
+      if (br >= 0 && br < 128 && lr_ >= 0 && lr_ < 128) {
+        atomicOr(&ym[lr_ * 4 + (br >> 5)], 1u << (br & 31));
+        if (LOSS) loss -= zs[lr_ * kZPitch + br];
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- G = sigmoid(Z) - Y, BF16, coalesced rows of G^T
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int id = it * kThreads + tid;
+    const int row = id >> 4, seg = id & 15;
+    const f32x4 z0 = *reinterpret_cast<const f32x4*>(zs + row * kZPitch + seg * 8);
+    const f32x4 z1 = *reinterpret_cast<const f32x4*>(zs + row * kZPitch + seg * 8 + 4);
+    const uint32_t yb = (ym[row * 4 + (seg >> 2)] >> ((seg & 3) * 8)) & 0xFFu;
+    float z[8] = {z0[0], z0[1], z0[2], z0[3], z1[0], z1[1], z1[2], z1[3]};
+    float g[8];
+    const bool row_ok = l0 + row < n;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      g[e] = sigmoidf_fast(z[e]) - (float)((yb >> e) & 1u);
+      if (LOSS && row_ok && b0 + seg * 8 + e < B) loss += softplusf_fast(z[e]);
+    }
+    if (row_ok && b0 + seg * 8 < Bp) {
+      uint4 o;
+      o.x = pack2_bf16(g[0], g[1]); o.y = pack2_bf16(g[2], g[3]);
+      o.z = pack2_bf16(g[4], g[5]); o.w = pack2_bf16(g[6], g[7]);
+      *reinterpret_cast<uint4*>(Gt + (size_t)(l0 + row) * Bp + b0 + seg * 8) = o;
+    }
+  }
+  if (LOSS) {
+    const float s = block_sum(loss, red);
+    if (tid == 0) loss_slots[(size_t)(tile0 + lt) * tiles_b + bt] = s;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Input gradient (Algorithm 1: X_gradient += large_k_matmul(logits, W_i)), dX += G W_c with the
+// weights as they are before this step's update.  The contraction runs over the labels; both
+// operands are stored label-major, so fragments come from transposing LDS reads and E4M3
+// weights are widened to BF16 in registers (no up-cast copy of W in memory).
+// Workgroup = 128 samples x 128 embedding columns x one slice s of the chunk's labels; the FP32
+// partial goes to dXacc[s] (owned by exactly this workgroup, so plain read-modify-write).
+// ---------------------------------------------------------------------------------------------
+template <bool FP8>
+__global__ void __launch_bounds__(kThreads, 2)
+k_dx(const char* __restrict__ Gt, const char* __restrict__ Wc, float* __restrict__ dXacc, int n, int d, int Bp,
+     int Bp128, int S) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  constexpr int WROWB = FP8 ? 128 : 256;
+  constexpr int ABYTES = 64 * 256, BBYTES = 64 * WROWB;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
+  const int tiles_b = Bp128 >> 7, tiles_j = d >> 7;
+  const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
+  const int jt = wg % tiles_j, bt = (wg / tiles_j) % tiles_b, s = wg / (tiles_j * tiles_b);
+  const int b0 = bt << 7, j0 = jt << 7;
+  const int ksteps = (n + 63) >> 6, per = (ksteps + S - 1) / S;
+  const int ks0 = s * per, ks1 = min(ks0 + per, ksteps);
+  if (ks0 >= ks1) return;
+
+  TileLoader<64, 256> la;
+  TileLoader<64, WROWB> lb;
+  const size_t strideA = (size_t)Bp * 2, strideB = (size_t)d * (FP8 ? 1 : 2);
+  const char* ga = Gt + (size_t)b0 * 2;
+  const char* gb = Wc + (size_t)j0 * (FP8 ? 1 : 2);
+  const int chunksA = min(16, (Bp - b0) >> 3);           // valid 16-byte chunks of a 128-sample row
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  auto loadA = [&](int ks) {
+    const int rv = n - ks * 64;
+#pragma unroll
+    for (int it = 0; it < la.N; ++it) {
+      const int id = it * kThreads + tid, r = id >> 4, c = id & 15;
+      la.v[it] = (r < rv && c < chunksA) ? *reinterpret_cast<const uint4*>(ga + (size_t)(ks * 64 + r) * strideA + c * 16)
+                                         : make_uint4(0, 0, 0, 0);
+    }
+  };
+  loadA(ks0);
+  lb.load(gb + (size_t)ks0 * 64 * strideB, strideB, n - ks0 * 64, tid);
+  la.store(smem, tid);
+  lb.store(smem + ABYTES, tid);
+  __syncthreads();
+  for (int ks = ks0; ks < ks1; ++ks) {
+    const char* sa = smem + ((ks - ks0) & 1) * (ABYTES + BBYTES);
+    const char* sb = sa + ABYTES;
+    if (ks + 1 < ks1) {
+      loadA(ks + 1);
+      lb.load(gb + (size_t)(ks + 1) * 64 * strideB, strideB, n - (ks + 1) * 64, tid);
+    }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      bf16x8 a[2], b[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) a[i] = frag_tr_bf16<256>(sa, 16 * kk, wm * 64 + 32 * i, lane);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        b[j] = FP8 ? frag_tr_fp8<WROWB>(sb, 16 * kk, wn * 64 + 32 * j, lane)
+                   : frag_tr_bf16<WROWB>(sb, 16 * kk, wn * 64 + 32 * j, lane);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (ks + 1 < ks1) {
+      char* da = smem + ((ks + 1 - ks0) & 1) * (ABYTES + BBYTES);
+      la.store(da, tid);
+      lb.store(da + ABYTES, tid);
+    }
+    __syncthreads();
+  }
+  float* out = dXacc + (size_t)s * Bp128 * d;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int b = b0 + wm * 64 + 32 * i + acc_row(v, lane);
+        const int jj = j0 + wn * 64 + 32 * j + (lane & 31);
+        float* p = out + (size_t)b * d + jj;
+        *p += acc[i][j][v];
+      }
+}
+
+// dX_out = BF16(sum over label slices of the FP32 partials); loss_out = sum of the tile losses.
+__global__ void __launch_bounds__(kThreads) k_finalize(const float* __restrict__ dXacc, int S, int Bp128, int B, int d,
+                                                       uint16_t* __restrict__ dX_out, const float* __restrict__ loss_slots,
+                                                       int nslots, float* __restrict__ loss_out) {
+  __shared__ float red[4];
+  if (dX_out) {
+    const size_t n = (size_t)B * d, plane = (size_t)Bp128 * d;
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (size_t)gridDim.x * kThreads) {
+      float s = 0.0f;
+      for (int k = 0; k < S; ++k) s += dXacc[k * plane + i];
+      dX_out[i] = (uint16_t)bf16_rne(s);
+    }
+  }
+  if (loss_out && blockIdx.x == 0) {
+    float s = 0.0f;
+    for (int i = threadIdx.x; i < nslots; i += kThreads) s += loss_slots[i];
+    const float t = block_sum(s, red);
+    if (threadIdx.x == 0) *loss_out = t;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Fused weight gradient + SGD + (Kahan) + rounding, in place (Algorithm 1, fuse_update).
+// One workgroup owns a 128 (labels) x 128 (columns) tile of W_c: grad = G^T X accumulated in FP32
+// over the whole batch on the BF16 matrix cores, then per element the FP32 update of
+// numerics.h, rounded stochastically (Eq. 1) or to nearest, written back in the storage format.
+// The weight gradient only ever exists as MFMA accumulators and one LDS tile.
+// ---------------------------------------------------------------------------------------------
+constexpr int kGPitch = 132;
+constexpr int kUpdateSmem = 128 * kGPitch * 4;
+static_assert(kUpdateSmem >= 4 * 128 * 128, "main-loop buffers must fit");
+
+template <int FMT, bool SR, bool KAHAN>
+__global__ void __launch_bounds__(kThreads, 2)
+k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restrict__ Wc, uint16_t* __restrict__ Cc,
+         int n, int d, int Bp, float lr, uint64_t seed, uint64_t step, uint64_t elem0) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
+  const int tiles_j = d >> 7;
+  const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
+  const int lt = wg / tiles_j, jt = wg % tiles_j;
+  const int l0 = lt << 7, j0 = jt << 7;
+  const size_t stride = (size_t)Bp * 2;
+  const int nk = Bp >> 6;
+
+  TileLoader<128, 128> la, lb;
+  const char* ga = Gt + (size_t)l0 * stride;
+  const char* gb = XT + (size_t)j0 * stride;
+  const int va = n - l0;
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  la.load(ga, stride, va, tid);
+  lb.load(gb, stride, 128, tid);
+  la.store(smem, tid);
+  lb.store(smem + 16384, tid);
+  __syncthreads();
+  for (int ks = 0; ks < nk; ++ks) {
+    const char* sa = smem + (ks & 1) * 32768;
+    const char* sb = sa + 16384;
+    if (ks + 1 < nk) {
+      la.load(ga + (size_t)(ks + 1) * 128, stride, va, tid);
+      lb.load(gb + (size_t)(ks + 1) * 128, stride, 128, tid);
+    }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      bf16x8 a[2], b[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) a[i] = frag_bf16(sa, wm * 64 + 32 * i, kk, lane);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) b[j] = frag_bf16(sb, wn * 64 + 32 * j, kk, lane);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (ks + 1 < nk) {
+      char* da = smem + ((ks + 1) & 1) * 32768;
+      la.store(da, tid);
+      lb.store(da + 16384, tid);
+    }
+    __syncthreads();
+  }
+
+  // ---- stage the gradient tile [label][column] in LDS
+  float* gs = reinterpret_cast<float*>(smem);
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        gs[(wm * 64 + 32 * i + acc_row(v, lane)) * kGPitch + wn * 64 + 32 * j + (lane & 31)] = acc[i][j][v];
+  __syncthreads();
+
+  // ---- per-element update, 16 consecutive columns per thread and pass
+  constexpr int ESZ = FMT == FMT_E4M3 ? 1 : 2;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int id = it * kThreads + tid;
+    const int row = id >> 3, seg = id & 7;
+    const int l = l0 + row;
+    if (l >= n) continue;
+    const size_t eoff = (size_t)l * d + j0 + seg * 16;          // element offset inside the chunk
+    uint32_t wbits[16], cbits[16];
+    char* wp = Wc + eoff * ESZ;
+    if (FMT == FMT_E4M3) {
+      const uint4 w = *reinterpret_cast<const uint4*>(wp);
+      const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+      for (int e = 0; e < 16; ++e) wbits[e] = (ww[e >> 2] >> ((e & 3) * 8)) & 0xFFu;
+    } else {
+      const uint4 w0 = *reinterpret_cast<const uint4*>(wp);
+      const uint4 w1 = *reinterpret_cast<const uint4*>(wp + 16);
+      const uint32_t ww[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+#pragma unroll
+      for (int e = 0; e < 16; ++e) wbits[e] = (ww[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+    }
+    if (KAHAN) {
+      const uint4 c0 = *reinterpret_cast<const uint4*>(Cc + eoff);
+      const uint4 c1 = *reinterpret_cast<const uint4*>(Cc + eoff + 8);
+      const uint32_t cc[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+#pragma unroll
+      for (int e = 0; e < 16; ++e) cbits[e] = (cc[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+    }
+    float g[16];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const f32x4 t = *reinterpret_cast<const f32x4*>(gs + row * kGPitch + seg * 16 + 4 * q);
+      g[4 * q] = t[0]; g[4 * q + 1] = t[1]; g[4 * q + 2] = t[2]; g[4 * q + 3] = t[3];
+    }
+    U4 rb[2];
+    if (SR) {
+      const uint64_t blk = (elem0 + eoff) >> 3;
+      rb[0] = sr_block(blk, seed, step);
+      rb[1] = sr_block(blk + 1, seed, step);
+    }
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const uint32_t r16 = SR ? sr_field(rb[e >> 3], e & 7) : 0u;
+      update_element<FMT, SR, KAHAN>(wbits[e], cbits[e], g[e], lr, r16);
+    }
+    if (FMT == FMT_E4M3) {
+      uint32_t o[4] = {0, 0, 0, 0};
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[e >> 2] |= wbits[e] << ((e & 3) * 8);
+      *reinterpret_cast<uint4*>(wp) = make_uint4(o[0], o[1], o[2], o[3]);
+    } else {
+      uint32_t o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[e >> 1] |= wbits[e] << ((e & 1) * 16);
+      *reinterpret_cast<uint4*>(wp) = make_uint4(o[0], o[1], o[2], o[3]);
+      *reinterpret_cast<uint4*>(wp + 16) = make_uint4(o[4], o[5], o[6], o[7]);
+    }
+    if (KAHAN) {
+      uint32_t o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[e >> 1] |= cbits[e] << ((e & 1) * 16);
+      *reinterpret_cast<uint4*>(Cc + eoff) = make_uint4(o[0], o[1], o[2], o[3]);
+      *reinterpret_cast<uint4*>(Cc + eoff + 8) = make_uint4(o[4], o[5], o[6], o[7]);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Stand-alone quantiser (round to nearest even or stochastic rounding with the step's fields).
+// ---------------------------------------------------------------------------------------------
+template <int FMT, bool SR>
+__global__ void __launch_bounds__(kThreads) k_quantize(const float* __restrict__ src, int64_t n, uint64_t seed, uint64_t step,
+                                                       uint64_t first, void* __restrict__ dst) {
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kThreads) {
+    const float t = src[i];
+    uint32_t q;
+    if (SR) {
+      const uint64_t e = first + (uint64_t)i;
+      const U4 rb = sr_block(e >> 3, seed, step);
+      q = quant_sr<FMT>(t, sr_field(rb, (int)(e & 7)));
+    } else {
+      q = quant_rne<FMT>(t);
+    }
+    if (FMT == FMT_E4M3) reinterpret_cast<uint8_t*>(dst)[i] = (uint8_t)q;
+    else reinterpret_cast<uint16_t*>(dst)[i] = (uint16_t)q;
+  }
+}
+
+}  // namespace elmo

@@ -1,0 +1,156 @@
+// Device-side number formats, counter-based random fields and rounding for the ELMO head.
+//
+// Everything here is written for gfx950 only.  The rules implemented are the paper's:
+//   * formats: Section 3 "Floating-point formats" (BF16; FP8 E4M3 as used in Algorithm 1,
+//     i.e. the OCP flavour: bias 7, largest finite 448, no infinities);
+//   * stochastic rounding: Section 3, Eq. (1);
+//   * the FP32 update arithmetic and Kahan compensation: Algorithm 1 (fuse_update) and the
+//     three-line recurrence of Section 3.
+// Where the paper is silent the choices are: Philox4x32-10 as the counter-based generator, one
+// 16-bit field per weight element, add-and-truncate on the magnitude, clipping of finite
+// overflow to the largest finite value, sign kept when a value rounds to zero.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace elmo {
+
+enum : int { FMT_BF16 = 0, FMT_E4M3 = 1 };
+
+// ---------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11).  ctr = (c0..c3), key = (k0, k1).
+// ---------------------------------------------------------------------------------------------
+struct U4 { uint32_t x, y, z, w; };
+
+__host__ __device__ inline U4 philox4x32_10(U4 c, uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c.x;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c.z;
+    U4 n;
+    n.x = (uint32_t)(p1 >> 32) ^ c.y ^ k0;
+    n.y = (uint32_t)p1;
+    n.z = (uint32_t)(p0 >> 32) ^ c.w ^ k1;
+    n.w = (uint32_t)p0;
+    c = n;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return c;
+}
+
+// The eight 16-bit rounding fields of the block of elements [8*blk, 8*blk+8).
+// Field f (element 8*blk+f) is bits [16*(f&1), 16*(f&1)+16) of word f>>1.
+__host__ __device__ inline U4 sr_block(uint64_t blk, uint64_t seed, uint64_t step) {
+  U4 c;
+  c.x = (uint32_t)blk;
+  c.y = (uint32_t)(blk >> 32);
+  c.z = (uint32_t)step;
+  c.w = (uint32_t)(step >> 32);
+  return philox4x32_10(c, (uint32_t)seed, (uint32_t)(seed >> 32));
+}
+
+__host__ __device__ inline uint32_t sr_field(const U4& b, int f) {
+  const uint32_t w = (f >> 1) == 0 ? b.x : (f >> 1) == 1 ? b.y : (f >> 1) == 2 ? b.z : b.w;
+  return (f & 1) ? (w >> 16) : (w & 0xFFFFu);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Bit casts and decoding
+// ---------------------------------------------------------------------------------------------
+__device__ inline uint32_t f2u(float f) { return __float_as_uint(f); }
+__device__ inline float u2f(uint32_t u) { return __uint_as_float(u); }
+
+__device__ inline float bf16_decode(uint32_t bits16) { return u2f(bits16 << 16); }
+
+// E4M3 (OCP) byte -> FP32, exact.  gfx950's conversion instruction implements the OCP format.
+__device__ inline float e4m3_decode(uint32_t code) {
+  return __builtin_amdgcn_cvt_f32_fp8((int)code, 0);
+}
+
+// ---------------------------------------------------------------------------------------------
+// FP32 -> BF16.  ADD = 0x7FFF + lsb gives round-to-nearest-even; ADD = r (16-bit field) gives
+// Eq. (1): the 16 dropped bits carry into the kept ones with probability dropped / 2^16.
+// ---------------------------------------------------------------------------------------------
+__device__ inline uint32_t bf16_finish(uint32_t bits, uint32_t mag, uint32_t q) {
+  q = q > 0x7F7Fu ? 0x7F7Fu : q;                 // finite overflow (and inf) clips
+  q = mag > 0x7F800000u ? 0x7FC0u : q;           // NaN stays NaN
+  return ((bits >> 16) & 0x8000u) | q;
+}
+__device__ inline uint32_t bf16_rne(float t) {
+  const uint32_t bits = f2u(t), mag = bits & 0x7FFFFFFFu;
+  const uint32_t q = (mag + 0x7FFFu + ((mag >> 16) & 1u)) >> 16;
+  return bf16_finish(bits, mag, q);
+}
+__device__ inline uint32_t bf16_sr(float t, uint32_t r16) {
+  const uint32_t bits = f2u(t), mag = bits & 0x7FFFFFFFu;
+  return bf16_finish(bits, mag, (mag + r16) >> 16);
+}
+
+// ---------------------------------------------------------------------------------------------
+// FP32 -> E4M3.  From 2^-6 upwards 20 bits of the FP32 magnitude are dropped; below, the grid is
+// uniform with spacing 2^-9 and |t| * 2^9 is rounded as a fixed-point number.
+// ---------------------------------------------------------------------------------------------
+__device__ inline uint32_t e4m3_finish(uint32_t bits, uint32_t mag, uint32_t code) {
+  code = code > 0x7Eu ? 0x7Eu : code;            // clip to 448
+  code = mag > 0x7F800000u ? 0x7Fu : code;       // NaN
+  return ((bits >> 24) & 0x80u) | code;
+}
+__device__ inline uint32_t e4m3_rne(float t) {
+  const uint32_t bits = f2u(t), mag = bits & 0x7FFFFFFFu;
+  uint32_t code;
+  if (mag >= 0x3C800000u) {                      // |t| >= 2^-6
+    code = ((mag + 0x7FFFFu + ((mag >> 20) & 1u)) >> 20) - 960u;
+  } else {
+    code = (uint32_t)__builtin_rintf(u2f(mag) * 512.0f);   // ties to even; 8 = first normal code
+  }
+  return e4m3_finish(bits, mag, code);
+}
+__device__ inline uint32_t e4m3_sr(float t, uint32_t r16) {
+  const uint32_t bits = f2u(t), mag = bits & 0x7FFFFFFFu;
+  uint32_t code;
+  if (mag >= 0x3C800000u) {
+    code = ((mag + (r16 << 4)) >> 20) - 960u;    // 16 most significant dropped bits decide
+  } else {
+    const uint32_t q = (uint32_t)(u2f(mag) * 33554432.0f);   // |t| 2^25, truncated: 16 fraction bits
+    code = (q + r16) >> 16;
+  }
+  return e4m3_finish(bits, mag, code);
+}
+
+template <int FMT> __device__ inline uint32_t quant_rne(float t) {
+  return FMT == FMT_BF16 ? bf16_rne(t) : e4m3_rne(t);
+}
+template <int FMT> __device__ inline uint32_t quant_sr(float t, uint32_t r16) {
+  return FMT == FMT_BF16 ? bf16_sr(t, r16) : e4m3_sr(t, r16);
+}
+template <int FMT> __device__ inline float decode(uint32_t bits) {
+  return FMT == FMT_BF16 ? bf16_decode(bits) : e4m3_decode(bits);
+}
+
+// ---------------------------------------------------------------------------------------------
+// One element of the fused update (Algorithm 1, fuse_update; Kahan recurrence of Section 3 with
+// s = w, v = -lr*g).  Every FP32 operation is rounded once (no fused multiply-add).
+//   plain : t = w - lr*g                    w' = Q(t)
+//   Kahan : y = -(lr*g) - c;  t = w + y     w' = Q(t);  c' = RNE_BF16((w' - w) - y)
+// ---------------------------------------------------------------------------------------------
+template <int FMT, bool SR, bool KAHAN>
+__device__ inline void update_element(uint32_t& wbits, uint32_t& cbits, float g, float lr, uint32_t r16) {
+  const float w = decode<FMT>(wbits);
+  const float u = __fmul_rn(lr, g);
+  float t, y = 0.0f;
+  if (KAHAN) {
+    y = __fsub_rn(-u, bf16_decode(cbits));
+    t = __fadd_rn(w, y);
+  } else {
+    t = __fsub_rn(w, u);
+  }
+  const uint32_t q = SR ? quant_sr<FMT>(t, r16) : quant_rne<FMT>(t);
+  if (KAHAN) {
+    const float wn = decode<FMT>(q);
+    cbits = bf16_rne(__fsub_rn(__fsub_rn(wn, w), y));
+  }
+  wbits = q;
+}
+
+}  // namespace elmo

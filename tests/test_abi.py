@@ -1,0 +1,85 @@
+"""The C-ABI library loads without a GPU, exports every symbol the header declares, plans its
+buffers by the closed forms, and turns bad arguments into error codes (no compute calls here)."""
+import os
+import re
+
+import pytest
+
+from oracle import elmo_oracle as o
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def b():
+    from paper_2510_11168_amd import build
+    if not build.is_built():
+        build.build()
+    from paper_2510_11168_amd import binding
+    return binding
+
+
+def test_every_declared_symbol_is_exported(b):
+    hdr = open(os.path.join(ROOT, "include", "elmo_head.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(elmo_[a-z0-9_]+)\s*\(", hdr))
+    assert declared == set(b.EXPORTS)
+    for name in declared:
+        assert hasattr(b._lib, name)
+
+
+def test_host_philox_matches_published_vectors_and_oracle(b):
+    assert b.elmo_philox4x32_10([0, 0, 0, 0], [0, 0]) == [0x6627E8D5, 0xE169C58D, 0xBC57AC4C, 0x9B00DBD8]
+    assert b.elmo_philox4x32_10([0xFFFFFFFF] * 4, [0xFFFFFFFF] * 2) == [0x408F276D, 0x41C83B0E, 0xA20BC7C6, 0x6D5451FD]
+    ctr, key = [7, 1 << 31, 123456789, 42], [0xDEADBEEF, 0x01234567]
+    assert b.elmo_philox4x32_10(ctr, key) == [int(x) for x in o.philox4x32_10(ctr, key)]
+
+
+def test_logit_buffer_closed_form_reproduces_the_papers_figures(b):
+    """Section 4.4: 3M-label head (2,812,281 labels), batch 128, 16-bit logits: 687 MiB unchunked,
+    86 MiB with 8 chunks."""
+    full = b.elmo_logit_buffer_bytes(128, 2812281)
+    assert full == 128 * 2812281 * 2
+    assert round(full / 2**20) == 687
+    assert round(b.elmo_logit_buffer_bytes(128, -(-2812281 // 8)) / 2**20) == 86
+    # weights: 8 GiB in FP32 -> 4 GiB BF16 / 2 GiB FP8 (Section 4.4 footnote)
+    w16, _, _ = b.elmo_head_sizes(2812281, 768, b.ELMO_BF16, 131072, 128, 4096, 0)
+    w8, c8, _ = b.elmo_head_sizes(2812281, 768, b.ELMO_FP8_E4M3, 131072, 128, 4096, b.ELMO_KAHAN)
+    assert w16 == 2812281 * 768 * 2 and w8 == 2812281 * 768 and c8 == 2812281 * 768 * 2
+    assert round(w16 / 2**30) == 4 and round(w8 / 2**30) == 2
+
+
+def test_workspace_is_one_chunks_buffer_plus_small_terms(b):
+    L, d, B, chunk = 3_000_000, 768, 1024, 131072
+    _, _, ws = b.elmo_head_sizes(L, d, b.ELMO_FP8_E4M3, chunk, B, 16384, b.ELMO_SR)
+    g = b.elmo_logit_buffer_bytes(B, chunk)
+    assert g <= ws <= g + 200 * 2**20          # everything else is O(B d) and O(L / 128)
+    _, _, ws2 = b.elmo_head_sizes(L, d, b.ELMO_FP8_E4M3, 2 * chunk, B, 16384, b.ELMO_SR)
+    assert ws2 - ws == g                        # linear in the chunk size, nothing scales with L * B
+    _, _, ws_small = b.elmo_head_sizes(1000, 256, b.ELMO_BF16, 1 << 20, 64, 512, 0)
+    assert ws_small < 16 * 2**20                # chunk is clipped to the label count
+
+
+@pytest.mark.parametrize("args,code", [
+    ((0, 768, 0, 1024, 8, 8, 0), -1),            # L
+    ((100, 100, 0, 1024, 8, 8, 0), -1),          # d not a multiple of 128
+    ((100, 768, 0, 100, 8, 8, 0), -1),           # chunk not a multiple of 128
+    ((100, 768, 0, 1024, 0, 8, 0), -1),          # max_B
+    ((100, 768, 0, 1024, 8, 0, 0), -1),          # max_nnz
+    ((100, 768, 7, 1024, 8, 8, 0), -2),          # format
+    ((100, 768, 0, 1024, 8, 8, 64), -2),         # flag bits
+])
+def test_bad_plans_are_rejected(b, args, code):
+    with pytest.raises(b.ElmoError) as e:
+        b.elmo_head_sizes(*args)
+    assert e.value.code == code and len(str(e.value)) > 20
+
+
+def test_create_rejects_missing_or_small_buffers(b):
+    with pytest.raises(b.ElmoError) as e:
+        b.elmo_head_create(1000, 256, b.ELMO_BF16, 512, flags=0, max_B=8, max_nnz=64, W=None, comp=None, workspace=None)
+    assert e.value.code == -1 and "W buffer" in str(e.value)
+    with pytest.raises(b.ElmoError):
+        b.elmo_head_destroy(None)
+    with pytest.raises(b.ElmoError):
+        b.elmo_quantize(None, 10, 0, 0, 0, 0, 0, None)

@@ -1,0 +1,431 @@
+"""GPU parity: the HIP path (called through the C ABI) against the CPU oracle on the same seeded
+inputs.  Bars (from the benchmark spec):
+  * quantisation / stochastic-rounding kernels: bit-exact on identical FP32 inputs;
+  * logits-derived quantities and dX: relative Frobenius error <= 2e-2 (BF16) / 6e-2 (FP8);
+  * updated weights: within 1 unit in the last place of the storage format for >= 99.9 % of the
+    elements after one step (same random fields on both sides).
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import elmo_oracle as o
+from paper_2510_11168_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def b():
+    from paper_2510_11168_amd import binding
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return binding
+
+
+def dev(a):
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    return torch.from_numpy(a).to(DEV)
+
+
+def host_u16(t):
+    return t.cpu().numpy().view(np.uint16)
+
+
+def ordered(bits, fmt):
+    """Monotone integer index of a sign-magnitude code: neighbours on the grid differ by 1."""
+    bits = np.asarray(bits).astype(np.int64)
+    if fmt == o.BF16:
+        mag, neg = bits & 0x7FFF, (bits >> 15) & 1
+    else:
+        mag, neg = bits & 0x7F, (bits >> 7) & 1
+    return np.where(neg == 1, -mag, mag)
+
+
+def assert_far_misses_are_tiny(Wn, Wref, dist, fmt, lr):
+    """Beyond the 1-ulp bar: where the two sides differ by more than two grid steps the weight
+    must sit next to zero, where a grid step is far smaller than the update itself.  There the
+    difference is bounded in absolute terms: one BF16 step of one logit-gradient term times |x|
+    (|x| < 1 after L2 normalisation), times lr."""
+    far = dist > 2
+    if np.any(far):
+        diff = np.abs(o.decode(Wn, fmt) - o.decode(Wref, fmt))[far]
+        assert diff.max() <= lr * 2.0**-8, f"largest far miss {diff.max():.3e}"
+
+
+def rel_fro(a, ref):
+    return float(np.linalg.norm(np.asarray(a, np.float64) - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+# --------------------------------------------------------------------------------- quantisers
+def _quant_inputs():
+    rng = np.random.default_rng(11)
+    n = 1 << 21
+    x = (rng.standard_normal(n) * np.exp(rng.uniform(-20, 8, n))).astype(np.float32)
+    # every FP32 exponent with random mantissas, exact grid points, ties, zeros, overflow, inf, NaN
+    exps = np.repeat(np.arange(0, 255, dtype=np.uint32), 64)
+    man = rng.integers(0, 1 << 23, size=exps.size, dtype=np.uint32)
+    sign = rng.integers(0, 2, size=exps.size, dtype=np.uint32)
+    allexp = ((sign << 31) | (exps << 23) | man).view(np.float32)
+    grid = o.decode_e4m3(np.arange(256, dtype=np.uint8))
+    grid = grid[~np.isnan(grid)].astype(np.float32)
+    ties = ((grid[:-1].astype(np.float64) + grid[1:].astype(np.float64)) / 2).astype(np.float32)
+    special = np.array([0.0, -0.0, 448.0, 464.0, 465.0, 1e9, -1e9, np.inf, -np.inf, np.nan, 3.4e38, -3.4e38,
+                        1e-45, -1e-45, 2.0**-10, 3 * 2.0**-10, 2.0**-6, 2.0**-6 - 2.0**-20], dtype=np.float32)
+    return np.concatenate([x, allexp, grid, ties, special])
+
+
+@pytest.mark.parametrize("fmt", [o.BF16, o.E4M3])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_quantize_bit_exact(b, fmt, mode):
+    x = _quant_inputs()
+    n = x.size
+    seed, step, first = 0x1234567890ABCDEF, 0xFEDCBA9876543210, (1 << 40) + 5      # odd offset: all fields
+    say(f"[quantize] fmt={fmt} mode={mode} n={n}")
+    src = torch.from_numpy(x).to(DEV)
+    dst = torch.zeros(n, dtype=torch.int16 if fmt == o.BF16 else torch.uint8, device=DEV)
+    b.elmo_quantize(src, n, fmt, mode, seed, step, first, dst)
+    torch.cuda.synchronize()
+    got = dst.cpu().numpy()
+    got = got.view(np.uint16) if fmt == o.BF16 else got
+    r = o.sr_fields(seed, step, first + np.arange(n, dtype=np.uint64)) if mode else None
+    want = o.quantize(x, fmt, r)
+    bad = np.nonzero(got != want)[0]
+    assert bad.size == 0, f"{bad.size} mismatches, first at {bad[0]}: x={x[bad[0]]!r} got={got[bad[0]]:#x} want={want[bad[0]]:#x}"
+
+
+def test_quantize_empty_is_a_no_op(b):
+    b.elmo_quantize(None, 0, o.BF16, 0, 0, 0, 0, None)
+
+
+# --------------------------------------------------------------------------------- head step
+class Case:
+    """A head on the device initialised from host bits, plus the host copies the oracle needs."""
+
+    def __init__(self, b, L, d, fmt, chunk, flags, B, max_nnz=None, seed=0, w_std=0.02, comp_std=0.0):
+        rng = np.random.default_rng([seed, L, d])
+        self.b, self.L, self.d, self.fmt, self.flags = b, L, d, fmt, flags
+        self.W0 = o.quantize(synth.make_w0_f32(rng, L, d, w_std), fmt)
+        self.C0 = None
+        if flags & o.FLAG_KAHAN:
+            self.C0 = o.round_bf16((rng.standard_normal((L, d)) * comp_std).astype(np.float32))
+        self.head = b.Head(L, d, fmt, chunk, flags, B, max_nnz or 64 * B)
+        self.load(self.W0, self.C0)
+
+    def load(self, W, C):
+        self.head.weights().copy_(dev(W))
+        if C is not None:
+            self.head.compensation().copy_(dev(C))
+
+    def W(self):
+        w = self.head.weights().cpu().numpy()
+        return w.view(np.uint16) if self.fmt == o.BF16 else w
+
+    def C(self):
+        return None if self.head.comp is None else host_u16(self.head.compensation())
+
+    def step(self, X, indptr, indices, lr, seed, step, want_dx=True, want_loss=True):
+        Xd, ip, ix = dev(X), dev(indptr), dev(indices)
+        dX = torch.zeros(X.shape, dtype=torch.int16, device=DEV) if want_dx else None
+        loss = torch.zeros(1, dtype=torch.float32, device=DEV) if want_loss else None
+        self.head.step(Xd, ip, ix, lr, seed, step, dX, loss)
+        torch.cuda.synchronize()
+        return (None if dX is None else o.decode_bf16(host_u16(dX)),
+                None if loss is None else float(loss.item()))
+
+
+def check_step(case, X, indptr, indices, lr, seed, step, tol, W_before=None, C_before=None):
+    """Run one GPU step and compare everything with the oracle fed the same starting bits."""
+    W_before = case.W() if W_before is None else W_before
+    C_before = case.C() if C_before is None else C_before
+    dX, loss = case.step(X, indptr, indices, lr, seed, step)
+    ref = o.head_step(W_before, C_before, X, indptr, indices, lr, seed, step, case.fmt, case.flags)
+    Wn = case.W()
+    dist = np.abs(ordered(Wn, case.fmt) - ordered(ref["W_new"], case.fmt))
+    frac_exact = float(np.mean(dist == 0))
+    frac_1ulp = float(np.mean(dist <= 1))
+    e_dx = rel_fro(dX, ref["dX_partial"])
+    e_loss = abs(loss - ref["loss"]) / abs(ref["loss"])
+    say(f"   W': exact {frac_exact:.5f}, within 1 ulp {frac_1ulp:.6f}, max {dist.max()};  dX rel-Fro {e_dx:.2e};  loss rel {e_loss:.2e}")
+    assert frac_1ulp >= 0.999
+    assert_far_misses_are_tiny(Wn, ref["W_new"], dist, case.fmt, lr)
+    assert e_dx <= tol
+    assert e_loss <= 2e-3
+    if case.flags & o.FLAG_KAHAN:
+        # compensation: compare the value the pair (w', c') represents, w' - c', with the oracle's
+        same = dist == 0
+        cg, cr = o.decode_bf16(case.C()), o.decode_bf16(ref["comp_new"])
+        scale = np.maximum(np.abs(o.decode(ref["W_new"], case.fmt)), 2.0**-9)
+        err = np.abs(cg - cr)[same] / scale[same]
+        say(f"   comp: max |c - c_ref| / |w| on identical w' = {err.max():.2e}")
+        assert np.quantile(err, 0.999) <= 2.0**-8
+    return ref
+
+
+def test_tiny_config_three_steps(b):
+    """BASELINE config 1: L=8192, d=256, B=64, BF16 + SR, chunk 2048, lr 0.05, 3 steps."""
+    cfg = synth.CONFIGS["tiny"]
+    case = Case(b, cfg.L, cfg.d, cfg.fmt, cfg.chunk, cfg.flags, cfg.B)
+    zipf = synth.ZipfLabels(cfg.L, cfg.zipf_s)
+    for step in range(cfg.steps):
+        X, indptr, indices = synth.make_batch(cfg, step, zipf)
+        say(f"[tiny] step {step} nnz={len(indices)}")
+        check_step(case, X, indptr, indices, cfg.lr, 0, step, 2e-2)
+
+
+@pytest.mark.parametrize("fmt,flags,tol", [
+    (o.E4M3, o.FLAG_SR | o.FLAG_KAHAN, 6e-2),
+    (o.E4M3, o.FLAG_SR, 6e-2),
+    (o.E4M3, 0, 6e-2),
+    (o.BF16, o.FLAG_KAHAN, 2e-2),
+    (o.BF16, 0, 2e-2),
+])
+def test_ragged_shapes_all_modes(b, fmt, flags, tol):
+    """Labels and batch that are no multiple of any tile, several chunks with a short last one,
+    non-zero compensation on entry."""
+    L, d, B, chunk = 5 * 128 + 77, 256, 70, 256
+    case = Case(b, L, d, fmt, chunk, flags, B, w_std=0.05, comp_std=2e-4, seed=3)
+    rng = np.random.default_rng(5)
+    X = synth.make_x(rng, B, d)
+    indptr, indices = synth.ZipfLabels(L, 1.0).draw_csr(rng, B, "lognormal5")
+    say(f"[ragged] fmt={fmt} flags={flags} L={L} B={B} chunk={chunk} nnz={len(indices)}")
+    check_step(case, X, indptr, indices, 0.1, 42, 7, tol)
+
+
+def test_same_operand_error_is_at_bf16_roundoff(b):
+    """Sharper than the contract: G is held in BF16 (unit roundoff 2^-9), so dX should agree with
+    the FP64 oracle to a few 1e-3 when both start from the same bits."""
+    L, d, B = 2048, 256, 128
+    case = Case(b, L, d, o.E4M3, 1024, o.FLAG_SR, B, w_std=0.05)
+    rng = np.random.default_rng(8)
+    X = synth.make_x(rng, B, d)
+    indptr, indices = synth.ZipfLabels(L, 1.0).draw_csr(rng, B, "fixed5")
+    say("[same-operand] E4M3 L=2048 d=256 B=128")
+    dX, _ = case.step(X, indptr, indices, 0.05, 1, 1)
+    ref = o.head_step(case.W0, None, X, indptr, indices, 0.05, 1, 1, o.E4M3, o.FLAG_SR)
+    e = rel_fro(dX, ref["dX_partial"])
+    say(f"   dX rel-Fro {e:.2e}")
+    assert e <= 6e-3
+
+
+def test_weights_do_not_depend_on_chunk_and_steps_repeat(b):
+    """Chunk invariance: identical updated weights for any chunk size at fixed (seed, step);
+    same call twice from the same state gives the same bits; another step index does not."""
+    L, d, B = 1000, 256, 96
+    rng = np.random.default_rng(2)
+    X = synth.make_x(rng, B, d)
+    indptr, indices = synth.ZipfLabels(L, 1.0).draw_csr(rng, B, "fixed5")
+    flags = o.FLAG_SR | o.FLAG_KAHAN
+    outs = []
+    for chunk in (128, 384, 1024):
+        case = Case(b, L, d, o.E4M3, chunk, flags, B, w_std=0.05, seed=1)
+        say(f"[chunk-invariance] chunk={chunk}")
+        dX, _ = case.step(X, indptr, indices, 0.05, 9, 4)
+        outs.append((case.W(), case.C(), dX))
+    for W, C, dX in outs[1:]:
+        assert np.array_equal(W, outs[0][0]) and np.array_equal(C, outs[0][1])
+        assert rel_fro(dX, outs[0][2]) < 1e-2
+    case = Case(b, L, d, o.E4M3, 384, flags, B, w_std=0.05, seed=1)
+    case.step(X, indptr, indices, 0.05, 9, 4)
+    assert np.array_equal(case.W(), outs[0][0])
+    case = Case(b, L, d, o.E4M3, 384, flags, B, w_std=0.05, seed=1)
+    case.step(X, indptr, indices, 0.05, 9, 5)
+    assert not np.array_equal(case.W(), outs[0][0])
+
+
+def test_rne_cancels_tiny_updates_bit_identically(b):
+    """Section 4.1: with nearest rounding an update below half a spacing leaves W untouched."""
+    L, d, B = 512, 128, 32
+    case = Case(b, L, d, o.BF16, 256, 0, B, w_std=0.3)
+    rng = np.random.default_rng(4)
+    X = synth.make_x(rng, B, d)
+    indptr, indices = synth.ZipfLabels(L, 1.0).draw_csr(rng, B, "fixed5")
+    say("[rne-cancel]")
+    case.step(X, indptr, indices, 1e-7, 0, 0, want_dx=False, want_loss=False)
+    W = case.W()
+    big = np.abs(o.decode_bf16(case.W0)) > 1e-2
+    assert np.array_equal(W[big], case.W0[big])
+
+
+def test_degenerate_inputs(b):
+    """B = 1, a batch without positives, fewer labels than one tile, zero weights (closed form)."""
+    L, d = 100, 128
+    case = Case(b, L, d, o.BF16, 128, o.FLAG_SR, 4, max_nnz=16)
+    rng = np.random.default_rng(6)
+    X = synth.make_x(rng, 1, d)
+    say("[degenerate] B=1, one positive")
+    check_step(case, X, np.array([0, 1], np.int32), np.array([99], np.int32), 0.05, 0, 0, 2e-2)
+    say("[degenerate] no positives at all")
+    X = synth.make_x(rng, 3, d)
+    check_step(case, X, np.zeros(4, np.int32), np.zeros(0, np.int32), 0.05, 0, 1, 2e-2)
+    say("[degenerate] zero weights: dX = 0, loss = B L ln 2")
+    case.load(np.zeros((L, d), np.uint16), None)
+    dX, loss = case.step(X, np.array([0, 1, 1, 2], np.int32), np.array([5, 7], np.int32), 0.05, 0, 2)
+    assert np.all(dX == 0)
+    assert abs(loss - 3 * L * np.log(2.0)) < 1e-3 * 3 * L
+
+
+def test_validation_flag_reports_bad_labels_on_the_next_call(b):
+    """Bad label ids are caught by the kernels' own bounds checks (nothing faults) and surface
+    as error -4 on the following call."""
+    L, d = 300, 128
+    head = b.Head(L, d, b.ELMO_BF16, 128, b.ELMO_VALIDATE, 4, 16)
+    X = dev(synth.make_x(np.random.default_rng(0), 2, d))
+    say("[validate] out-of-range label id")
+    head.step(X, dev(np.array([0, 1, 2], np.int32)), dev(np.array([5, 300], np.int32)), 0.05, 0, 0)
+    torch.cuda.synchronize()
+    with pytest.raises(b.ElmoError) as e:
+        head.step(X, dev(np.array([0, 1, 2], np.int32)), dev(np.array([5, 6], np.int32)), 0.05, 0, 1)
+    assert e.value.code == -4
+    head.step(X, dev(np.array([0, 1, 2], np.int32)), dev(np.array([5, 6], np.int32)), 0.05, 0, 1)
+    torch.cuda.synchronize()
+    head.step(X, dev(np.array([0, 1, 2], np.int32)), dev(np.array([5, 6], np.int32)), 0.05, 0, 2)
+    torch.cuda.synchronize()
+    with pytest.raises(b.ElmoError) as e:                       # B > max_B is refused on the host
+        b.elmo_head_step(head.h, X, 5, dev(np.array([0, 1], np.int32)), None, 0, 0.05, 0, 0)
+    assert e.value.code == -1
+
+
+# --------------------------------------------------------------------------------- sampled checks at scale
+def _sample_labels(L, chunk, indices, rng, n_random):
+    ids = [np.unique(indices), np.arange(max(0, L - 300), L)]
+    for c0 in range(0, L, chunk):
+        ids.append(np.array([c0, min(L, c0 + chunk) - 1]))
+    ids.append(rng.integers(0, L, size=n_random))
+    return np.unique(np.concatenate(ids).astype(np.int64))
+
+
+def _init_on_device(b, head, cfg, seed=0):
+    """W0 ~ N(0, std) drawn on the device in slices and rounded to the storage format by the
+    library's own nearest-even kernel (whose bit-exactness is tested above)."""
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    W = head.weights()
+    rows = 65536
+    for l0 in range(0, cfg.L, rows):
+        l1 = min(cfg.L, l0 + rows)
+        f = torch.randn((l1 - l0) * cfg.d, device=DEV, generator=g) * cfg.w_std
+        b.elmo_quantize(f, f.numel(), cfg.fmt, 0, 0, 0, 0, W[l0:l1])
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name,dx_rows", [("mid", 8), ("large", 4), ("xl", 2)])
+def test_full_size_configs_on_samples(b, name, dx_rows):
+    """BASELINE configs 2-4 at full size in the launch configuration the benchmark times.
+    Labels are independent given X, so the oracle evaluates a label sample exactly (all in-batch
+    positives, chunk-boundary rows, the ragged tail, random rows) and a few full rows of dX."""
+    cfg = synth.CONFIGS[name]
+    tol = 6e-2 if cfg.fmt == o.E4M3 else 2e-2
+    say(f"[{name}] L={cfg.L} d={cfg.d} B={cfg.B} chunk={cfg.chunk} fmt={cfg.fmt} flags={cfg.flags}: init")
+    head = b.Head(cfg.L, cfg.d, cfg.fmt, cfg.chunk, cfg.flags, cfg.B, 64 * cfg.B)
+    _init_on_device(b, head, cfg)
+    zipf = synth.ZipfLabels(cfg.L, cfg.zipf_s)
+    rng = np.random.default_rng(1)
+    for step in range(2):                     # second step starts from non-zero compensation
+        X, indptr, indices = synth.make_batch(cfg, step, zipf)
+        ids = _sample_labels(cfg.L, cfg.chunk, indices, rng, 2048)
+        idt = torch.from_numpy(ids).to(DEV)
+        Wb = head.weights()[idt].cpu().numpy()
+        Wb = Wb.view(np.uint16) if cfg.fmt == o.BF16 else Wb
+        Cb = host_u16(head.compensation()[idt]) if head.comp is not None else None
+        rows = np.sort(rng.choice(cfg.B, size=dx_rows, replace=False))
+        W_all = None
+        if step == 0:
+            W_all = head.weights().cpu().numpy()
+            W_all = W_all.view(np.uint16) if cfg.fmt == o.BF16 else W_all
+        Xd, ip, ix = dev(X), dev(indptr), dev(indices)
+        dX = torch.zeros(X.shape, dtype=torch.int16, device=DEV)
+        loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+        say(f"[{name}] step {step}: nnz={len(indices)}, {len(ids)} sampled labels, GPU step")
+        head.step(Xd, ip, ix, cfg.lr, 0, step, dX, loss)
+        torch.cuda.synchronize()
+        say(f"[{name}] step {step}: oracle on the label sample")
+        ref = o.head_step(Wb, Cb, X, indptr, indices, cfg.lr, 0, step, cfg.fmt, cfg.flags, label_ids=ids)
+        Wn = head.weights()[idt].cpu().numpy()
+        Wn = Wn.view(np.uint16) if cfg.fmt == o.BF16 else Wn
+        dist = np.abs(ordered(Wn, cfg.fmt) - ordered(ref["W_new"], cfg.fmt))
+        say(f"   W' sample: exact {np.mean(dist == 0):.5f}, within 1 ulp {np.mean(dist <= 1):.6f}, max {dist.max()}")
+        assert np.mean(dist <= 1) >= 0.999
+        assert_far_misses_are_tiny(Wn, ref["W_new"], dist, cfg.fmt, cfg.lr)
+        if Cb is not None:
+            cg = o.decode_bf16(host_u16(head.compensation()[idt]))
+            same = dist == 0
+            scale = np.maximum(np.abs(o.decode(ref["W_new"], cfg.fmt)), 2.0**-9)
+            err = (np.abs(cg - o.decode_bf16(ref["comp_new"])) / scale)[same]
+            assert np.quantile(err, 0.999) <= 2.0**-8
+        if W_all is not None:
+            say(f"[{name}] step {step}: oracle dX for rows {rows.tolist()} over all labels")
+            dX_ref, _ = o.input_gradient_rows(W_all, X, indptr, indices, cfg.fmt, rows)
+            got = o.decode_bf16(host_u16(dX))[rows]
+            e = rel_fro(got, dX_ref)
+            say(f"   dX rows rel-Fro {e:.2e}; loss {loss.item():.6g}")
+            assert e <= tol
+            assert np.isfinite(loss.item()) and loss.item() > 0
+    head.close()
+
+
+# --------------------------------------------------------------------------------- top-k
+def _check_topk(b, head, Wbits, X, k, fmt, tol):
+    B = X.shape[0]
+    idx = torch.zeros((B, k), dtype=torch.int32, device=DEV)
+    sc = torch.zeros((B, k), dtype=torch.float32, device=DEV)
+    head.topk(dev(X), k, idx, sc)
+    torch.cuda.synchronize()
+    idx, sc = idx.cpu().numpy(), sc.cpu().numpy().astype(np.float64)
+    Z = o.logits(Wbits, X, fmt)
+    ref_idx, ref_sc = o.topk(Z, k)
+    exact = float(np.mean(idx == ref_idx))
+    scale = np.abs(ref_sc).max()
+    eps = tol * scale
+    for i in range(B):
+        assert len(set(idx[i].tolist())) == k and idx[i].min() >= 0 and idx[i].max() < Wbits.shape[0]
+        # what is unique: the score multiset (to tolerance); what must be valid: every returned id
+        # scores at least the oracle's k-th value minus eps, and is reported with its own logit
+        assert np.all(Z[i, idx[i]] >= ref_sc[i, -1] - eps)
+        assert np.all(np.abs(sc[i] - Z[i, idx[i]]) <= eps)
+        assert np.all(np.diff(sc[i]) <= 0)
+    say(f"   top-{k}: ids identical to the FP64 order in {exact:.4f} of the slots")
+    return exact
+
+
+@pytest.mark.parametrize("fmt", [o.BF16, o.E4M3])
+def test_topk_small_brute_force(b, fmt):
+    L, d, B = 3000 + 17, 256, 70
+    case = Case(b, L, d, fmt, 1024, 0, B, w_std=0.05, seed=12)
+    X = synth.make_x(np.random.default_rng(1), B, d)
+    for k in (1, 5, 100, 128):
+        say(f"[topk-small] fmt={fmt} k={k}")
+        _check_topk(b, case.head, case.W0, X, k, fmt, 2e-3 if fmt == o.BF16 else 2e-3)
+
+
+def test_topk_ties_prefer_smaller_ids(b):
+    """All-zero weights: every logit ties at 0, so the answer is ids 0..k-1 in order."""
+    L, d, B, k = 1000, 128, 5, 10
+    case = Case(b, L, d, o.BF16, 512, 0, B)
+    case.load(np.zeros((L, d), np.uint16), None)
+    idx = torch.zeros((B, k), dtype=torch.int32, device=DEV)
+    sc = torch.ones((B, k), dtype=torch.float32, device=DEV)
+    say("[topk-ties]")
+    case.head.topk(dev(synth.make_x(np.random.default_rng(0), B, d)), k, idx, sc)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), np.tile(np.arange(k), (B, 1))) and np.all(sc.cpu().numpy() == 0)
+
+
+def test_topk_mid_size(b):
+    cfg = synth.CONFIGS["mid"]
+    head = b.Head(cfg.L, cfg.d, cfg.fmt, cfg.chunk, 0, 64, 64)
+    _init_on_device(b, head, cfg)
+    W = head.weights().cpu().numpy().view(np.uint16)
+    X = synth.make_x(np.random.default_rng(3), 64, cfg.d)
+    say("[topk-mid] L=131072 B=64 k=100")
+    _check_topk(b, head, W, X, 100, cfg.fmt, 2e-3)

@@ -147,6 +147,26 @@ def test_rne_e4m3_roundtrip_ties_and_clipping():
     assert int(o.round_e4m3(f(2.0**-6 - 2.0**-12))) == 0x08
 
 
+def test_bf16_grid_rounds_once_from_fp64():
+    """The BF16 rounding of the FP64 logit gradient: equals the FP32 route wherever FP32 holds the
+    value exactly, and does not double-round where it does not."""
+    x32 = _spread_f32(1 << 18, -30, 1, 7)
+    np.testing.assert_array_equal(o.bf16_grid_f64(x32.astype(np.float64)), o.decode_bf16(o.round_bf16(x32)))
+    assert o.bf16_grid_f64(1.0 + 2.0**-8) == 1.0                       # tie -> even
+    assert o.bf16_grid_f64(1.0 + 2.0**-8 + 2.0**-40) == 1.0 + 2.0**-7  # just above the tie
+    assert o.bf16_grid_f64(-0.3) == -0.30078125 and o.bf16_grid_f64(0.0) == 0.0
+    from fractions import Fraction
+    rng = np.random.default_rng(0)
+    for x in rng.uniform(-1, 1, 200):
+        e = np.frexp(x)[1] - 1
+        ulp = Fraction(2) ** int(e - 7)
+        q = Fraction(float(x)) / ulp
+        lo = q.numerator // q.denominator
+        r = q - lo
+        n = lo + (1 if (r > Fraction(1, 2) or (r == Fraction(1, 2) and lo % 2 == 1)) else 0)
+        assert Fraction(float(o.bf16_grid_f64(x))) == n * ulp
+
+
 # ----------------------------------------------------------------------------- SR, Eq. (1)
 def _grid(fmt):
     if fmt == o.E4M3:

@@ -50,6 +50,9 @@ def test_step_against_explicit_loops(fmt):
             z = sum(Xq[i, j] * W[l, j] for j in range(d))
             Z[i, l] = z
             G[i, l] = 1.0 / (1.0 + math.exp(-z)) - Y[i, l]
+    G_exact = G.copy()
+    # the logit gradient is held in BF16 (Section 4.4); the independent route is torch's cast
+    G = torch.from_numpy(G).to(torch.bfloat16).to(torch.float64).numpy()
     for i in range(B):
         for j in range(d):
             dX[i, j] = sum(G[i, l] * W[l, j] for l in range(L))
@@ -58,7 +61,10 @@ def test_step_against_explicit_loops(fmt):
             dW[l, j] = sum(G[i, l] * X[i, j] for i in range(B))      # BF16 inputs, no 1/B
     out = o.head_step(W_bits, None, X_bits, indptr, indices, 0.05, 0, 0, fmt, 0)
     np.testing.assert_allclose(out["Z"], Z, rtol=0, atol=1e-13)
-    np.testing.assert_allclose(out["G"], G, rtol=0, atol=1e-13)
+    np.testing.assert_array_equal(out["G"], G)
+    exact = o.head_step(W_bits, None, X_bits, indptr, indices, 0.05, 0, 0, fmt, 0, g_exact=True)
+    np.testing.assert_allclose(exact["G"], G_exact, rtol=0, atol=1e-13)
+    assert 0 < np.abs(exact["G"] - out["G"]).max() <= 2.0**-9      # one BF16 rounding apart
     np.testing.assert_allclose(out["dX_partial"], dX, rtol=0, atol=1e-12)
     np.testing.assert_allclose(out["dW"], dW, rtol=0, atol=1e-12)
     if fmt == o.E4M3:   # the two kinds of input really differ, so the test can tell them apart
@@ -89,7 +95,7 @@ def test_gradients_are_derivatives_of_the_summed_bce_loss():
     Wd = o.decode_bf16(W_bits)
     X = o.decode_bf16(X_bits)
     Y = o.csr_to_dense(indptr, indices, 12)
-    out = o.head_step(W_bits, None, X_bits, indptr, indices, 0.05, 0, 0, o.BF16, 0)
+    out = o.head_step(W_bits, None, X_bits, indptr, indices, 0.05, 0, 0, o.BF16, 0, g_exact=True)
     loss = lambda Xv, Wv: o.bce_loss(Xv @ Wv.T, Y)
     assert abs(loss(X, Wd) - out["loss"]) < 1e-12
     h = 1e-6
