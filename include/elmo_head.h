@@ -99,6 +99,15 @@ int elmo_head_topk(elmo_head_t* h, const void* X, int32_t B, int32_t k, int32_t*
 
 int elmo_head_destroy(elmo_head_t* h);
 
+/* Measurement hooks.  elmo_head_profile(h, 1) makes every later step / top-k call record a HIP
+ * event on its stream at each boundary between kernel classes; elmo_head_profile(h, 0) stops.
+ * elmo_head_profile_read waits for the last recorded event, then returns per class the summed
+ * event-to-event time in milliseconds and the number of spans, and clears the record.  Classes:
+ * 0 step set-up, 1 logits + epilogue, 2 input gradient, 3 fused update, 4 finalise, 5 top-k.
+ * ms and launches are HOST arrays of 6 entries. */
+int elmo_head_profile(elmo_head_t* h, int enable);
+int elmo_head_profile_read(elmo_head_t* h, double ms[6], int64_t launches[6]);
+
 /* Text of the last error on the calling thread; never NULL. */
 const char* elmo_last_error(void);
 

@@ -60,6 +60,10 @@ _lib.elmo_head_topk.restype = C.c_int
 _lib.elmo_head_topk.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.elmo_head_destroy.restype = C.c_int
 _lib.elmo_head_destroy.argtypes = [C.c_void_p]
+_lib.elmo_head_profile.restype = C.c_int
+_lib.elmo_head_profile.argtypes = [C.c_void_p, C.c_int]
+_lib.elmo_head_profile_read.restype = C.c_int
+_lib.elmo_head_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
 _lib.elmo_quantize.restype = C.c_int
 _lib.elmo_quantize.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_uint64, C.c_uint64, C.c_uint64,
                                C.c_void_p, C.c_void_p]
@@ -67,7 +71,8 @@ _lib.elmo_philox4x32_10.restype = None
 _lib.elmo_philox4x32_10.argtypes = [C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
 
 EXPORTS = ("elmo_last_error", "elmo_logit_buffer_bytes", "elmo_head_sizes", "elmo_head_create",
-           "elmo_head_step", "elmo_head_topk", "elmo_head_destroy", "elmo_quantize", "elmo_philox4x32_10")
+           "elmo_head_step", "elmo_head_topk", "elmo_head_destroy", "elmo_quantize", "elmo_philox4x32_10",
+           "elmo_head_profile", "elmo_head_profile_read")
 
 
 def _check(rc: int) -> None:
@@ -125,6 +130,21 @@ def elmo_head_topk(h, X, B, k, idx_out=None, score_out=None, stream=None) -> Non
 
 def elmo_head_destroy(h) -> None:
     _check(_lib.elmo_head_destroy(h))
+
+
+PROFILE_CLASSES = ("setup", "logits", "dx", "update", "finalize", "topk")
+
+
+def elmo_head_profile(h, enable: bool) -> None:
+    _check(_lib.elmo_head_profile(h, int(enable)))
+
+
+def elmo_head_profile_read(h):
+    """{class: (milliseconds, spans)} accumulated since profiling was enabled / last read."""
+    ms = (C.c_double * 6)()
+    n = (C.c_int64 * 6)()
+    _check(_lib.elmo_head_profile_read(h, ms, n))
+    return {name: (ms[i], n[i]) for i, name in enumerate(PROFILE_CLASSES)}
 
 
 def elmo_quantize(src, n, dtype, mode, seed, step, first_elem, dst, stream=None) -> None:

@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "kernels.h"
 #include "topk.h"
@@ -86,10 +87,33 @@ int check_launch(const char* what) {
 
 }  // namespace
 
+// Optional per-kernel-class timing: one event at every boundary between kernel classes of a
+// step; a span is charged to the class launched after its first event.
+enum { CLS_SETUP = 0, CLS_LOGITS, CLS_DX, CLS_UPDATE, CLS_FINAL, CLS_TOPK, CLS_END, CLS_COUNT = CLS_END };
+struct Profiler {
+  bool on = false;
+  std::vector<hipEvent_t> ev;
+  std::vector<int> cls;       // class of the span that starts at ev[i]; CLS_END closes a call
+  size_t used = 0;
+  void mark(hipStream_t st, int c) {
+    if (!on) return;
+    if (used == ev.size()) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) { on = false; return; }
+      ev.push_back(e);
+      cls.push_back(c);
+    }
+    cls[used] = c;
+    if (hipEventRecord(ev[used], st) != hipSuccess) { on = false; return; }
+    ++used;
+  }
+};
+
 struct elmo_head {
   Plan p;
   char* W; char* comp; char* ws;
   bool validated_step_pending;
+  Profiler prof;
 };
 
 extern "C" {
@@ -136,7 +160,31 @@ int elmo_head_create(int64_t L, int32_t d, int weight_dtype, int64_t chunk, cons
 
 int elmo_head_destroy(elmo_head_t* h) {
   if (!h) return fail(-1, "NULL head");
+  for (hipEvent_t e : h->prof.ev) (void)hipEventDestroy(e);
   delete h;
+  return 0;
+}
+
+int elmo_head_profile(elmo_head_t* h, int enable) {
+  if (!h) return fail(-1, "NULL head");
+  h->prof.on = enable != 0;
+  h->prof.used = 0;
+  return 0;
+}
+
+int elmo_head_profile_read(elmo_head_t* h, double ms[6], int64_t launches[6]) {
+  if (!h || !ms || !launches) return fail(-1, "NULL argument");
+  Profiler& pr = h->prof;
+  for (int i = 0; i < CLS_COUNT; ++i) { ms[i] = 0.0; launches[i] = 0; }
+  if (pr.used) ELMO_HIP(hipEventSynchronize(pr.ev[pr.used - 1]));
+  for (size_t i = 0; i + 1 < pr.used; ++i) {
+    if (pr.cls[i] == CLS_END) continue;
+    float t = 0.0f;
+    ELMO_HIP(hipEventElapsedTime(&t, pr.ev[i], pr.ev[i + 1]));
+    ms[pr.cls[i]] += t;
+    launches[pr.cls[i]] += 1;
+  }
+  pr.used = 0;
   return 0;
 }
 
@@ -254,6 +302,8 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
   S = std::min(S, p.dx_rows / Bp128);
   S = std::max(1, std::min(S, 64));
 
+  Profiler& prof = h->prof;
+  prof.mark(st, CLS_SETUP);
   // ---- step set-up: inputs, zeroed partial sums, label index
   {
     const size_t n = (size_t)Bp * d;
@@ -289,6 +339,7 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
     char* Wc = h->W + (size_t)c0 * d * esz;
     uint16_t* Cc = h->comp ? (uint16_t*)h->comp + (size_t)c0 * d : nullptr;
     const int tile0 = (int)(c0 / 128);
+    prof.mark(st, CLS_LOGITS);
     {
       const int grid = tiles_l * tiles_b;
       if (fp8) {
@@ -301,12 +352,14 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
       if (int rc = check_launch("k_logits")) return rc;
     }
     if (dX_out) {
+      prof.mark(st, CLS_DX);
       const int grid = tiles_b * tiles_j * S;
       const int smem = 2 * (64 * 256 + 64 * (fp8 ? 128 : 256));
       if (fp8) elmo::k_dx<true><<<grid, elmo::kThreads, smem, st>>>((const char*)Gt, Wc, dXacc, n, d, Bp, Bp128, S);
       else elmo::k_dx<false><<<grid, elmo::kThreads, smem, st>>>((const char*)Gt, Wc, dXacc, n, d, Bp, Bp128, S);
       if (int rc = check_launch("k_dx")) return rc;
     }
+    prof.mark(st, CLS_UPDATE);
     {
       const int grid = tiles_l * tiles_j;
       const bool sr = p.flags & ELMO_SR, kahan = p.flags & ELMO_KAHAN;
@@ -317,6 +370,7 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
     }
   }
 
+  prof.mark(st, CLS_FINAL);
   if (dX_out || loss_out) {
     const size_t n = (size_t)B * d;
     const int grid = dX_out ? (int)std::min<size_t>((n + 255) / 256, 4096) : 1;
@@ -324,6 +378,7 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
                                                      p.ntiles * tiles_b, loss_out);
     if (int rc = check_launch("k_finalize")) return rc;
   }
+  prof.mark(st, CLS_END);
   return 0;
 }
 
@@ -348,6 +403,9 @@ extern "C" int elmo_head_topk(elmo_head_t* h, const void* X, int32_t B, int32_t 
   }
   const char* Xa = fp8 ? (const char*)Xq : (const char*)X;
   const int a_rows = fp8 ? Bp : B;
-  return elmo::topk_run(st, fp8, Xa, a_rows, h->W, p.L, d, p.chunk, B, Bp, k, h->ws + p.off_topk, idx_out, score_out, g_err,
-                        sizeof g_err);
+  h->prof.mark(st, CLS_TOPK);
+  const int rc = elmo::topk_run(st, fp8, Xa, a_rows, h->W, p.L, d, p.chunk, B, Bp, k, h->ws + p.off_topk, idx_out, score_out, g_err,
+                                sizeof g_err);
+  h->prof.mark(st, CLS_END);
+  return rc;
 }
