@@ -300,8 +300,8 @@ k_dx(const char* __restrict__ Gt, const char* __restrict__ Wc, float* __restrict
 #pragma unroll
     for (int it = 0; it < la.N; ++it) {
       const int id = it * kThreads + tid, r = id >> 4, c = id & 15;
-      la.v[it] = (r < rv && c < chunksA) ? *reinterpret_cast<const uint4*>(ga + (size_t)(ks * 64 + r) * strideA + c * 16)
-                                         : make_uint4(0, 0, 0, 0);
+      la.v[it] = (r < rv && c < chunksA) ? *reinterpret_cast<const u32x4*>(ga + (size_t)(ks * 64 + r) * strideA + c * 16)
+                                         : u32x4{0u, 0u, 0u, 0u};
     }
   };
   loadA(ks0);
@@ -384,11 +384,63 @@ constexpr int kGPitch = 132;
 constexpr int kUpdateSmem = 128 * kGPitch * 4;
 static_assert(kUpdateSmem >= 4 * 128 * 128, "main-loop buffers must fit");
 
+// Sixteen consecutive elements of one weight row: storage bits in, storage bits out.
+// E4M3: w[0..3] hold 4 codes each; BF16: w[0..7] hold 2 patterns each.  c[0..7]: BF16 compensation.
+template <int FMT, bool SR, bool KAHAN>
+__device__ inline void update16(uint32_t (&w)[8], uint32_t (&c)[8], const float (&g)[16], float lr, const U4 (&rb)[2]) {
+  const uint32_t rw[8] = {rb[0].x, rb[0].y, rb[0].z, rb[0].w, rb[1].x, rb[1].y, rb[1].z, rb[1].w};
+  if (FMT == FMT_E4M3) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      uint32_t out = 0u;
+      float cn[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int i = 4 * q + e;
+        const float wv = e4m3_decode_byte(w[q], e);
+        const float u = __fmul_rn(lr, g[i]);
+        float t, y = 0.0f;
+        if (KAHAN) {
+          const float cv = u2f((i & 1) ? (c[i >> 1] & 0xFFFF0000u) : (c[i >> 1] << 16));
+          y = __fsub_rn(-u, cv);
+          t = __fadd_rn(wv, y);
+        } else {
+          t = __fsub_rn(wv, u);
+        }
+        if (SR) {
+          const uint32_t rnd = (i & 1) ? (rw[i >> 1] & 0xFFFF0000u) : (rw[i >> 1] << 16);
+          out = e4m3_sr_pack(t, rnd, out, e);
+        } else {
+          out |= e4m3_rne(t) << (8 * e);
+        }
+        if (KAHAN) cn[e] = __fsub_rn(__fsub_rn(e4m3_decode_byte(out, e), wv), y);
+      }
+      w[q] = out;
+      if (KAHAN) {
+        c[2 * q] = pack2_bf16(cn[0], cn[1]);       // hardware round-to-nearest-even
+        c[2 * q + 1] = pack2_bf16(cn[2], cn[3]);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      uint32_t wb = (w[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
+      uint32_t cb = KAHAN ? (c[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu : 0u;
+      const uint32_t r16 = SR ? ((rw[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu) : 0u;
+      update_element<FMT, SR, KAHAN>(wb, cb, g[i], lr, r16);
+      w[i >> 1] = (i & 1) ? (w[i >> 1] & 0x0000FFFFu) | (wb << 16) : (w[i >> 1] & 0xFFFF0000u) | wb;
+      if (KAHAN) c[i >> 1] = (i & 1) ? (c[i >> 1] & 0x0000FFFFu) | (cb << 16) : (c[i >> 1] & 0xFFFF0000u) | cb;
+    }
+  }
+}
+
 template <int FMT, bool SR, bool KAHAN>
 __global__ void __launch_bounds__(kThreads, 2)
 k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restrict__ Wc, uint16_t* __restrict__ Cc,
          int n, int d, int Bp, float lr, uint64_t seed, uint64_t step, uint64_t elem0) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
+  constexpr int ESZ = FMT == FMT_E4M3 ? 1 : 2;
+  constexpr int WQ = FMT == FMT_E4M3 ? 1 : 2;       // 16-byte loads per 16 weights
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
   const int tiles_j = d >> 7;
   const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
@@ -396,11 +448,28 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
   const int l0 = lt << 7, j0 = jt << 7;
   const size_t stride = (size_t)Bp * 2;
   const int nk = Bp >> 6;
+  const int va = n - l0;
 
-  TileLoader<128, 128> la, lb;
+  // This thread's share of the weight (and compensation) tile, fetched before the product so the
+  // read-modify-write never waits on memory: 4 passes x 16 consecutive columns of one row.
+  const int urow = tid >> 3, useg = tid & 7;
+  u32x4 wreg[4][WQ];
+  u32x4 creg[4][2];
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int l = min(l0 + it * 32 + urow, n - 1);
+    const size_t eoff = (size_t)l * d + j0 + useg * 16;
+#pragma unroll
+    for (int q = 0; q < WQ; ++q) wreg[it][q] = *reinterpret_cast<const u32x4*>(Wc + eoff * ESZ + 16 * q);
+    if (KAHAN) {
+      creg[it][0] = *reinterpret_cast<const u32x4*>(Cc + eoff);
+      creg[it][1] = *reinterpret_cast<const u32x4*>(Cc + eoff + 8);
+    }
+  }
+
+  TileLoader<128, 128> la0, la1, lb0, lb1;
   const char* ga = Gt + (size_t)l0 * stride;
   const char* gb = XT + (size_t)j0 * stride;
-  const int va = n - l0;
   f32x16 acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -409,18 +478,7 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  la.load(ga, stride, va, tid);
-  lb.load(gb, stride, 128, tid);
-  la.store(smem, tid);
-  lb.store(smem + 16384, tid);
-  __syncthreads();
-  for (int ks = 0; ks < nk; ++ks) {
-    const char* sa = smem + (ks & 1) * 32768;
-    const char* sb = sa + 16384;
-    if (ks + 1 < nk) {
-      la.load(ga + (size_t)(ks + 1) * 128, stride, va, tid);
-      lb.load(gb + (size_t)(ks + 1) * 128, stride, 128, tid);
-    }
+  auto mma = [&](const char* sa, const char* sb) {
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       bf16x8 a[2], b[2];
@@ -434,13 +492,39 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
         for (int j = 0; j < 2; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
-    if (ks + 1 < nk) {
-      char* da = smem + ((ks + 1) & 1) * 32768;
-      la.store(da, tid);
-      lb.store(da + 16384, tid);
-    }
-    __syncthreads();
+  };
+  // K loop over the batch, slabs of 64 samples; global loads run two slabs ahead of the MFMAs
+  // (two register sets, selected by literal index so they stay in registers), LDS is double
+  // buffered, one barrier per slab.
+#define ELMO_UPDATE_STAGE(KS, ST, LD)                                          \
+  {                                                                            \
+    if ((KS) + 2 < nk) {                                                       \
+      la##LD.load_clamped(ga + (size_t)((KS) + 2) * 128, stride, va, tid);     \
+      lb##LD.load_clamped(gb + (size_t)((KS) + 2) * 128, stride, 128, tid);    \
+    }                                                                          \
+    const char* sa_ = smem + ((KS) & 1) * 32768;                               \
+    mma(sa_, sa_ + 16384);                                                     \
+    if ((KS) + 1 < nk) {                                                       \
+      char* da_ = smem + (((KS) + 1) & 1) * 32768;                             \
+      la##ST.store(da_, tid);                                                  \
+      lb##ST.store(da_ + 16384, tid);                                          \
+    }                                                                          \
+    __syncthreads();                                                           \
   }
+  la0.load_clamped(ga, stride, va, tid);
+  lb0.load_clamped(gb, stride, 128, tid);
+  if (nk > 1) {
+    la1.load_clamped(ga + 128, stride, va, tid);
+    lb1.load_clamped(gb + 128, stride, 128, tid);
+  }
+  la0.store(smem, tid);
+  lb0.store(smem + 16384, tid);
+  __syncthreads();
+  for (int ks = 0; ks < nk; ks += 2) {
+    ELMO_UPDATE_STAGE(ks, 1, 0)
+    if (ks + 1 < nk) ELMO_UPDATE_STAGE(ks + 1, 0, 1)
+  }
+#undef ELMO_UPDATE_STAGE
 
   // ---- stage the gradient tile [label][column] in LDS
   float* gs = reinterpret_cast<float*>(smem);
@@ -453,40 +537,24 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
         gs[(wm * 64 + 32 * i + acc_row(v, lane)) * kGPitch + wn * 64 + 32 * j + (lane & 31)] = acc[i][j][v];
   __syncthreads();
 
-  // ---- per-element update, 16 consecutive columns per thread and pass
-  constexpr int ESZ = FMT == FMT_E4M3 ? 1 : 2;
+  // ---- per-element update
 #pragma unroll
   for (int it = 0; it < 4; ++it) {
-    const int id = it * kThreads + tid;
-    const int row = id >> 3, seg = id & 7;
+    const int row = it * 32 + urow;
     const int l = l0 + row;
     if (l >= n) continue;
-    const size_t eoff = (size_t)l * d + j0 + seg * 16;          // element offset inside the chunk
-    uint32_t wbits[16], cbits[16];
-    char* wp = Wc + eoff * ESZ;
-    if (FMT == FMT_E4M3) {
-      const uint4 w = *reinterpret_cast<const uint4*>(wp);
-      const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+    const size_t eoff = (size_t)l * d + j0 + useg * 16;
+    uint32_t w[8], c[8];
 #pragma unroll
-      for (int e = 0; e < 16; ++e) wbits[e] = (ww[e >> 2] >> ((e & 3) * 8)) & 0xFFu;
-    } else {
-      const uint4 w0 = *reinterpret_cast<const uint4*>(wp);
-      const uint4 w1 = *reinterpret_cast<const uint4*>(wp + 16);
-      const uint32_t ww[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
-#pragma unroll
-      for (int e = 0; e < 16; ++e) wbits[e] = (ww[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-    }
-    if (KAHAN) {
-      const uint4 c0 = *reinterpret_cast<const uint4*>(Cc + eoff);
-      const uint4 c1 = *reinterpret_cast<const uint4*>(Cc + eoff + 8);
-      const uint32_t cc[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
-#pragma unroll
-      for (int e = 0; e < 16; ++e) cbits[e] = (cc[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+    for (int q = 0; q < 4; ++q) {
+      w[q] = wreg[it][0][q];
+      if (WQ == 2) w[4 + q] = wreg[it][WQ - 1][q];
+      if (KAHAN) { c[q] = creg[it][0][q]; c[4 + q] = creg[it][1][q]; }
     }
     float g[16];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const f32x4 t = *reinterpret_cast<const f32x4*>(gs + row * kGPitch + seg * 16 + 4 * q);
+      const f32x4 t = *reinterpret_cast<const f32x4*>(gs + row * kGPitch + useg * 16 + 4 * q);
       g[4 * q] = t[0]; g[4 * q + 1] = t[1]; g[4 * q + 2] = t[2]; g[4 * q + 3] = t[3];
     }
     U4 rb[2];
@@ -495,29 +563,13 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
       rb[0] = sr_block(blk, seed, step);
       rb[1] = sr_block(blk + 1, seed, step);
     }
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const uint32_t r16 = SR ? sr_field(rb[e >> 3], e & 7) : 0u;
-      update_element<FMT, SR, KAHAN>(wbits[e], cbits[e], g[e], lr, r16);
-    }
-    if (FMT == FMT_E4M3) {
-      uint32_t o[4] = {0, 0, 0, 0};
-#pragma unroll
-      for (int e = 0; e < 16; ++e) o[e >> 2] |= wbits[e] << ((e & 3) * 8);
-      *reinterpret_cast<uint4*>(wp) = make_uint4(o[0], o[1], o[2], o[3]);
-    } else {
-      uint32_t o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-      for (int e = 0; e < 16; ++e) o[e >> 1] |= wbits[e] << ((e & 1) * 16);
-      *reinterpret_cast<uint4*>(wp) = make_uint4(o[0], o[1], o[2], o[3]);
-      *reinterpret_cast<uint4*>(wp + 16) = make_uint4(o[4], o[5], o[6], o[7]);
-    }
+    update16<FMT, SR, KAHAN>(w, c, g, lr, rb);
+    char* wp = Wc + eoff * ESZ;
+    *reinterpret_cast<u32x4*>(wp) = u32x4{w[0], w[1], w[2], w[3]};
+    if (WQ == 2) *reinterpret_cast<u32x4*>(wp + 16) = u32x4{w[4], w[5], w[6], w[7]};
     if (KAHAN) {
-      uint32_t o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-      for (int e = 0; e < 16; ++e) o[e >> 1] |= cbits[e] << ((e & 1) * 16);
-      *reinterpret_cast<uint4*>(Cc + eoff) = make_uint4(o[0], o[1], o[2], o[3]);
-      *reinterpret_cast<uint4*>(Cc + eoff + 8) = make_uint4(o[4], o[5], o[6], o[7]);
+      *reinterpret_cast<u32x4*>(Cc + eoff) = u32x4{c[0], c[1], c[2], c[3]};
+      *reinterpret_cast<u32x4*>(Cc + eoff + 8) = u32x4{c[4], c[5], c[6], c[7]};
     }
   }
 }

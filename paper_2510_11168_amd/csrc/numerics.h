@@ -106,16 +106,35 @@ __device__ inline uint32_t e4m3_rne(float t) {
   }
   return e4m3_finish(bits, mag, code);
 }
-__device__ inline uint32_t e4m3_sr(float t, uint32_t r16) {
-  const uint32_t bits = f2u(t), mag = bits & 0x7FFFFFFFu;
-  uint32_t code;
-  if (mag >= 0x3C800000u) {
-    code = ((mag + (r16 << 4)) >> 20) - 960u;    // 16 most significant dropped bits decide
-  } else {
-    const uint32_t q = (uint32_t)(u2f(mag) * 33554432.0f);   // |t| 2^25, truncated: 16 fraction bits
-    code = (q + r16) >> 16;
+// Stochastic rounding to E4M3 on gfx950's conversion unit.  v_cvt_sr_fp8_f32 adds the top bits of
+// its 32-bit random operand to the dropped bits of the magnitude and truncates; with the 16-bit
+// field in the upper half of that operand this is the add-and-truncate rule above (the 16 most
+// significant dropped bits decide), in the subnormal range too.  The instruction turns finite
+// overflow into NaN, so the clipping to +-448 is done first; NaN is passed through unclipped.
+// `old`/`byte` select the destination byte of a packed result (the other bytes are kept).
+__device__ inline uint32_t e4m3_sr_pack(float t, uint32_t rand_hi16, uint32_t old, int byte) {
+  float tc = __builtin_amdgcn_fmed3f(t, -448.0f, 448.0f);
+  tc = (t != t) ? t : tc;
+  switch (byte) {
+    case 0: return (uint32_t)__builtin_amdgcn_cvt_sr_fp8_f32(tc, rand_hi16, (int)old, 0);
+    case 1: return (uint32_t)__builtin_amdgcn_cvt_sr_fp8_f32(tc, rand_hi16, (int)old, 1);
+    case 2: return (uint32_t)__builtin_amdgcn_cvt_sr_fp8_f32(tc, rand_hi16, (int)old, 2);
+    default: return (uint32_t)__builtin_amdgcn_cvt_sr_fp8_f32(tc, rand_hi16, (int)old, 3);
   }
-  return e4m3_finish(bits, mag, code);
+}
+// (for a NaN input the instruction returns a NaN code whose sign bit need not be the input's)
+__device__ inline uint32_t e4m3_sr(float t, uint32_t r16) {
+  const uint32_t q = e4m3_sr_pack(t, r16 << 16, 0u, 0) & 0xFFu;
+  return (t != t) ? (((f2u(t) >> 24) & 0x80u) | 0x7Fu) : q;
+}
+
+__device__ inline float e4m3_decode_byte(uint32_t packed, int byte) {
+  switch (byte) {
+    case 0: return __builtin_amdgcn_cvt_f32_fp8((int)packed, 0);
+    case 1: return __builtin_amdgcn_cvt_f32_fp8((int)packed, 1);
+    case 2: return __builtin_amdgcn_cvt_f32_fp8((int)packed, 2);
+    default: return __builtin_amdgcn_cvt_f32_fp8((int)packed, 3);
+  }
 }
 
 template <int FMT> __device__ inline uint32_t quant_rne(float t) {

@@ -18,6 +18,7 @@ typedef int i32x2 __attribute__((ext_vector_type(2)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
@@ -43,14 +44,24 @@ template <int ROWS, int ROWB> struct TileLoader {
   static constexpr int CPR = ROWB / 16;
   static constexpr int N = ROWS * CPR / kThreads;
   static_assert(ROWS * CPR % kThreads == 0, "tile must split evenly over the workgroup");
-  uint4 v[N];
+  u32x4 v[N];   // native vectors: plain loads/stores the optimiser keeps in registers
   __device__ inline void load(const char* __restrict__ g, size_t stride, int rows_valid, int tid) {
 #pragma unroll
     for (int it = 0; it < N; ++it) {
       const int id = it * kThreads + tid;
       const int r = id / CPR, c = id % CPR;
-      if (r < rows_valid) v[it] = *reinterpret_cast<const uint4*>(g + (size_t)r * stride + c * 16);
-      else v[it] = make_uint4(0, 0, 0, 0);
+      if (r < rows_valid) v[it] = *reinterpret_cast<const u32x4*>(g + (size_t)r * stride + c * 16);
+      else v[it] = u32x4{0u, 0u, 0u, 0u};
+    }
+  }
+  // Branch-free variant: rows at or beyond rows_valid (>= 1) re-read the last valid row.  For
+  // operands whose out-of-range rows only feed outputs that are masked later.
+  __device__ inline void load_clamped(const char* __restrict__ g, size_t stride, int rows_valid, int tid) {
+#pragma unroll
+    for (int it = 0; it < N; ++it) {
+      const int id = it * kThreads + tid;
+      const int r = min(id / CPR, rows_valid - 1), c = id % CPR;
+      v[it] = *reinterpret_cast<const u32x4*>(g + (size_t)r * stride + c * 16);
     }
   }
   __device__ inline void store(char* lds, int tid) const {
@@ -58,7 +69,7 @@ template <int ROWS, int ROWB> struct TileLoader {
     for (int it = 0; it < N; ++it) {
       const int id = it * kThreads + tid;
       const int r = id / CPR, c = id % CPR;
-      *reinterpret_cast<uint4*>(lds + tile_off<ROWB>(r, c)) = v[it];
+      *reinterpret_cast<u32x4*>(lds + tile_off<ROWB>(r, c)) = v[it];
     }
   }
 };
