@@ -56,15 +56,16 @@ int make_plan(int64_t L, int d, int fmt, int64_t chunk, int maxB, int64_t max_nn
   if (flags & ~(uint32_t)(ELMO_SR | ELMO_KAHAN | ELMO_VALIDATE)) return fail(-2, "unknown flag bits 0x%x", flags);
   p.L = L; p.d = d; p.fmt = fmt; p.chunk = chunk; p.maxB = maxB; p.max_nnz = max_nnz; p.flags = flags;
   p.Bp_max = round_up(maxB, 64);
-  p.tiles_b_max = (p.Bp_max + 127) / 128;
+  p.tiles_b_max = (p.Bp_max + 255) / 256;      // 256-sample tiles of the matrix products
   p.ntiles = (int)((L + 127) / 128);
   const int tiles_j = d / 128;
-  p.dx_rows = std::min(65536 / tiles_j + 128 * p.tiles_b_max + 128, 64 * 128 * p.tiles_b_max);
+  // slices x padded batch of the input-gradient partials: about one workgroup per CU
+  p.dx_rows = std::min(65536 / tiles_j + 256 * p.tiles_b_max + 256, 64 * 256 * p.tiles_b_max);
   const int64_t chunk_eff = std::min<int64_t>(chunk, (L + 127) / 128 * 128);
   size_t o = 0;
   p.off_xq = o;  o += align256(fmt == ELMO_FP8_E4M3 ? (size_t)p.Bp_max * d : 0);
   p.off_xt = o;  o += align256((size_t)d * p.Bp_max * 2);
-  p.off_g = o;   o += align256((size_t)chunk_eff * p.Bp_max * 2);
+  p.off_g = o;   o += align256((size_t)chunk_eff * p.Bp_max * 2 + 4096);   // + slack: the last rows are read 512 bytes wide
   p.off_dx = o;  o += align256((size_t)p.dx_rows * d * 4);
   p.off_loss = o; o += align256((size_t)p.ntiles * p.tiles_b_max * 4);
   p.off_cnt = o; o += align256((size_t)(p.ntiles + 1) * 4);
@@ -228,7 +229,7 @@ int poll_validation(elmo_head* h) {
 template <bool FP8, bool LOSS>
 void launch_logits(hipStream_t st, int grid, const char* Xa, int a_rows, const char* Wc, int n, int d, int Bp, int B,
                    uint16_t* Gt, const int* binptr, const int2* pos, int tile0, float* loss_slots) {
-  elmo::k_logits<FP8, LOSS><<<grid, elmo::kThreads, elmo::kLogitsSmem, st>>>(Xa, a_rows, Wc, n, d, Bp, B, Gt, binptr, pos,
+  elmo::k_logits<FP8, LOSS><<<grid, elmo::kGemmThreads, elmo::kNtRingBytes, st>>>(Xa, a_rows, Wc, n, d, Bp, B, Gt, binptr, pos,
                                                                              tile0, loss_slots);
 }
 
@@ -236,7 +237,7 @@ template <int FMT>
 void launch_update(hipStream_t st, int grid, bool sr, bool kahan, const char* Gt, const char* XT, char* Wc, uint16_t* Cc,
                    int n, int d, int Bp, float lr, uint64_t seed, uint64_t step, uint64_t elem0) {
 #define ELMO_UPD(SR_, KA_) \
-  elmo::k_update<FMT, SR_, KA_><<<grid, elmo::kThreads, elmo::kUpdateSmem, st>>>(Gt, XT, Wc, Cc, n, d, Bp, lr, seed, step, elem0)
+  elmo::k_update<FMT, SR_, KA_><<<grid, elmo::kGemmThreads, elmo::kNtRingBytes, st>>>(Gt, XT, Wc, Cc, n, d, Bp, lr, seed, step, elem0)
   if (sr && kahan) ELMO_UPD(true, true);
   else if (sr) ELMO_UPD(true, false);
   else if (kahan) ELMO_UPD(false, true);
@@ -249,18 +250,20 @@ int raise_lds_limits() {
   static bool done = false;
   if (done) return 0;
 #define ELMO_ATTR(k, bytes) ELMO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))
-  ELMO_ATTR((elmo::k_logits<true, true>), elmo::kLogitsSmem);
-  ELMO_ATTR((elmo::k_logits<true, false>), elmo::kLogitsSmem);
-  ELMO_ATTR((elmo::k_logits<false, true>), elmo::kLogitsSmem);
-  ELMO_ATTR((elmo::k_logits<false, false>), elmo::kLogitsSmem);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, true, true>), elmo::kUpdateSmem);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, true, false>), elmo::kUpdateSmem);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, false, true>), elmo::kUpdateSmem);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, false, false>), elmo::kUpdateSmem);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, true, true>), elmo::kUpdateSmem);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, true, false>), elmo::kUpdateSmem);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, false, true>), elmo::kUpdateSmem);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, false, false>), elmo::kUpdateSmem);
+  ELMO_ATTR((elmo::k_logits<true, true>), elmo::kNtRingBytes);
+  ELMO_ATTR((elmo::k_logits<true, false>), elmo::kNtRingBytes);
+  ELMO_ATTR((elmo::k_logits<false, true>), elmo::kNtRingBytes);
+  ELMO_ATTR((elmo::k_logits<false, false>), elmo::kNtRingBytes);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, true, true>), elmo::kNtRingBytes);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, true, false>), elmo::kNtRingBytes);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, false, true>), elmo::kNtRingBytes);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, false, false>), elmo::kNtRingBytes);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, true, true>), elmo::kNtRingBytes);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, true, false>), elmo::kNtRingBytes);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, false, true>), elmo::kNtRingBytes);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, false, false>), elmo::kNtRingBytes);
+  ELMO_ATTR((elmo::k_dx<true>), elmo::dx_smem_bytes<true>());
+  ELMO_ATTR((elmo::k_dx<false>), elmo::dx_smem_bytes<false>());
   ELMO_ATTR((elmo::k_topk_chunk<true>), elmo::kTopkSmem);
   ELMO_ATTR((elmo::k_topk_chunk<false>), elmo::kTopkSmem);
 #undef ELMO_ATTR
@@ -283,8 +286,8 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
   if (int rc = raise_lds_limits()) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
   const bool fp8 = p.fmt == ELMO_FP8_E4M3;
-  const int d = p.d, Bp = round_up(B, 64), Bp128 = round_up(Bp, 128);
-  const int tiles_b = Bp128 / 128, tiles_j = d / 128;
+  const int d = p.d, Bp = round_up(B, 64), Bp256 = round_up(Bp, 256);
+  const int tiles_b = Bp256 / 256, tiles_j = d / 128;
 
   uint8_t* Xq = fp8 ? (uint8_t*)(h->ws + p.off_xq) : nullptr;
   uint16_t* XT = (uint16_t*)(h->ws + p.off_xt);
@@ -297,9 +300,10 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
   int2* pos = (int2*)(h->ws + p.off_pos);
   int* flag = (p.flags & ELMO_VALIDATE) ? (int*)(h->ws + p.off_flag) : nullptr;
 
-  // label slices of the input-gradient product: enough workgroups to fill 256 CUs twice over
-  int S = std::max(1, (512 + tiles_b * tiles_j - 1) / (tiles_b * tiles_j));
-  S = std::min(S, p.dx_rows / Bp128);
+  // label slices of the input-gradient product: at most one 512-thread workgroup per CU, so the
+  // whole grid is resident at once (256 CUs) and no second, nearly empty round of workgroups runs
+  int S = std::max(1, 256 / (tiles_b * tiles_j));
+  S = std::min(S, p.dx_rows / Bp256);
   S = std::max(1, std::min(S, 64));
 
   Profiler& prof = h->prof;
@@ -310,7 +314,7 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
     elmo::k_prep_x<<<(int)std::min<size_t>((n + 255) / 256, 4096), elmo::kThreads, 0, st>>>((const uint16_t*)X, B, Bp, d, Xq, XT);
     if (int rc = check_launch("k_prep_x")) return rc;
     if (dX_out) {
-      const size_t w = (size_t)S * Bp128 * d;
+      const size_t w = (size_t)S * Bp256 * d;
       elmo::k_fill_u32<<<(int)std::min<size_t>((w + 255) / 256, 4096), elmo::kThreads, 0, st>>>((uint32_t*)dXacc, w, 0u);
       if (int rc = check_launch("k_fill_u32")) return rc;
     }
@@ -335,7 +339,7 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
   const int a_rows = fp8 ? Bp : B;
   for (int64_t c0 = 0; c0 < p.L; c0 += p.chunk) {
     const int n = (int)std::min<int64_t>(p.chunk, p.L - c0);
-    const int tiles_l = (n + 127) / 128;
+    const int tiles_l = (n + 127) / 128, tiles_l256 = (n + 255) / 256;
     char* Wc = h->W + (size_t)c0 * d * esz;
     uint16_t* Cc = h->comp ? (uint16_t*)h->comp + (size_t)c0 * d : nullptr;
     const int tile0 = (int)(c0 / 128);
@@ -354,14 +358,13 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
     if (dX_out) {
       prof.mark(st, CLS_DX);
       const int grid = tiles_b * tiles_j * S;
-      const int smem = 2 * (64 * 256 + 64 * (fp8 ? 128 : 256));
-      if (fp8) elmo::k_dx<true><<<grid, elmo::kThreads, smem, st>>>((const char*)Gt, Wc, dXacc, n, d, Bp, Bp128, S);
-      else elmo::k_dx<false><<<grid, elmo::kThreads, smem, st>>>((const char*)Gt, Wc, dXacc, n, d, Bp, Bp128, S);
+      if (fp8) elmo::k_dx<true><<<grid, elmo::kGemmThreads, elmo::dx_smem_bytes<true>(), st>>>((const char*)Gt, Wc, dXacc, n, d, Bp, Bp256, S);
+      else elmo::k_dx<false><<<grid, elmo::kGemmThreads, elmo::dx_smem_bytes<false>(), st>>>((const char*)Gt, Wc, dXacc, n, d, Bp, Bp256, S);
       if (int rc = check_launch("k_dx")) return rc;
     }
     prof.mark(st, CLS_UPDATE);
     {
-      const int grid = tiles_l * tiles_j;
+      const int grid = tiles_l256 * tiles_j;
       const bool sr = p.flags & ELMO_SR, kahan = p.flags & ELMO_KAHAN;
       const uint64_t elem0 = (uint64_t)c0 * (uint64_t)d;
       if (fp8) launch_update<elmo::FMT_E4M3>(st, grid, sr, kahan, (const char*)Gt, (const char*)XT, Wc, Cc, n, d, Bp, lr, seed, step, elem0);
@@ -374,7 +377,7 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
   if (dX_out || loss_out) {
     const size_t n = (size_t)B * d;
     const int grid = dX_out ? (int)std::min<size_t>((n + 255) / 256, 4096) : 1;
-    elmo::k_finalize<<<grid, elmo::kThreads, 0, st>>>(dXacc, S, Bp128, B, d, (uint16_t*)dX_out, loss_slots,
+    elmo::k_finalize<<<grid, elmo::kThreads, 0, st>>>(dXacc, S, Bp256, B, d, (uint16_t*)dX_out, loss_slots,
                                                      p.ntiles * tiles_b, loss_out);
     if (int rc = check_launch("k_finalize")) return rc;
   }

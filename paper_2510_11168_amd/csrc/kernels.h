@@ -19,13 +19,16 @@ __device__ inline uint32_t pack2_bf16(float a, float b) {   // hardware round-to
 __device__ inline float sigmoidf_fast(float z) { return __frcp_rn(1.0f + __expf(-z)); }
 __device__ inline float softplusf_fast(float z) { return fmaxf(z, 0.0f) + __logf(1.0f + __expf(-fabsf(z))); }
 
-__device__ inline float block_sum(float v, float* red /*>= 4 floats of LDS*/) {
+template <int NW> __device__ inline float block_sum(float v, float* red /*>= NW floats of LDS*/) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   if (lane == 0) red[w] = v;
   __syncthreads();
-  return red[0] + red[1] + red[2] + red[3];
+  float s = 0.0f;
+#pragma unroll
+  for (int i = 0; i < NW; ++i) s += red[i];
+  return s;
 }
 
 __global__ void __launch_bounds__(kThreads) k_fill_u32(uint32_t* __restrict__ p, size_t n, uint32_t v) {
@@ -108,95 +111,92 @@ __global__ void __launch_bounds__(kThreads) k_label_scatter(const int* __restric
 }
 
 // ---------------------------------------------------------------------------------------------
-// Logits + fused epilogue (Algorithm 1: matmul_fp8, sigmoid_, "-= 1" at the positives).
-// One workgroup computes a 128 (samples) x 128 (labels) tile of Z = Xq W_c^T with FP32
-// accumulation over the full embedding width, then G = sigmoid(Z) - Y, and stores G^T[l][b] as
-// BF16 (labels x batch, the layout the paper's logits buffer has).  Z never reaches memory.
-// FP8: both operands E4M3, v_mfma_f32_32x32x64_f8f6f4.  BF16: v_mfma_f32_32x32x16_bf16.
+// The three matrix products share one shape: 512-thread workgroups (8 waves as 4 x 2, each wave a
+// 64 x 64 block of 32x32 MFMA tiles) computing a 256 x 128 output tile, operands streamed by
+// asynchronous global->LDS loads through a 3-stage ring (tiles.h).  One workgroup per CU: the tile
+// is sized so that the traffic between L2 and LDS per flop is half that of a 128 x 128 tile, which
+// is what bounded the first version of these kernels.
 // ---------------------------------------------------------------------------------------------
-constexpr int kZPitch = 132;                                   // floats per staged row
-constexpr int kLogitsSmem = 128 * kZPitch * 4 + 128 * 4 * 4 + 16;   // stage + positives mask + reduce
-static_assert(kLogitsSmem >= 4 * 128 * 128, "main-loop buffers must fit the epilogue's LDS");
+constexpr int kGemmThreads = 512;
+constexpr int kGemmWaves = 8;
+constexpr int kStages = 3;
+constexpr int kNtRingBytes = kStages * (256 + 128) * 128;        // K-contiguous operands, 128-byte slabs
 
-template <bool FP8, bool LOSS>
-__global__ void __launch_bounds__(kThreads, 2)
-k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, int n, int d, int Bp, int B,
-         uint16_t* __restrict__ Gt, const int* __restrict__ binptr, const int2* __restrict__ pos, int tile0,
-         float* __restrict__ loss_slots) {
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
-  const int tiles_b = (Bp + 127) >> 7;
-  const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
-  const int lt = wg / tiles_b, bt = wg % tiles_b;
-  const int b0 = bt << 7, l0 = lt << 7;
-  const size_t rowb = (size_t)d * (FP8 ? 1 : 2);
-  const int nk = (int)(rowb >> 7);
-
-  TileLoader<128, 128> la, lb;
-  const char* ga = Xa + (size_t)b0 * rowb;
-  const char* gb = Wc + (size_t)l0 * rowb;
-  const int va = a_rows - b0, vb = n - l0;
-  f32x16 acc[2][2];
+__device__ inline void zero_acc(f32x16 (&acc)[2][2]) {
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+}
 
-  la.load(ga, rowb, va, tid);
-  lb.load(gb, rowb, vb, tid);
-  la.store(smem, tid);
-  lb.store(smem + 16384, tid);
-  __syncthreads();
-  for (int ks = 0; ks < nk; ++ks) {
-    const char* sa = smem + (ks & 1) * 32768;
-    const char* sb = sa + 16384;
-    if (ks + 1 < nk) {
-      la.load(ga + (size_t)(ks + 1) * 128, rowb, va, tid);
-      lb.load(gb + (size_t)(ks + 1) * 128, rowb, vb, tid);
-    }
-    if (FP8) {
+// ---------------------------------------------------------------------------------------------
+// Logits + fused epilogue (Algorithm 1: matmul_fp8, sigmoid_, "-= 1" at the positives).
+// One workgroup computes a 256 (samples) x 128 (labels) tile of Z = Xq W_c^T with FP32
+// accumulation over the full embedding width, then G = sigmoid(Z) - Y, and stores G^T[l][b] as
+// BF16 (labels x batch, the layout the paper's logits buffer has).  Z never reaches memory.
+// FP8: both operands E4M3, v_mfma_f32_32x32x64_f8f6f4.  BF16: v_mfma_f32_32x32x16_bf16.
+// Rows of G^T between n and the end of the last 128-label tile are written as zeros (the input
+// gradient product reads whole 64-label slabs).
+// ---------------------------------------------------------------------------------------------
+constexpr int kZPitch = 260;                                         // floats per staged row (256 + 4)
+constexpr int kLogitsSmem = 128 * kZPitch * 4 + 128 * 8 * 4 + 32;    // Z^T stage + positives mask + reduce
+static_assert(kLogitsSmem <= kNtRingBytes, "epilogue reuses the ring memory");
+
+template <bool FP8, bool LOSS>
+__global__ void __launch_bounds__(kGemmThreads, 1)
+k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, int n, int d, int Bp, int B,
+         uint16_t* __restrict__ Gt, const int* __restrict__ binptr, const int2* __restrict__ pos, int tile0,
+         float* __restrict__ loss_slots) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
+  const int tiles_b = (Bp + 255) >> 8;
+  const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
+  const int lt = wg / tiles_b, bt = wg % tiles_b;
+  const int b0 = bt << 8, l0 = lt << 7;
+  const size_t rowb = (size_t)d * (FP8 ? 1 : 2);
+
+  f32x16 acc[2][2];
+  zero_acc(acc);
+  ring_pipeline<256, 128, 128, 128, kStages, kGemmWaves>(
+      Xa + (size_t)b0 * rowb, rowb, a_rows - b0, 0, 128, Wc + (size_t)l0 * rowb, rowb, n - l0, 0, 128, (int)(rowb >> 7), smem,
+      wave, lane, [&](const char* sa, const char* sb) {
+        if (FP8) {
 #pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-        i32x8 a[2], b[2];
+          for (int kk = 0; kk < 2; ++kk) {
+            i32x8 a[2], b[2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) a[i] = frag_fp8(sa, wm * 64 + 32 * i, kk, lane);
+            for (int i = 0; i < 2; ++i) a[i] = frag_fp8(sa, wm * 64 + 32 * i, kk, lane);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) b[j] = frag_fp8(sb, wn * 64 + 32 * j, kk, lane);
+            for (int j = 0; j < 2; ++j) b[j] = frag_fp8(sb, wn * 64 + 32 * j, kk, lane);
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < 2; ++i)
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 0, 0, 0, 0, 0, 0);
-      }
-    } else {
+              for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 0, 0, 0, 0, 0, 0);
+          }
+        } else {
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        bf16x8 a[2], b[2];
+          for (int kk = 0; kk < 4; ++kk) {
+            bf16x8 a[2], b[2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) a[i] = frag_bf16(sa, wm * 64 + 32 * i, kk, lane);
+            for (int i = 0; i < 2; ++i) a[i] = frag_bf16(sa, wm * 64 + 32 * i, kk, lane);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) b[j] = frag_bf16(sb, wn * 64 + 32 * j, kk, lane);
+            for (int j = 0; j < 2; ++j) b[j] = frag_bf16(sb, wn * 64 + 32 * j, kk, lane);
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < 2; ++i)
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-      }
-    }
-    if (ks + 1 < nk) {
-      char* da = smem + ((ks + 1) & 1) * 32768;
-      la.store(da, tid);
-      lb.store(da + 16384, tid);
-    }
-    __syncthreads();
-  }
+              for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+          }
+        }
+      });
 
   // ---- epilogue: stage Z^T (labels x samples) in LDS as FP32
   float* zs = reinterpret_cast<float*>(smem);
   uint32_t* ym = reinterpret_cast<uint32_t*>(smem + 128 * kZPitch * 4);
-  float* red = reinterpret_cast<float*>(smem + 128 * kZPitch * 4 + 128 * 4 * 4);
+  float* red = reinterpret_cast<float*>(smem + 128 * kZPitch * 4 + 128 * 8 * 4);
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -209,7 +209,7 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
         z[0] = acc[i][j][4 * q]; z[1] = acc[i][j][4 * q + 1]; z[2] = acc[i][j][4 * q + 2]; z[3] = acc[i][j][4 * q + 3];
         *reinterpret_cast<f32x4*>(zs + l * kZPitch + b) = z;
       }
-  for (int i = tid; i < 128 * 4; i += kThreads) ym[i] = 0u;
+  for (int i = tid; i < 128 * 8; i += kGemmThreads) ym[i] = 0u;
   __syncthreads();
 
   // ---- positives of this label tile that fall into this batch tile
@@ -217,11 +217,11 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
   {
     const int gt = tile0 + lt;
     const int p0 = binptr[gt], p1 = binptr[gt + 1];
-    for (int p = p0 + tid; p < p1; p += kThreads) {
+    for (int p = p0 + tid; p < p1; p += kGemmThreads) {
       const int2 e = pos[p];
       const int lr_ = e.x - (gt << 7), br = e.y - b0;
-      if (br >= 0 && br < 128 && lr_ >= 0 && lr_ < 128) {
-        atomicOr(&ym[lr_ * 4 + (br >> 5)], 1u << (br & 31));
+      if (br >= 0 && br < 256 && lr_ >= 0 && lr_ < 128) {
+        atomicOr(&ym[lr_ * 8 + (br >> 5)], 1u << (br & 31));
         if (LOSS) loss -= zs[lr_ * kZPitch + br];
       }
     }
@@ -231,28 +231,28 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
   // ---- G = sigmoid(Z) - Y, BF16, coalesced rows of G^T
 #pragma unroll
   for (int it = 0; it < 8; ++it) {
-    const int id = it * kThreads + tid;
-    const int row = id >> 4, seg = id & 15;
+    const int id = it * kGemmThreads + tid;
+    const int row = id >> 5, seg = id & 31;
     const f32x4 z0 = *reinterpret_cast<const f32x4*>(zs + row * kZPitch + seg * 8);
     const f32x4 z1 = *reinterpret_cast<const f32x4*>(zs + row * kZPitch + seg * 8 + 4);
-    const uint32_t yb = (ym[row * 4 + (seg >> 2)] >> ((seg & 3) * 8)) & 0xFFu;
-    float z[8] = {z0[0], z0[1], z0[2], z0[3], z1[0], z1[1], z1[2], z1[3]};
+    const uint32_t yb = (ym[row * 8 + (seg >> 2)] >> ((seg & 3) * 8)) & 0xFFu;
+    const float z[8] = {z0[0], z0[1], z0[2], z0[3], z1[0], z1[1], z1[2], z1[3]};
     float g[8];
     const bool row_ok = l0 + row < n;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      g[e] = sigmoidf_fast(z[e]) - (float)((yb >> e) & 1u);
+      g[e] = row_ok ? sigmoidf_fast(z[e]) - (float)((yb >> e) & 1u) : 0.0f;
       if (LOSS && row_ok && b0 + seg * 8 + e < B) loss += softplusf_fast(z[e]);
     }
-    if (row_ok && b0 + seg * 8 < Bp) {
-      uint4 o;
-      o.x = pack2_bf16(g[0], g[1]); o.y = pack2_bf16(g[2], g[3]);
-      o.z = pack2_bf16(g[4], g[5]); o.w = pack2_bf16(g[6], g[7]);
-      *reinterpret_cast<uint4*>(Gt + (size_t)(l0 + row) * Bp + b0 + seg * 8) = o;
+    if (b0 + seg * 8 < Bp) {
+      u32x4 o;
+      o[0] = pack2_bf16(g[0], g[1]); o[1] = pack2_bf16(g[2], g[3]);
+      o[2] = pack2_bf16(g[4], g[5]); o[3] = pack2_bf16(g[6], g[7]);
+      *reinterpret_cast<u32x4*>(Gt + (size_t)(l0 + row) * Bp + b0 + seg * 8) = o;
     }
   }
   if (LOSS) {
-    const float s = block_sum(loss, red);
+    const float s = block_sum<kGemmWaves>(loss, red);
     if (tid == 0) loss_slots[(size_t)(tile0 + lt) * tiles_b + bt] = s;
   }
 }
@@ -262,83 +262,52 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
 // weights as they are before this step's update.  The contraction runs over the labels; both
 // operands are stored label-major, so fragments come from transposing LDS reads and E4M3
 // weights are widened to BF16 in registers (no up-cast copy of W in memory).
-// Workgroup = 128 samples x 128 embedding columns x one slice s of the chunk's labels; the FP32
+// Workgroup = 256 samples x 128 embedding columns x one slice s of the chunk's labels; the FP32
 // partial goes to dXacc[s] (owned by exactly this workgroup, so plain read-modify-write).
+// Label rows beyond n inside the last 64-label slab are harmless: G^T holds zeros there and the
+// weight rows are re-reads of row n-1.
 // ---------------------------------------------------------------------------------------------
+template <bool FP8> constexpr int dx_smem_bytes() { return kStages * (64 * 512 + 64 * (FP8 ? 128 : 256)); }
+
 template <bool FP8>
-__global__ void __launch_bounds__(kThreads, 2)
+__global__ void __launch_bounds__(kGemmThreads, 1)
 k_dx(const char* __restrict__ Gt, const char* __restrict__ Wc, float* __restrict__ dXacc, int n, int d, int Bp,
-     int Bp128, int S) {
+     int Bp256, int S) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int WROWB = FP8 ? 128 : 256;
-  constexpr int ABYTES = 64 * 256, BBYTES = 64 * WROWB;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
-  const int tiles_b = Bp128 >> 7, tiles_j = d >> 7;
+  const int tiles_b = Bp256 >> 8, tiles_j = d >> 7;
   const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
   const int jt = wg % tiles_j, bt = (wg / tiles_j) % tiles_b, s = wg / (tiles_j * tiles_b);
-  const int b0 = bt << 7, j0 = jt << 7;
+  const int b0 = bt << 8, j0 = jt << 7;
   const int ksteps = (n + 63) >> 6, per = (ksteps + S - 1) / S;
   const int ks0 = s * per, ks1 = min(ks0 + per, ksteps);
   if (ks0 >= ks1) return;
-
-  TileLoader<64, 256> la;
-  TileLoader<64, WROWB> lb;
   const size_t strideA = (size_t)Bp * 2, strideB = (size_t)d * (FP8 ? 1 : 2);
-  const char* ga = Gt + (size_t)b0 * 2;
-  const char* gb = Wc + (size_t)j0 * (FP8 ? 1 : 2);
-  const int chunksA = min(16, (Bp - b0) >> 3);           // valid 16-byte chunks of a 128-sample row
-  f32x16 acc[2][2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  auto loadA = [&](int ks) {
-    const int rv = n - ks * 64;
+  f32x16 acc[2][2];
+  zero_acc(acc);
+  ring_pipeline<64, 512, 64, WROWB, kStages, kGemmWaves>(
+      Gt + (size_t)ks0 * 64 * strideA + (size_t)b0 * 2, strideA, (ksteps - ks0) * 64 /* zero rows past n are real */, 64, 64 * strideA,
+      Wc + (size_t)ks0 * 64 * strideB + (size_t)j0 * (FP8 ? 1 : 2), strideB, n - ks0 * 64, 64, 64 * strideB, ks1 - ks0, smem, wave,
+      lane, [&](const char* sa, const char* sb) {
 #pragma unroll
-    for (int it = 0; it < la.N; ++it) {
-      const int id = it * kThreads + tid, r = id >> 4, c = id & 15;
-      la.v[it] = (r < rv && c < chunksA) ? *reinterpret_cast<const u32x4*>(ga + (size_t)(ks * 64 + r) * strideA + c * 16)
-                                         : u32x4{0u, 0u, 0u, 0u};
-    }
-  };
-  loadA(ks0);
-  lb.load(gb + (size_t)ks0 * 64 * strideB, strideB, n - ks0 * 64, tid);
-  la.store(smem, tid);
-  lb.store(smem + ABYTES, tid);
-  __syncthreads();
-  for (int ks = ks0; ks < ks1; ++ks) {
-    const char* sa = smem + ((ks - ks0) & 1) * (ABYTES + BBYTES);
-    const char* sb = sa + ABYTES;
-    if (ks + 1 < ks1) {
-      loadA(ks + 1);
-      lb.load(gb + (size_t)(ks + 1) * 64 * strideB, strideB, n - (ks + 1) * 64, tid);
-    }
+        for (int kk = 0; kk < 4; ++kk) {
+          bf16x8 a[2], b[2];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 a[2], b[2];
+          for (int i = 0; i < 2; ++i) a[i] = frag_tr_bf16<512>(sa, 16 * kk, wm * 64 + 32 * i, lane);
 #pragma unroll
-      for (int i = 0; i < 2; ++i) a[i] = frag_tr_bf16<256>(sa, 16 * kk, wm * 64 + 32 * i, lane);
+          for (int j = 0; j < 2; ++j)
+            b[j] = FP8 ? frag_tr_fp8<WROWB>(sb, 16 * kk, wn * 64 + 32 * j, lane)
+                       : frag_tr_bf16<WROWB>(sb, 16 * kk, wn * 64 + 32 * j, lane);
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
-        b[j] = FP8 ? frag_tr_fp8<WROWB>(sb, 16 * kk, wn * 64 + 32 * j, lane)
-                   : frag_tr_bf16<WROWB>(sb, 16 * kk, wn * 64 + 32 * j, lane);
+          for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
-    if (ks + 1 < ks1) {
-      char* da = smem + ((ks + 1 - ks0) & 1) * (ABYTES + BBYTES);
-      la.store(da, tid);
-      lb.store(da + ABYTES, tid);
-    }
-    __syncthreads();
-  }
-  float* out = dXacc + (size_t)s * Bp128 * d;
+            for (int j = 0; j < 2; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+      });
+  float* out = dXacc + (size_t)s * Bp256 * d;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -353,12 +322,12 @@ k_dx(const char* __restrict__ Gt, const char* __restrict__ Wc, float* __restrict
 }
 
 // dX_out = BF16(sum over label slices of the FP32 partials); loss_out = sum of the tile losses.
-__global__ void __launch_bounds__(kThreads) k_finalize(const float* __restrict__ dXacc, int S, int Bp128, int B, int d,
+__global__ void __launch_bounds__(kThreads) k_finalize(const float* __restrict__ dXacc, int S, int Bp256, int B, int d,
                                                        uint16_t* __restrict__ dX_out, const float* __restrict__ loss_slots,
                                                        int nslots, float* __restrict__ loss_out) {
   __shared__ float red[4];
   if (dX_out) {
-    const size_t n = (size_t)B * d, plane = (size_t)Bp128 * d;
+    const size_t n = (size_t)B * d, plane = (size_t)Bp256 * d;
     for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (size_t)gridDim.x * kThreads) {
       float s = 0.0f;
       for (int k = 0; k < S; ++k) s += dXacc[k * plane + i];
@@ -368,21 +337,21 @@ __global__ void __launch_bounds__(kThreads) k_finalize(const float* __restrict__
   if (loss_out && blockIdx.x == 0) {
     float s = 0.0f;
     for (int i = threadIdx.x; i < nslots; i += kThreads) s += loss_slots[i];
-    const float t = block_sum(s, red);
+    const float t = block_sum<4>(s, red);
     if (threadIdx.x == 0) *loss_out = t;
   }
 }
 
 // ---------------------------------------------------------------------------------------------
 // Fused weight gradient + SGD + (Kahan) + rounding, in place (Algorithm 1, fuse_update).
-// One workgroup owns a 128 (labels) x 128 (columns) tile of W_c: grad = G^T X accumulated in FP32
+// One workgroup owns a 256 (labels) x 128 (columns) tile of W_c: grad = G^T X accumulated in FP32
 // over the whole batch on the BF16 matrix cores, then per element the FP32 update of
 // numerics.h, rounded stochastically (Eq. 1) or to nearest, written back in the storage format.
 // The weight gradient only ever exists as MFMA accumulators and one LDS tile.
 // ---------------------------------------------------------------------------------------------
 constexpr int kGPitch = 132;
-constexpr int kUpdateSmem = 128 * kGPitch * 4;
-static_assert(kUpdateSmem >= 4 * 128 * 128, "main-loop buffers must fit");
+constexpr int kUpdateSmem = 256 * kGPitch * 4;
+static_assert(kUpdateSmem <= kNtRingBytes, "epilogue reuses the ring memory");
 
 // Sixteen consecutive elements of one weight row: storage bits in, storage bits out.
 // E4M3: w[0..3] hold 4 codes each; BF16: w[0..7] hold 2 patterns each.  c[0..7]: BF16 compensation.
@@ -435,7 +404,7 @@ __device__ inline void update16(uint32_t (&w)[8], uint32_t (&c)[8], const float 
 }
 
 template <int FMT, bool SR, bool KAHAN>
-__global__ void __launch_bounds__(kThreads, 2)
+__global__ void __launch_bounds__(kGemmThreads, 1)
 k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restrict__ Wc, uint16_t* __restrict__ Cc,
          int n, int d, int Bp, float lr, uint64_t seed, uint64_t step, uint64_t elem0) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -445,9 +414,8 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
   const int tiles_j = d >> 7;
   const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
   const int lt = wg / tiles_j, jt = wg % tiles_j;
-  const int l0 = lt << 7, j0 = jt << 7;
+  const int l0 = lt << 8, j0 = jt << 7;
   const size_t stride = (size_t)Bp * 2;
-  const int nk = Bp >> 6;
   const int va = n - l0;
 
   // This thread's share of the weight (and compensation) tile, fetched before the product so the
@@ -457,7 +425,7 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
   u32x4 creg[4][2];
 #pragma unroll
   for (int it = 0; it < 4; ++it) {
-    const int l = min(l0 + it * 32 + urow, n - 1);
+    const int l = min(l0 + it * 64 + urow, n - 1);
     const size_t eoff = (size_t)l * d + j0 + useg * 16;
 #pragma unroll
     for (int q = 0; q < WQ; ++q) wreg[it][q] = *reinterpret_cast<const u32x4*>(Wc + eoff * ESZ + 16 * q);
@@ -467,64 +435,26 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
     }
   }
 
-  TileLoader<128, 128> la0, la1, lb0, lb1;
-  const char* ga = Gt + (size_t)l0 * stride;
-  const char* gb = XT + (size_t)j0 * stride;
   f32x16 acc[2][2];
+  zero_acc(acc);
+  // K loop over the batch in slabs of 64 samples
+  ring_pipeline<256, 128, 128, 128, kStages, kGemmWaves>(
+      Gt + (size_t)l0 * stride, stride, va, 0, 128, XT + (size_t)j0 * stride, stride, 128, 0, 128, Bp >> 6, smem, wave, lane,
+      [&](const char* sa, const char* sb) {
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+        for (int kk = 0; kk < 4; ++kk) {
+          bf16x8 a[2], b[2];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+          for (int i = 0; i < 2; ++i) a[i] = frag_bf16(sa, wm * 64 + 32 * i, kk, lane);
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-  auto mma = [&](const char* sa, const char* sb) {
+          for (int j = 0; j < 2; ++j) b[j] = frag_bf16(sb, wn * 64 + 32 * j, kk, lane);
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 a[2], b[2];
+          for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int i = 0; i < 2; ++i) a[i] = frag_bf16(sa, wm * 64 + 32 * i, kk, lane);
-#pragma unroll
-      for (int j = 0; j < 2; ++j) b[j] = frag_bf16(sb, wn * 64 + 32 * j, kk, lane);
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
-  };
-  // K loop over the batch, slabs of 64 samples; global loads run two slabs ahead of the MFMAs
-  // (two register sets, selected by literal index so they stay in registers), LDS is double
-  // buffered, one barrier per slab.
-#define ELMO_UPDATE_STAGE(KS, ST, LD)                                          \
-  {                                                                            \
-    if ((KS) + 2 < nk) {                                                       \
-      la##LD.load_clamped(ga + (size_t)((KS) + 2) * 128, stride, va, tid);     \
-      lb##LD.load_clamped(gb + (size_t)((KS) + 2) * 128, stride, 128, tid);    \
-    }                                                                          \
-    const char* sa_ = smem + ((KS) & 1) * 32768;                               \
-    mma(sa_, sa_ + 16384);                                                     \
-    if ((KS) + 1 < nk) {                                                       \
-      char* da_ = smem + (((KS) + 1) & 1) * 32768;                             \
-      la##ST.store(da_, tid);                                                  \
-      lb##ST.store(da_ + 16384, tid);                                          \
-    }                                                                          \
-    __syncthreads();                                                           \
-  }
-  la0.load_clamped(ga, stride, va, tid);
-  lb0.load_clamped(gb, stride, 128, tid);
-  if (nk > 1) {
-    la1.load_clamped(ga + 128, stride, va, tid);
-    lb1.load_clamped(gb + 128, stride, 128, tid);
-  }
-  la0.store(smem, tid);
-  lb0.store(smem + 16384, tid);
-  __syncthreads();
-  for (int ks = 0; ks < nk; ks += 2) {
-    ELMO_UPDATE_STAGE(ks, 1, 0)
-    if (ks + 1 < nk) ELMO_UPDATE_STAGE(ks + 1, 0, 1)
-  }
-#undef ELMO_UPDATE_STAGE
+            for (int j = 0; j < 2; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+      });
 
   // ---- stage the gradient tile [label][column] in LDS
   float* gs = reinterpret_cast<float*>(smem);
@@ -540,7 +470,7 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
   // ---- per-element update
 #pragma unroll
   for (int it = 0; it < 4; ++it) {
-    const int row = it * 32 + urow;
+    const int row = it * 64 + urow;
     const int l = l0 + row;
     if (l >= n) continue;
     const size_t eoff = (size_t)l * d + j0 + useg * 16;
