@@ -1,11 +1,17 @@
 // Top-k scoring over all labels (the top_k of the paper's P@k definition) for gfx950.
 //
-// The [B, L] score matrix is never formed.  A workgroup owns 64 query rows and one contiguous
-// segment of the labels; it walks the segment in 128-label tiles, computes the tile's logits on
-// the matrix cores exactly as the training step does (E4M3 x E4M3 or BF16 x BF16, FP32
-// accumulation), and keeps per row a sorted list of the k best (score, id) seen so far in LDS.
-// Only scores above the row's current k-th best take the insertion path.  A second kernel merges
-// the per-segment lists of a row.  Order: score descending, label id ascending on ties.
+// The [B, L] score matrix is never formed.  Main path: the labels are visited in a few levels of
+// geometrically growing size (2048, then 16x more each time).  A level computes its logits tile
+// by tile on the matrix cores exactly as the training step does (E4M3 x E4M3 or BF16 x BF16,
+// FP32 accumulation) and appends every score that beats the row's threshold -- the k-th best
+// score over all earlier levels -- to the row's candidate list; a select kernel then sorts the
+// candidates, keeps the k best and raises the threshold.  A later label that merely ties the
+// threshold can never enter the top k (same score, larger id), so the comparison is strict and
+// the result exact.  With thresholds from 1/16 of the labels about 16 k candidates per row
+// survive a level; the lists hold 4096.  A row whose list overflows (scores rising steeply with
+// the label id) is flagged and recomputed by the fallback path below, which has no capacity
+// limit: 64 query rows per workgroup walk a label segment keeping a sorted k-list in LDS, and a
+// merge kernel joins the segments.  Order: score descending, label id ascending on ties.
 #pragma once
 #include <limits.h>
 
@@ -17,6 +23,8 @@
 namespace elmo {
 
 constexpr int kTopkMaxK = 128;
+constexpr int kTopkCand = 4096;                    // candidate list length per row (main path)
+constexpr int kTopkLevel0 = 2048;                  // labels of the first level; later levels grow 16x
 constexpr int kTopkRows = 64;                       // query rows per workgroup
 constexpr int kTopkZP = 132;                        // floats per staged row
 constexpr int kTopkLP = 129;                        // list pitch (odd: one row per thread, no bank clash)
@@ -27,19 +35,28 @@ static_assert(kTopkRows * kTopkZP * 4 <= kTopkStage, "staged tile must fit the o
 // Label segments per 64-row group: enough workgroups to fill the chip, at most 64 lists to merge.
 inline int topk_segments(int tiles_b) { return std::max(1, std::min(64, 512 / tiles_b)); }
 
-// Bytes of per-segment partial lists for any batch of at most Bp_max rows.
+// Main-path scratch: thresholds, counters, overflow flags and candidate lists per (padded) row.
+inline size_t topk_main_rows(int Bp_max) { return (size_t)(Bp_max + 255) / 256 * 256; }
+inline size_t topk_main_bytes(int Bp_max) { return topk_main_rows(Bp_max) * (12 + (size_t)kTopkCand * 8) + 1024; }
+
+// Bytes of per-segment partial lists for any batch of at most Bp_max rows, plus the main path's.
 inline size_t topk_scratch_bytes(int Bp_max, int64_t /*chunk*/) {
   const int tb_max = (Bp_max + kTopkRows - 1) / kTopkRows;
   size_t lists = 0;
   for (int tb = 1; tb <= tb_max; ++tb) lists = std::max(lists, (size_t)tb * kTopkRows * topk_segments(tb));
-  return lists * kTopkMaxK * 8;
+  return lists * kTopkMaxK * 8 + topk_main_bytes(Bp_max);
 }
 
 template <bool FP8>
 __global__ void __launch_bounds__(kThreads, 1)
 k_topk_chunk(const char* __restrict__ Xa, int a_rows, const char* __restrict__ W, int64_t L, int d, int k, int P,
-             int tiles_per_seg, float* __restrict__ part_sc, int* __restrict__ part_id) {
+             int tiles_per_seg, float* __restrict__ part_sc, int* __restrict__ part_id, const int* __restrict__ only_rows,
+             int B) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
+  if (only_rows) {   // fallback use: nothing to do unless one of this group's rows is flagged
+    const int r = (blockIdx.x / P) * kTopkRows + (threadIdx.x & 63);
+    if (!__syncthreads_or(r < B && only_rows[r] != 0)) return;
+  }
   float* zs = reinterpret_cast<float*>(smem);
   float* lsc = reinterpret_cast<float*>(smem + kTopkStage);
   int* lid = reinterpret_cast<int*>(smem + kTopkStage + kTopkRows * kTopkLP * 4);
@@ -161,27 +178,8 @@ k_topk_chunk(const char* __restrict__ Xa, int a_rows, const char* __restrict__ W
   }
 }
 
-// Merge the P per-segment lists of one row: bitonic sort of P*k (padded to a power of two) pairs
-// by (score descending, id ascending), first k written out.
-__global__ void __launch_bounds__(kThreads) k_topk_merge(const float* __restrict__ part_sc, const int* __restrict__ part_id,
-                                                         int P, int k, int N2, int* __restrict__ idx_out,
-                                                         float* __restrict__ score_out) {
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  float* sc = reinterpret_cast<float*>(smem);
-  int* id = reinterpret_cast<int*>(smem + (size_t)N2 * 4);
-  const int b = blockIdx.x, tid = threadIdx.x;
-  const int items = P * k;
-  for (int i = tid; i < N2; i += kThreads) {
-    if (i < items) {
-      const size_t o = ((size_t)b * P + i / k) * kTopkMaxK + i % k;
-      sc[i] = part_sc[o];
-      id[i] = part_id[o];
-    } else {
-      sc[i] = -INFINITY;
-      id[i] = INT_MAX;
-    }
-  }
-  __syncthreads();
+// In-LDS bitonic sort of N2 (a power of two) pairs by (score descending, id ascending).
+__device__ inline void bitonic_sort_pairs(float* sc, int* id, int N2, int tid) {
   for (int size = 2; size <= N2; size <<= 1) {
     for (int stride = size >> 1; stride > 0; stride >>= 1) {
       for (int i = tid; i < (N2 >> 1); i += kThreads) {
@@ -196,36 +194,203 @@ __global__ void __launch_bounds__(kThreads) k_topk_merge(const float* __restrict
       __syncthreads();
     }
   }
+}
+
+// Merge the P per-segment lists of one row: bitonic sort of P*k (padded to a power of two) pairs
+// by (score descending, id ascending), first k written out.
+__global__ void __launch_bounds__(kThreads) k_topk_merge(const float* __restrict__ part_sc, const int* __restrict__ part_id,
+                                                         int P, int k, int N2, int* __restrict__ idx_out,
+                                                         float* __restrict__ score_out, const int* __restrict__ only_rows) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  float* sc = reinterpret_cast<float*>(smem);
+  int* id = reinterpret_cast<int*>(smem + (size_t)N2 * 4);
+  const int b = blockIdx.x, tid = threadIdx.x;
+  if (only_rows && only_rows[b] == 0) return;
+  const int items = P * k;
+  for (int i = tid; i < N2; i += kThreads) {
+    if (i < items) {
+      const size_t o = ((size_t)b * P + i / k) * kTopkMaxK + i % k;
+      sc[i] = part_sc[o];
+      id[i] = part_id[o];
+    } else {
+      sc[i] = -INFINITY;
+      id[i] = INT_MAX;
+    }
+  }
+  __syncthreads();
+  bitonic_sort_pairs(sc, id, N2, tid);
   for (int i = tid; i < k; i += kThreads) {
     if (idx_out) idx_out[(size_t)b * k + i] = id[i];
     if (score_out) score_out[(size_t)b * k + i] = sc[i];
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Main path: threshold filter fused into the logits tile, and the per-row select.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kThreads) k_topk_init(float* __restrict__ tau, int* __restrict__ cnt, int* __restrict__ ovf, int rows) {
+  const int i = blockIdx.x * kThreads + threadIdx.x;
+  if (i < rows) { tau[i] = -INFINITY; cnt[i] = 0; ovf[i] = 0; }
+}
+
+// Logits of labels [l_begin, l_begin + n) for all rows, 256 x 128 tiles as in the training step;
+// every score above its row's threshold is appended to that row's candidate list.
+template <bool FP8>
+__global__ void __launch_bounds__(kGemmThreads, 1)
+k_topk_filter(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wl, int n, int l_begin, int d, int Bp, int B,
+              const float* __restrict__ tau, int* __restrict__ cnt, int* __restrict__ ovf, float* __restrict__ cand_sc,
+              int* __restrict__ cand_id) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
+  const int tiles_b = (Bp + 255) >> 8;
+  const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
+  const int lt = wg / tiles_b, bt = wg % tiles_b;
+  const int b0 = bt << 8, l0 = lt << 7;
+  const size_t rowb = (size_t)d * (FP8 ? 1 : 2);
+  f32x16 acc[2][2];
+  zero_acc(acc);
+  ring_pipeline<256, 128, 128, 128, kStages, kGemmWaves>(
+      Xa + (size_t)b0 * rowb, rowb, a_rows - b0, 0, 128, Wl + (size_t)l0 * rowb, rowb, n - l0, 0, 128, (int)(rowb >> 7), smem,
+      wave, lane, [&](const char* sa, const char* sb) {
+        if (FP8) {
+#pragma unroll
+          for (int kk = 0; kk < 2; ++kk) {
+            i32x8 a[2], b[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) a[i] = frag_fp8(sa, wm * 64 + 32 * i, kk, lane);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) b[j] = frag_fp8(sb, wn * 64 + 32 * j, kk, lane);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+              for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 0, 0, 0, 0, 0, 0);
+          }
+        } else {
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) {
+            bf16x8 a[2], b[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) a[i] = frag_bf16(sa, wm * 64 + 32 * i, kk, lane);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) b[j] = frag_bf16(sb, wn * 64 + 32 * j, kk, lane);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+              for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+          }
+        }
+      });
+  float* tau_s = reinterpret_cast<float*>(smem);
+  for (int i = tid; i < 256; i += kGemmThreads) tau_s[i] = b0 + i < B ? tau[b0 + i] : INFINITY;   // padding rows never emit
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int b = wm * 64 + 32 * i + acc_row(v, lane);
+        const int l = l0 + wn * 64 + 32 * j + (lane & 31);
+        const float z = acc[i][j][v];
+        if (l < n && z > tau_s[b]) {
+          const int row = b0 + b;
+          const int slot = atomicAdd(&cnt[row], 1);
+          if (slot < kTopkCand) {
+            cand_sc[(size_t)row * kTopkCand + slot] = z;
+            cand_id[(size_t)row * kTopkCand + slot] = l_begin + l;
+          } else {
+            ovf[row] = 1;
+          }
+        }
+      }
+}
+
+// Per row: sort the candidates, keep the k best at the front of the list, raise the threshold.
+__global__ void __launch_bounds__(kThreads) k_topk_select(float* __restrict__ tau, int* __restrict__ cnt, float* __restrict__ cand_sc,
+                                                          int* __restrict__ cand_id, int k, int* __restrict__ idx_out,
+                                                          float* __restrict__ score_out) {
+  __shared__ float sc[kTopkCand];
+  __shared__ int id[kTopkCand];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int m = min(cnt[b], kTopkCand);
+  int N2 = 2;
+  while (N2 < m) N2 <<= 1;
+  for (int i = tid; i < N2; i += kThreads) {
+    sc[i] = i < m ? cand_sc[(size_t)b * kTopkCand + i] : -INFINITY;
+    id[i] = i < m ? cand_id[(size_t)b * kTopkCand + i] : INT_MAX;
+  }
+  __syncthreads();
+  bitonic_sort_pairs(sc, id, N2, tid);
+  const int keep = min(m, k);
+  for (int i = tid; i < keep; i += kThreads) {
+    cand_sc[(size_t)b * kTopkCand + i] = sc[i];
+    cand_id[(size_t)b * kTopkCand + i] = id[i];
+  }
+  if (tid == 0) {
+    cnt[b] = keep;
+    tau[b] = m >= k ? sc[k - 1] : -INFINITY;
+  }
+  if (idx_out || score_out)
+    for (int i = tid; i < k; i += kThreads) {
+      if (idx_out) idx_out[(size_t)b * k + i] = id[i];
+      if (score_out) score_out[(size_t)b * k + i] = sc[i];
+    }
+}
+
+inline int topk_launch_error(const char* what, char* err, size_t errsz) {
+  const hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return 0;
+  snprintf(err, errsz, "launch of %s failed: %s", what, hipGetErrorString(e));
+  return -3;
+}
+
 inline int topk_run(hipStream_t st, bool fp8, const char* Xa, int a_rows, const char* W, int64_t L, int d, int64_t /*chunk*/,
                     int B, int Bp, int k, char* scratch, int* idx_out, float* score_out, char* err, size_t errsz) {
+  // ---- main path
+  const size_t rows = topk_main_rows(Bp);
+  float* tau = reinterpret_cast<float*>(scratch);
+  int* cnt = reinterpret_cast<int*>(scratch + rows * 4);
+  int* ovf = reinterpret_cast<int*>(scratch + rows * 8);
+  float* cand_sc = reinterpret_cast<float*>(scratch + rows * 12);
+  int* cand_id = reinterpret_cast<int*>(scratch + rows * 12 + rows * (size_t)kTopkCand * 4);
+  char* fb_scratch = scratch + topk_main_bytes(Bp);
+  const size_t rowb = (size_t)d * (fp8 ? 1 : 2);
+  k_topk_init<<<(int)((rows + kThreads - 1) / kThreads), kThreads, 0, st>>>(tau, cnt, ovf, (int)rows);
+  if (int rc = topk_launch_error("k_topk_init", err, errsz)) return rc;
+  const int tiles_b256 = (Bp + 255) / 256;
+  for (int64_t begin = 0, end = std::min<int64_t>(L, kTopkLevel0); begin < L; begin = end, end = std::min<int64_t>(L, end * 17)) {
+    const int n = (int)(end - begin);
+    const int grid = (n + 127) / 128 * tiles_b256;
+    const char* Wl = W + (size_t)begin * rowb;
+    if (fp8) k_topk_filter<true><<<grid, kGemmThreads, kNtRingBytes, st>>>(Xa, a_rows, Wl, n, (int)begin, d, Bp, B, tau, cnt, ovf, cand_sc, cand_id);
+    else k_topk_filter<false><<<grid, kGemmThreads, kNtRingBytes, st>>>(Xa, a_rows, Wl, n, (int)begin, d, Bp, B, tau, cnt, ovf, cand_sc, cand_id);
+    if (int rc = topk_launch_error("k_topk_filter", err, errsz)) return rc;
+    const bool last = end == L;
+    k_topk_select<<<B, kThreads, 0, st>>>(tau, cnt, cand_sc, cand_id, k, last ? idx_out : nullptr, last ? score_out : nullptr);
+    if (int rc = topk_launch_error("k_topk_select", err, errsz)) return rc;
+  }
+  // ---- fallback for rows whose candidate list overflowed (does nothing when no row is flagged)
   const int tiles_b = (B + kTopkRows - 1) / kTopkRows;
   const int tiles_l = (int)((L + 127) / 128);
   int P = topk_segments(tiles_b);
   P = std::min(P, tiles_l);
   const int tps = (tiles_l + P - 1) / P;
   P = (tiles_l + tps - 1) / tps;
-  float* part_sc = reinterpret_cast<float*>(scratch);
-  int* part_id = reinterpret_cast<int*>(scratch + (size_t)tiles_b * kTopkRows * P * kTopkMaxK * 4);
-  if ((size_t)tiles_b * kTopkRows * P * kTopkMaxK * 8 > topk_scratch_bytes(Bp, 0)) {
+  float* part_sc = reinterpret_cast<float*>(fb_scratch);
+  int* part_id = reinterpret_cast<int*>(fb_scratch + (size_t)tiles_b * kTopkRows * P * kTopkMaxK * 4);
+  if ((size_t)tiles_b * kTopkRows * P * kTopkMaxK * 8 + topk_main_bytes(Bp) > topk_scratch_bytes(Bp, 0)) {
     snprintf(err, errsz, "top-k scratch plan exceeded");
     return -3;
   }
-  if (fp8) k_topk_chunk<true><<<tiles_b * P, kThreads, kTopkSmem, st>>>(Xa, a_rows, W, L, d, k, P, tps, part_sc, part_id);
-  else k_topk_chunk<false><<<tiles_b * P, kThreads, kTopkSmem, st>>>(Xa, a_rows, W, L, d, k, P, tps, part_sc, part_id);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) { snprintf(err, errsz, "launch of k_topk_chunk failed: %s", hipGetErrorString(e)); return -3; }
+  if (fp8) k_topk_chunk<true><<<tiles_b * P, kThreads, kTopkSmem, st>>>(Xa, a_rows, W, L, d, k, P, tps, part_sc, part_id, ovf, B);
+  else k_topk_chunk<false><<<tiles_b * P, kThreads, kTopkSmem, st>>>(Xa, a_rows, W, L, d, k, P, tps, part_sc, part_id, ovf, B);
+  if (int rc = topk_launch_error("k_topk_chunk", err, errsz)) return rc;
   int N2 = 2;
   while (N2 < P * k) N2 <<= 1;
-  k_topk_merge<<<B, kThreads, (size_t)N2 * 8, st>>>(part_sc, part_id, P, k, N2, idx_out, score_out);
-  e = hipGetLastError();
-  if (e != hipSuccess) { snprintf(err, errsz, "launch of k_topk_merge failed: %s", hipGetErrorString(e)); return -3; }
-  return 0;
+  k_topk_merge<<<B, kThreads, (size_t)N2 * 8, st>>>(part_sc, part_id, P, k, N2, idx_out, score_out, ovf);
+  return topk_launch_error("k_topk_merge", err, errsz);
 }
 
 }  // namespace elmo

@@ -421,6 +421,23 @@ def test_topk_ties_prefer_smaller_ids(b):
     assert np.array_equal(idx.cpu().numpy(), np.tile(np.arange(k), (B, 1))) and np.all(sc.cpu().numpy() == 0)
 
 
+def test_topk_rising_scores_take_the_unbounded_path(b):
+    """Scores that rise with the label id beat every threshold taken from earlier labels, so the
+    per-row candidate lists of the fast path overflow and the capacity-free path must answer."""
+    L, d, B, k = 40000, 128, 9, 20
+    rng = np.random.default_rng(5)
+    X = synth.make_x(rng, B, d)
+    u = o.decode_bf16(X).mean(axis=0)
+    u /= np.linalg.norm(u)
+    ramp = np.linspace(0.0, 2.0, L)[:, None] * u[None, :] + rng.standard_normal((L, d)) * 1e-3
+    case = Case(b, L, d, o.BF16, 4096, 0, B)
+    W = o.round_bf16(ramp.astype(np.float32))
+    case.load(W, None)
+    say("[topk-rising] L=40000 B=9 k=20")
+    exact = _check_topk(b, case.head, W, X, k, o.BF16, 2e-3)
+    assert exact > 0.9
+
+
 def test_topk_mid_size(b):
     cfg = synth.CONFIGS["mid"]
     head = b.Head(cfg.L, cfg.d, cfg.fmt, cfg.chunk, 0, 64, 64)
