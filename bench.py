@@ -29,6 +29,34 @@ PEAK_BF16_TFLOPS = 2500.0
 PEAK_FP8_TFLOPS = 5000.0
 
 
+def profiled_traffic(kernel: str, workload: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary of this
+    workload (FETCH_SIZE and WRITE_SIZE, scaled by the factors measured in the same runs), or None."""
+    if workload != "xl":
+        return None
+    path = os.path.join(ROOT, "profiles", "head_step_xl_fp8_B1024.txt")
+    try:
+        lines = open(path).read().splitlines()
+    except OSError:
+        return None
+    scale = {}
+    for ln in lines:
+        ln = ln.strip()
+        if ln.startswith("FETCH_SIZE:") or ln.startswith("WRITE_SIZE:"):
+            scale[ln.split(":")[0]] = float(ln.rsplit("by", 1)[1])
+    name = {"logits": "k_logits", "dx": "k_dx", "update": "k_update"}[kernel]
+    for ln in lines:
+        f = ln.split()
+        if len(f) >= 4 and f[0].startswith(name + "<") and "FETCH" not in ln:
+            try:
+                fetch_kib, write_kib = float(f[-2]), float(f[-1])
+            except ValueError:
+                continue
+            if len(scale) == 2 and fetch_kib > 1000:       # the counter table, not the timing table
+                return (fetch_kib * scale["FETCH_SIZE"] + write_kib * scale["WRITE_SIZE"]) * 1024.0
+    return None
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -149,7 +177,9 @@ def main():
                 "peak": (PEAK_FP8_TFLOPS if (dom == "logits" and fp8) else PEAK_BF16_TFLOPS), "frac": kd["mfma_frac"]}
     else:
         roof = {"bound": "hbm", "achieved": kd["algo_gbs"], "unit": "GB/s", "peak": PEAK_HBM_GBS, "frac": kd["hbm_frac"]}
-    roof.update({"kernel": dom, "avg_launch_ms": kd["avg_ms"], "traffic": None})
+    unchanged = not (args.batch or args.chunk or args.no_kahan or args.no_dx)
+    roof.update({"kernel": dom, "avg_launch_ms": kd["avg_ms"],
+                 "traffic": profiled_traffic(dom, args.workload) if unchanged else None})
 
     # whole-step figures of the headline metric: flop/s against the FP8 MFMA peak (6 B L d flop per
     # step) and weight read-modify-write bytes against HBM peak
