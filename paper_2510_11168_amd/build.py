@@ -15,6 +15,8 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed FP32 instructions are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the update arithmetic rounds after every FP32 operation: no contraction into fused multiply-adds
+    "-ffp-contract=off",
     "-Wno-unused-result",
 ]
 

@@ -61,6 +61,7 @@ int make_plan(int64_t L, int d, int fmt, int64_t chunk, int maxB, int64_t max_nn
   const int tiles_j = d / 128;
   // slices x padded batch of the input-gradient partials: about one workgroup per CU
   p.dx_rows = std::min(65536 / tiles_j + 256 * p.tiles_b_max + 256, 64 * 256 * p.tiles_b_max);
+  if (d % 256 == 0) p.dx_rows = std::max(p.dx_rows, 256 / (d / 256) * 128);   // small-batch path: one 128-row slice per label group
   const int64_t chunk_eff = std::min<int64_t>(chunk, (L + 127) / 128 * 128);
   size_t o = 0;
   p.off_xq = o;  o += align256(fmt == ELMO_FP8_E4M3 ? (size_t)p.Bp_max * d : 0);
@@ -245,6 +246,38 @@ void launch_update(hipStream_t st, int grid, bool sr, bool kahan, const char* Gt
 #undef ELMO_UPD
 }
 
+// Small-batch fused input gradient + update.  Returns the launch's dynamic LDS size through the
+// template so that the attribute call and the launch agree.
+template <int FMT, bool SR, bool KAHAN, bool DX>
+int launch_dx_update_one(hipStream_t st, int grid, const char* Gt, const char* XT, char* Wc, uint16_t* Cc, float* dXacc, int n,
+                         int d, int Bp, float lr, uint64_t seed, uint64_t step, uint64_t elem0, int tpg) {
+  static bool attr_done = false;
+  constexpr int smem = elmo::dxu_smem_bytes<FMT, KAHAN>();
+  if (!attr_done) {
+    ELMO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&elmo::k_dx_update<FMT, SR, KAHAN, DX>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem));
+    attr_done = true;
+  }
+  elmo::k_dx_update<FMT, SR, KAHAN, DX><<<grid, elmo::kGemmThreads, smem, st>>>(Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, seed, step,
+                                                                               elem0, tpg);
+  return 0;
+}
+template <int FMT>
+int launch_dx_update(hipStream_t st, int grid, bool sr, bool kahan, bool dx, const char* Gt, const char* XT, char* Wc, uint16_t* Cc,
+                     float* dXacc, int n, int d, int Bp, float lr, uint64_t seed, uint64_t step, uint64_t elem0, int tpg) {
+#define ELMO_DXU(SR_, KA_, DX_) \
+  return launch_dx_update_one<FMT, SR_, KA_, DX_>(st, grid, Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, seed, step, elem0, tpg)
+  if (sr && kahan && dx) ELMO_DXU(true, true, true);
+  if (sr && kahan) ELMO_DXU(true, true, false);
+  if (sr && dx) ELMO_DXU(true, false, true);
+  if (sr) ELMO_DXU(true, false, false);
+  if (kahan && dx) ELMO_DXU(false, true, true);
+  if (kahan) ELMO_DXU(false, true, false);
+  if (dx) ELMO_DXU(false, false, true);
+  ELMO_DXU(false, false, false);
+#undef ELMO_DXU
+}
+
 // Opt in to more than 64 KiB of dynamic LDS for the tile kernels (done once per process).
 int raise_lds_limits() {
   static bool done = false;
@@ -302,11 +335,16 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
   int2* pos = (int2*)(h->ws + p.off_pos);
   int* flag = (p.flags & ELMO_VALIDATE) ? (int*)(h->ws + p.off_flag) : nullptr;
 
+  // Small batches are bound by memory traffic: input gradient and update share one pass over W.
+  const bool small_batch = Bp <= 128 && d % 256 == 0;
+  const int col_blocks = d / 256, label_groups = small_batch ? 256 / col_blocks : 0;
   // label slices of the input-gradient product: at most one 512-thread workgroup per CU, so the
   // whole grid is resident at once (256 CUs) and no second, nearly empty round of workgroups runs
   int S = std::max(1, 256 / (tiles_b * tiles_j));
   S = std::min(S, p.dx_rows / Bp256);
   S = std::max(1, std::min(S, 64));
+  const int dx_slices = small_batch ? label_groups : S;
+  const int dx_plane_rows = small_batch ? 128 : Bp256;
 
   Profiler& prof = h->prof;
   prof.mark(st, CLS_SETUP);
@@ -316,7 +354,7 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
     elmo::k_prep_x<<<(int)std::min<size_t>((n + 255) / 256, 4096), elmo::kThreads, 0, st>>>((const uint16_t*)X, B, Bp, d, Xq, XT);
     if (int rc = check_launch("k_prep_x")) return rc;
     if (dX_out) {
-      const size_t w = (size_t)S * Bp256 * d;
+      const size_t w = (size_t)dx_slices * dx_plane_rows * d;
       elmo::k_fill_u32<<<(int)std::min<size_t>((w + 255) / 256, 4096), elmo::kThreads, 0, st>>>((uint32_t*)dXacc, w, 0u);
       if (int rc = check_launch("k_fill_u32")) return rc;
     }
@@ -357,6 +395,19 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
       }
       if (int rc = check_launch("k_logits")) return rc;
     }
+    if (small_batch) {
+      prof.mark(st, CLS_UPDATE);
+      const int ntiles32 = (n + 31) / 32, tpg = (ntiles32 + label_groups - 1) / label_groups;
+      const int groups_used = (ntiles32 + tpg - 1) / tpg;
+      const bool sr = p.flags & ELMO_SR, kahan = p.flags & ELMO_KAHAN;
+      const uint64_t elem0 = (uint64_t)c0 * (uint64_t)d;
+      int rc;
+      if (fp8) rc = launch_dx_update<elmo::FMT_E4M3>(st, groups_used * col_blocks, sr, kahan, dX_out != nullptr, (const char*)Gt, (const char*)XT, Wc, Cc, dXacc, n, d, Bp, lr, seed, step, elem0, tpg);
+      else rc = launch_dx_update<elmo::FMT_BF16>(st, groups_used * col_blocks, sr, kahan, dX_out != nullptr, (const char*)Gt, (const char*)XT, Wc, Cc, dXacc, n, d, Bp, lr, seed, step, elem0, tpg);
+      if (rc) return rc;
+      if (int rc2 = check_launch("k_dx_update")) return rc2;
+      continue;
+    }
     if (dX_out) {
       prof.mark(st, CLS_DX);
       const int grid = tiles_b * tiles_j * S;
@@ -379,7 +430,7 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
   if (dX_out || loss_out) {
     const size_t n = (size_t)B * d;
     const int grid = dX_out ? (int)std::min<size_t>((n + 255) / 256, 4096) : 1;
-    elmo::k_finalize<<<grid, elmo::kThreads, 0, st>>>(dXacc, S, Bp256, B, d, (uint16_t*)dX_out, loss_slots,
+    elmo::k_finalize<<<grid, elmo::kThreads, 0, st>>>(dXacc, dx_slices, dx_plane_rows, B, d, (uint16_t*)dX_out, loss_slots,
                                                      p.ntiles * tiles_b, loss_out);
     if (int rc = check_launch("k_finalize")) return rc;
   }

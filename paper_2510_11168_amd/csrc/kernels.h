@@ -267,6 +267,16 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
 // Label rows beyond n inside the last 64-label slab are harmless: G^T holds zeros there and the
 // weight rows are re-reads of row n-1.
 // ---------------------------------------------------------------------------------------------
+// dst[32 x 32 block, row pitch d] += one 32x32 accumulator tile.  All sixteen loads are issued
+// before the first store, so the read-modify-write costs one memory round trip, not sixteen.
+__device__ inline void add_acc_to_global(float* __restrict__ dst, int d, int lane, const f32x16& acc) {
+  float old[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) old[v] = dst[(size_t)acc_row(v, lane) * d + (lane & 31)];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) dst[(size_t)acc_row(v, lane) * d + (lane & 31)] = old[v] + acc[v];
+}
+
 template <bool FP8> constexpr int dx_smem_bytes() { return kStages * (64 * 512 + 64 * (FP8 ? 128 : 256)); }
 
 template <bool FP8>
@@ -312,13 +322,7 @@ k_dx(const char* __restrict__ Gt, const char* __restrict__ Wc, float* __restrict
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int b = b0 + wm * 64 + 32 * i + acc_row(v, lane);
-        const int jj = j0 + wn * 64 + 32 * j + (lane & 31);
-        float* p = out + (size_t)b * d + jj;
-        *p += acc[i][j][v];
-      }
+      add_acc_to_global(out + (size_t)(b0 + wm * 64 + 32 * i) * d + j0 + wn * 64 + 32 * j, d, lane, acc[i][j]);
 }
 
 // dX_out = BF16(sum over label slices of the FP32 partials); loss_out = sum of the tile losses.
@@ -502,6 +506,174 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
       *reinterpret_cast<u32x4*>(Cc + eoff + 8) = u32x4{c[4], c[5], c[6], c[7]};
     }
   }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Small batches (padded batch <= 128): input gradient and fused update in ONE pass over the
+// weights.  At small batch the step is bound by memory traffic, and running the two products as
+// separate kernels reads every weight twice; here a workgroup streams tiles of 32 labels x 256
+// columns of W_c (and of the compensation) exactly once, and from each tile, while it sits in LDS,
+// forms both  dX[:, cols] += G W_tile  (old weights, transposing reads)  and  grad = G^T X[:, cols]
+// followed by the same per-element update as k_update.  Workgroup (g, c) owns column block c
+// (256 columns) and the g-th contiguous range of label tiles of the chunk; its 128 x 256 slice of
+// dX stays in registers over all its tiles and is added to dXacc[g] at the end (one owner).
+// The X operand of the gradient product lives in registers for the whole kernel.
+// Stage of the 3-deep ring: [W 32 x 256 el | G^T 32 x 256 B | comp 32 x 512 B].
+// ---------------------------------------------------------------------------------------------
+template <int FMT, bool KAHAN> constexpr int dxu_stage_bytes() {
+  return 32 * 256 * (FMT == FMT_E4M3 ? 1 : 2) + 32 * 256 + (KAHAN ? 32 * 512 : 0);
+}
+constexpr int kDxuGsBytes = 32 * 260 * 4;
+template <int FMT, bool KAHAN> constexpr int dxu_smem_bytes() { return kStages * dxu_stage_bytes<FMT, KAHAN>() + kDxuGsBytes; }
+
+// The body is a separate inlined function with restrict-qualified parameters on purpose: inlining
+// it tags every LDS access inside with alias information, without which the compiler puts a full
+// vmcnt(0) wait in front of the transposing LDS reads (it cannot tell them from the asynchronous
+// loads still in flight for later stages) and the ring stops prefetching.  The waits that are
+// needed are the explicit ones below.
+template <int FMT, bool SR, bool KAHAN, bool DX>
+__device__ __forceinline__ void dx_update_body(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restrict__ Wc,
+                                               uint16_t* __restrict__ Cc, float* __restrict__ dXacc, int n, int d, int Bp,
+                                               float lr, uint64_t seed, uint64_t step, uint64_t elem0, int tiles_per_group,
+                                               char* smem) {
+  constexpr int ESZ = FMT == FMT_E4M3 ? 1 : 2;
+  constexpr int WROWB = 256 * ESZ;
+  constexpr int WBYTES = 32 * WROWB, GBYTES = 32 * 256, SBYTES = dxu_stage_bytes<FMT, KAHAN>();
+  constexpr int LPS = WROWB / 256 + 1 + (KAHAN ? 2 : 0);     // asynchronous loads per wave and tile
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int C = d >> 8;
+  const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
+  const int g = wg / C, c = wg % C;
+  const int ntiles = (n + 31) >> 5;
+  const int t0 = g * tiles_per_group, t1 = min(t0 + tiles_per_group, ntiles);
+  if (t0 >= t1) return;
+  const int j0 = c << 8;
+  const size_t gstride = (size_t)Bp * 2;
+  const int KS = Bp >> 4;                                   // k16 steps over the batch: 4 or 8
+  char* ring = smem;
+  float* gs = reinterpret_cast<float*>(smem + kStages * SBYTES);
+
+  // X^T fragments of this wave's 32 columns (B operand of grad = G^T X), resident for the kernel
+  bf16x8 xt[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    const int b = min(16 * ks + 8 * (lane >> 5), Bp - 8);
+    xt[ks] = *reinterpret_cast<const bf16x8*>(XT + ((size_t)(j0 + 32 * wave + (lane & 31)) * Bp + b) * 2);
+  }
+  const int bt = wave & 3, jh = wave >> 2;                  // dX block of this wave: rows 32*bt.., columns 128*jh..
+  f32x16 dxa[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) dxa[t][v] = 0.0f;
+
+  auto issue = [&](int t) {
+    char* st = ring + (t % kStages) * SBYTES;
+    const int l0 = t << 5, valid = n - l0;
+    dma_tile<32, WROWB, kGemmWaves>(Wc + ((size_t)l0 * d + j0) * ESZ, (size_t)d * ESZ, valid, st, wave, lane);
+    // rows of G^T past n exist and hold zeros (written by the logits kernel): no clamping, so they add nothing to dX
+    dma_tile<32, 256, kGemmWaves>(Gt + (size_t)l0 * gstride, gstride, 32, st + WBYTES, wave, lane, Bp >> 3);
+    if (KAHAN)
+      dma_tile<32, 512, kGemmWaves>(reinterpret_cast<const char*>(Cc) + ((size_t)l0 * d + j0) * 2, (size_t)d * 2, valid,
+                                    st + WBYTES + GBYTES, wave, lane);
+  };
+  issue(t0);
+  if (t0 + 1 < t1) issue(t0 + 1);
+  for (int t = t0; t < t1; ++t) {
+    // Tile t has landed once only younger operations are outstanding: tile t+1's loads and the
+    // stores of tile t-1's update (vector loads and stores retire in issue order on gfx9-family
+    // parts and share vmcnt).  Every wave issues NSTORE stores per full tile; the only tile that
+    // can be ragged is the last one of the chunk, after which nothing is waited for.
+    constexpr int NSTORE = ESZ + (KAHAN ? 2 : 0);
+    if (t + 1 >= t1) wait_vmcnt<0>();
+    else if (t == t0) wait_vmcnt<LPS>();
+    else wait_vmcnt<LPS + NSTORE>();
+    barrier_nofence();
+    if (t + 2 < t1) issue(t + 2);
+    const char* ws = ring + (t % kStages) * SBYTES;
+    const char* gsl = ws + WBYTES;
+    const char* cs = gsl + GBYTES;
+    const int l0 = t << 5;
+
+    // grad[32 labels x 32 columns of this wave] = G^T X
+    f32x16 wa;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) wa[v] = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+      if (ks < KS) wa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_bf16<256>(gsl, 0, ks, lane), xt[ks], wa, 0, 0, 0);
+    // dX[32 samples x 128 columns of this wave] += G W_tile (weights as stored before the update)
+    if (DX) {
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        const bf16x8 a = frag_tr_bf16<256>(gsl, 16 * kk, 32 * bt, lane);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const bf16x8 b = FMT == FMT_E4M3 ? frag_tr_fp8<WROWB>(ws, 16 * kk, 128 * jh + 32 * q, lane)
+                                           : frag_tr_bf16<WROWB>(ws, 16 * kk, 128 * jh + 32 * q, lane);
+          dxa[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, dxa[q], 0, 0, 0);
+        }
+      }
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) gs[acc_row(v, lane) * 260 + 32 * wave + (lane & 31)] = wa[v];
+    barrier_lds();
+
+    // per-element update: thread -> one label row, 16 consecutive columns
+    const int l = tid >> 4, seg = tid & 15;
+    if (l0 + l < n) {
+      const size_t eoff = (size_t)(l0 + l) * d + j0 + seg * 16;
+      uint32_t w[8], cc[8];
+      if (FMT == FMT_E4M3) {
+        const u32x4 t4 = *reinterpret_cast<const u32x4*>(ws + tile_off<WROWB>(l, seg));
+        w[0] = t4[0]; w[1] = t4[1]; w[2] = t4[2]; w[3] = t4[3];
+      } else {
+        const u32x4 ta = *reinterpret_cast<const u32x4*>(ws + tile_off<WROWB>(l, 2 * seg));
+        const u32x4 tb = *reinterpret_cast<const u32x4*>(ws + tile_off<WROWB>(l, 2 * seg + 1));
+        w[0] = ta[0]; w[1] = ta[1]; w[2] = ta[2]; w[3] = ta[3]; w[4] = tb[0]; w[5] = tb[1]; w[6] = tb[2]; w[7] = tb[3];
+      }
+      if (KAHAN) {
+        const u32x4 ta = *reinterpret_cast<const u32x4*>(cs + tile_off<512>(l, 2 * seg));
+        const u32x4 tb = *reinterpret_cast<const u32x4*>(cs + tile_off<512>(l, 2 * seg + 1));
+        cc[0] = ta[0]; cc[1] = ta[1]; cc[2] = ta[2]; cc[3] = ta[3]; cc[4] = tb[0]; cc[5] = tb[1]; cc[6] = tb[2]; cc[7] = tb[3];
+      }
+      float gr[16];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const f32x4 t4 = *reinterpret_cast<const f32x4*>(gs + l * 260 + seg * 16 + 4 * q);
+        gr[4 * q] = t4[0]; gr[4 * q + 1] = t4[1]; gr[4 * q + 2] = t4[2]; gr[4 * q + 3] = t4[3];
+      }
+      U4 rb[2];
+      if (SR) {
+        const uint64_t blk = (elem0 + eoff) >> 3;
+        rb[0] = sr_block(blk, seed, step);
+        rb[1] = sr_block(blk + 1, seed, step);
+      }
+      update16<FMT, SR, KAHAN>(w, cc, gr, lr, rb);
+      char* wp = Wc + eoff * ESZ;
+      *reinterpret_cast<u32x4*>(wp) = u32x4{w[0], w[1], w[2], w[3]};
+      if (ESZ == 2) *reinterpret_cast<u32x4*>(wp + 16) = u32x4{w[4], w[5], w[6], w[7]};
+      if (KAHAN) {
+        *reinterpret_cast<u32x4*>(Cc + eoff) = u32x4{cc[0], cc[1], cc[2], cc[3]};
+        *reinterpret_cast<u32x4*>(Cc + eoff + 8) = u32x4{cc[4], cc[5], cc[6], cc[7]};
+      }
+    }
+  }
+  if (DX) {
+    float* out = dXacc + (size_t)g * 128 * d;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      add_acc_to_global(out + (size_t)(32 * bt) * d + j0 + 128 * jh + 32 * q, d, lane, dxa[q]);
+  }
+}
+
+template <int FMT, bool SR, bool KAHAN, bool DX>
+__global__ void __launch_bounds__(kGemmThreads, 1)
+k_dx_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restrict__ Wc, uint16_t* __restrict__ Cc,
+            float* __restrict__ dXacc, int n, int d, int Bp, float lr, uint64_t seed, uint64_t step, uint64_t elem0,
+            int tiles_per_group) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  dx_update_body<FMT, SR, KAHAN, DX>(Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, seed, step, elem0, tiles_per_group, smem);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -51,20 +51,28 @@ __device__ inline void barrier_nofence() {
   asm volatile("" ::: "memory");
 }
 
+// Same, after this wave's own LDS writes have completed (lgkmcnt(0)): orders ds_write -> barrier ->
+// ds_read without the fence of __syncthreads(), which would also drain the asynchronous loads.
+__device__ inline void barrier_lds() {
+  __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0), vmcnt and expcnt untouched
+  barrier_nofence();
+}
+
 // Asynchronous global -> LDS copy of a ROWS x ROWB-byte slab (no registers in between): one
 // global_load_lds_dwordx4 moves 64 lanes x 16 bytes into 1 KiB of consecutive LDS, i.e. 1024/ROWB
 // whole tile rows; each lane fetches the global chunk that belongs at its swizzled position.
 // Rows at or beyond rows_valid (>= 1) re-read the last valid row.  Issues ROWS*ROWB/4096 loads per
 // wave; completion is tracked by vmcnt in issue order.
 template <int ROWS, int ROWB, int NW>
-__device__ inline void dma_tile(const char* __restrict__ g, size_t stride, int rows_valid, char* lds_tile, int wave, int lane) {
+__device__ inline void dma_tile(const char* __restrict__ g, size_t stride, int rows_valid, char* lds_tile, int wave, int lane,
+                                int chunks_valid = 1 << 20) {
   constexpr int RPI = 1024 / ROWB, CPR = ROWB / 16, NI = ROWS / RPI / NW;
   static_assert(ROWS % (RPI * NW) == 0 && NI >= 1, "tile must split evenly over the waves");
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
     const int rbase = (wave * NI + i) * RPI;
     const int r = rbase + lane / CPR;
-    const int c = (lane % CPR) ^ swz_key<ROWB>(r);
+    const int c = min((lane % CPR) ^ swz_key<ROWB>(r), chunks_valid - 1);   // chunks past a short row re-read its last one
     const int rc = min(r, rows_valid - 1);
     __builtin_amdgcn_global_load_lds(ELMO_GLOBAL_PTR(g + (size_t)rc * stride + c * 16), ELMO_LDS_PTR(void, lds_tile + rbase * ROWB),
                                      16, 0, 0);
