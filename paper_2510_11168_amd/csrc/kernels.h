@@ -16,7 +16,11 @@ __device__ inline uint32_t pack2_bf16(float a, float b) {   // hardware round-to
   v[1] = (__bf16)b;
   return __builtin_bit_cast(uint32_t, v);
 }
-__device__ inline float sigmoidf_fast(float z) { return __frcp_rn(1.0f + __expf(-z)); }
+// sigmoid on the transcendental unit: v_exp_f32 and v_rcp_f32 (about 1 ulp each), five instructions.
+// The result is rounded to BF16 right away, so the last FP32 bits only matter next to a BF16 tie.
+__device__ inline float sigmoidf_fast(float z) {
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896341f * z));
+}
 __device__ inline float softplusf_fast(float z) { return fmaxf(z, 0.0f) + __logf(1.0f + __expf(-fabsf(z))); }
 
 template <int NW> __device__ inline float block_sum(float v, float* red /*>= NW floats of LDS*/) {
@@ -241,8 +245,9 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
     const bool row_ok = l0 + row < n;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      g[e] = row_ok ? sigmoidf_fast(z[e]) - (float)((yb >> e) & 1u) : 0.0f;
-      if (LOSS && row_ok && b0 + seg * 8 + e < B) loss += softplusf_fast(z[e]);
+      const float ge = sigmoidf_fast(z[e]) - (float)((yb >> e) & 1u);
+      g[e] = row_ok ? ge : 0.0f;
+      if (LOSS) loss += (row_ok && b0 + seg * 8 + e < B) ? softplusf_fast(z[e]) : 0.0f;
     }
     if (b0 + seg * 8 < Bp) {
       u32x4 o;
