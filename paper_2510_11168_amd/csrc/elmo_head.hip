@@ -58,7 +58,7 @@ int make_plan(int64_t L, int d, int fmt, int64_t chunk, int maxB, int64_t max_nn
   p.Bp_max = round_up(maxB, 64);
   p.tiles_b_max = (p.Bp_max + 255) / 256;      // 256-sample tiles of the matrix products
   p.ntiles = (int)((L + 127) / 128);
-  const int tiles_j = d / 128;
+  const int tiles_j = (d + 255) / 256;           // 256-column tiles of the input-gradient product
   // slices x padded batch of the input-gradient partials: about one workgroup per CU
   p.dx_rows = std::min(65536 / tiles_j + 256 * p.tiles_b_max + 256, 64 * 256 * p.tiles_b_max);
   if (d % 256 == 0) p.dx_rows = std::max(p.dx_rows, 256 / (d / 256) * 128);   // small-batch path: one 128-row slice per label group
@@ -230,7 +230,7 @@ int poll_validation(elmo_head* h) {
 template <bool FP8, bool LOSS>
 void launch_logits(hipStream_t st, int grid, const char* Xa, int a_rows, const char* Wc, int n, int d, int Bp, int B,
                    uint16_t* Gt, const int* binptr, const int2* pos, int tile0, float* loss_slots) {
-  elmo::k_logits<FP8, LOSS><<<grid, elmo::kGemmThreads, elmo::kNtRingBytes, st>>>(Xa, a_rows, Wc, n, d, Bp, B, Gt, binptr, pos,
+  elmo::k_logits<FP8, LOSS><<<grid, elmo::kGemmThreads, elmo::kLogitsSmem, st>>>(Xa, a_rows, Wc, n, d, Bp, B, Gt, binptr, pos,
                                                                              tile0, loss_slots);
 }
 
@@ -238,7 +238,7 @@ template <int FMT>
 void launch_update(hipStream_t st, int grid, bool sr, bool kahan, const char* Gt, const char* XT, char* Wc, uint16_t* Cc,
                    int n, int d, int Bp, float lr, uint64_t seed, uint64_t step, uint64_t elem0) {
 #define ELMO_UPD(SR_, KA_) \
-  elmo::k_update<FMT, SR_, KA_><<<grid, elmo::kGemmThreads, elmo::kNtRingBytes, st>>>(Gt, XT, Wc, Cc, n, d, Bp, lr, seed, step, elem0)
+  elmo::k_update<FMT, SR_, KA_><<<grid, elmo::kGemmThreads, elmo::kUpdateSmem, st>>>(Gt, XT, Wc, Cc, n, d, Bp, lr, seed, step, elem0)
   if (sr && kahan) ELMO_UPD(true, true);
   else if (sr) ELMO_UPD(true, false);
   else if (kahan) ELMO_UPD(false, true);
@@ -283,18 +283,18 @@ int raise_lds_limits() {
   static bool done = false;
   if (done) return 0;
 #define ELMO_ATTR(k, bytes) ELMO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))
-  ELMO_ATTR((elmo::k_logits<true, true>), elmo::kNtRingBytes);
-  ELMO_ATTR((elmo::k_logits<true, false>), elmo::kNtRingBytes);
-  ELMO_ATTR((elmo::k_logits<false, true>), elmo::kNtRingBytes);
-  ELMO_ATTR((elmo::k_logits<false, false>), elmo::kNtRingBytes);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, true, true>), elmo::kNtRingBytes);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, true, false>), elmo::kNtRingBytes);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, false, true>), elmo::kNtRingBytes);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, false, false>), elmo::kNtRingBytes);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, true, true>), elmo::kNtRingBytes);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, true, false>), elmo::kNtRingBytes);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, false, true>), elmo::kNtRingBytes);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, false, false>), elmo::kNtRingBytes);
+  ELMO_ATTR((elmo::k_logits<true, true>), elmo::kLogitsSmem);
+  ELMO_ATTR((elmo::k_logits<true, false>), elmo::kLogitsSmem);
+  ELMO_ATTR((elmo::k_logits<false, true>), elmo::kLogitsSmem);
+  ELMO_ATTR((elmo::k_logits<false, false>), elmo::kLogitsSmem);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, true, true>), elmo::kUpdateSmem);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, true, false>), elmo::kUpdateSmem);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, false, true>), elmo::kUpdateSmem);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, false, false>), elmo::kUpdateSmem);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, true, true>), elmo::kUpdateSmem);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, true, false>), elmo::kUpdateSmem);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, false, true>), elmo::kUpdateSmem);
+  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, false, false>), elmo::kUpdateSmem);
   ELMO_ATTR((elmo::k_dx<true>), elmo::dx_smem_bytes<true>());
   ELMO_ATTR((elmo::k_dx<false>), elmo::dx_smem_bytes<false>());
   ELMO_ATTR((elmo::k_topk_filter<true>), elmo::kNtRingBytes);
@@ -322,7 +322,7 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
   hipStream_t st = (hipStream_t)hip_stream;
   const bool fp8 = p.fmt == ELMO_FP8_E4M3;
   const int d = p.d, Bp = round_up(B, 64), Bp256 = round_up(Bp, 256);
-  const int tiles_b = Bp256 / 256, tiles_j = d / 128;
+  const int tiles_b = Bp256 / 256, tiles_j = (d + 255) / 256;   // 256 x 256 tiles of the matrix products
 
   uint8_t* Xq = fp8 ? (uint8_t*)(h->ws + p.off_xq) : nullptr;
   uint16_t* XT = (uint16_t*)(h->ws + p.off_xt);
@@ -379,7 +379,7 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
   const int a_rows = fp8 ? Bp : B;
   for (int64_t c0 = 0; c0 < p.L; c0 += p.chunk) {
     const int n = (int)std::min<int64_t>(p.chunk, p.L - c0);
-    const int tiles_l = (n + 127) / 128, tiles_l256 = (n + 255) / 256;
+    const int tiles_l = (n + 255) / 256;
     char* Wc = h->W + (size_t)c0 * d * esz;
     uint16_t* Cc = h->comp ? (uint16_t*)h->comp + (size_t)c0 * d : nullptr;
     const int tile0 = (int)(c0 / 128);
@@ -417,7 +417,7 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
     }
     prof.mark(st, CLS_UPDATE);
     {
-      const int grid = tiles_l256 * tiles_j;
+      const int grid = tiles_l * tiles_j;
       const bool sr = p.flags & ELMO_SR, kahan = p.flags & ELMO_KAHAN;
       const uint64_t elem0 = (uint64_t)c0 * (uint64_t)d;
       if (fp8) launch_update<elmo::FMT_E4M3>(st, grid, sr, kahan, (const char*)Gt, (const char*)XT, Wc, Cc, n, d, Bp, lr, seed, step, elem0);

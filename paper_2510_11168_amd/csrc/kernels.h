@@ -116,15 +116,17 @@ __global__ void __launch_bounds__(kThreads) k_label_scatter(const int* __restric
 
 // ---------------------------------------------------------------------------------------------
 // The three matrix products share one shape: 512-thread workgroups (8 waves as 4 x 2, each wave a
-// 64 x 64 block of 32x32 MFMA tiles) computing a 256 x 128 output tile, operands streamed by
-// asynchronous global->LDS loads through a 3-stage ring (tiles.h).  One workgroup per CU: the tile
-// is sized so that the traffic between L2 and LDS per flop is half that of a 128 x 128 tile, which
-// is what bounded the first version of these kernels.
+// 64 x 128 block of 32x32 MFMA tiles) computing a 256 x 256 output tile, operands streamed by
+// asynchronous global->LDS loads through a ring of LDS stages (tiles.h, ring_pipeline_pp).  One
+// workgroup per CU.  On this part the matrix cores and the L2->LDS fill do not overlap for free:
+// a tile of this size halves the fill traffic per flop of a 256 x 128 tile, and the ping-pong
+// issue order of the ring hides most of what is left.
 // ---------------------------------------------------------------------------------------------
 constexpr int kGemmThreads = 512;
 constexpr int kGemmWaves = 8;
 constexpr int kStages = 3;
-constexpr int kNtRingBytes = kStages * (256 + 128) * 128;        // K-contiguous operands, 128-byte slabs
+constexpr int kNtRingBytes = kStages * (256 + 128) * 128;        // top-k filter: 256 x 128 tiles, 3 stages
+constexpr int kWideRingBytes = 2 * (256 + 256) * 128;            // K-contiguous operands, 128-byte slabs, 2 stages
 
 __device__ inline void zero_acc(f32x16 (&acc)[2][2]) {
 #pragma unroll
@@ -134,19 +136,28 @@ __device__ inline void zero_acc(f32x16 (&acc)[2][2]) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 }
+__device__ inline void zero_acc(f32x16 (&acc)[2][4]) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+}
 
 // ---------------------------------------------------------------------------------------------
 // Logits + fused epilogue (Algorithm 1: matmul_fp8, sigmoid_, "-= 1" at the positives).
-// One workgroup computes a 256 (samples) x 128 (labels) tile of Z = Xq W_c^T with FP32
+// One workgroup computes a 256 (samples) x 256 (labels) tile of Z = Xq W_c^T with FP32
 // accumulation over the full embedding width, then G = sigmoid(Z) - Y, and stores G^T[l][b] as
 // BF16 (labels x batch, the layout the paper's logits buffer has).  Z never reaches memory.
 // FP8: both operands E4M3, v_mfma_f32_32x32x64_f8f6f4.  BF16: v_mfma_f32_32x32x16_bf16.
-// Rows of G^T between n and the end of the last 128-label tile are written as zeros (the input
-// gradient product reads whole 64-label slabs).
+// The epilogue handles the tile as two halves of 128 labels (one bin of the positives index
+// each), staged through LDS as FP32.  Rows of G^T between n and the next multiple of 128 are
+// written as zeros (the input-gradient product reads whole 64-label slabs).
 // ---------------------------------------------------------------------------------------------
 constexpr int kZPitch = 260;                                         // floats per staged row (256 + 4)
-constexpr int kLogitsSmem = 128 * kZPitch * 4 + 128 * 8 * 4 + 32;    // Z^T stage + positives mask + reduce
-static_assert(kLogitsSmem <= kNtRingBytes, "epilogue reuses the ring memory");
+constexpr int kLogitsEpiBytes = 128 * kZPitch * 4 + 128 * 8 * 4 + 32;    // Z^T stage + positives mask + reduce
+constexpr int kLogitsSmem = kLogitsEpiBytes > kWideRingBytes ? kLogitsEpiBytes : kWideRingBytes;
 
 template <bool FP8, bool LOSS>
 __global__ void __launch_bounds__(kGemmThreads, 1)
@@ -158,107 +169,112 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
   const int tiles_b = (Bp + 255) >> 8;
   const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
   const int lt = wg / tiles_b, bt = wg % tiles_b;
-  const int b0 = bt << 8, l0 = lt << 7;
+  const int b0 = bt << 8, l0 = lt << 8;
   const size_t rowb = (size_t)d * (FP8 ? 1 : 2);
 
-  f32x16 acc[2][2];
+  f32x16 acc[2][4];
   zero_acc(acc);
-  ring_pipeline<256, 128, 128, 128, kStages, kGemmWaves>(
-      Xa + (size_t)b0 * rowb, rowb, a_rows - b0, 0, 128, Wc + (size_t)l0 * rowb, rowb, n - l0, 0, 128, (int)(rowb >> 7), smem,
-      wave, lane, [&](const char* sa, const char* sb) {
+  ring_pipeline_pp<256, 128, 256, 128, 2, kGemmWaves>(
+      Xa + (size_t)b0 * rowb, rowb, a_rows - b0, 0, 128, 8, Wc + (size_t)l0 * rowb, rowb, n - l0, 0, 128, 8, (int)(rowb >> 7), smem,
+      wave, lane, [&](const char* sa, const char* sb, int half) {
         if (FP8) {
+          i32x8 a[2], b[4];
 #pragma unroll
-          for (int kk = 0; kk < 2; ++kk) {
-            i32x8 a[2], b[2];
+          for (int i = 0; i < 2; ++i) a[i] = frag_fp8(sa, wm * 64 + 32 * i, half, lane);
 #pragma unroll
-            for (int i = 0; i < 2; ++i) a[i] = frag_fp8(sa, wm * 64 + 32 * i, kk, lane);
+          for (int j = 0; j < 4; ++j) b[j] = frag_fp8(sb, wn * 128 + 32 * j, half, lane);
 #pragma unroll
-            for (int j = 0; j < 2; ++j) b[j] = frag_fp8(sb, wn * 64 + 32 * j, kk, lane);
+          for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-              for (int j = 0; j < 2; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 0, 0, 0, 0, 0, 0);
-          }
+            for (int j = 0; j < 4; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 0, 0, 0, 0, 0, 0);
         } else {
 #pragma unroll
-          for (int kk = 0; kk < 4; ++kk) {
-            bf16x8 a[2], b[2];
+          for (int kk = 2 * half; kk < 2 * half + 2; ++kk) {
+            bf16x8 a[2], b[4];
 #pragma unroll
             for (int i = 0; i < 2; ++i) a[i] = frag_bf16(sa, wm * 64 + 32 * i, kk, lane);
 #pragma unroll
-            for (int j = 0; j < 2; ++j) b[j] = frag_bf16(sb, wn * 64 + 32 * j, kk, lane);
+            for (int j = 0; j < 4; ++j) b[j] = frag_bf16(sb, wn * 128 + 32 * j, kk, lane);
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
-              for (int j = 0; j < 2; ++j)
+              for (int j = 0; j < 4; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
           }
         }
       });
 
-  // ---- epilogue: stage Z^T (labels x samples) in LDS as FP32
   float* zs = reinterpret_cast<float*>(smem);
   uint32_t* ym = reinterpret_cast<uint32_t*>(smem + 128 * kZPitch * 4);
   float* red = reinterpret_cast<float*>(smem + 128 * kZPitch * 4 + 128 * 8 * 4);
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int h = 0; h < 2; ++h) {
+    const int lh = l0 + 128 * h;                 // first label of this half
+    if (lh >= n) break;                          // the same for the whole workgroup
+    if (h) __syncthreads();                      // the first half has been read out of the stage
+    // ---- stage Z^T (labels x samples) of this half in LDS as FP32: the waves that own it write
+    if (wn == h) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int l = wn * 64 + 32 * j + (lane & 31);
-        const int b = wm * 64 + 32 * i + 8 * q + 4 * (lane >> 5);
-        f32x4 z;
-        z[0] = acc[i][j][4 * q]; z[1] = acc[i][j][4 * q + 1]; z[2] = acc[i][j][4 * q + 2]; z[3] = acc[i][j][4 * q + 3];
-        *reinterpret_cast<f32x4*>(zs + l * kZPitch + b) = z;
-      }
-  for (int i = tid; i < 128 * 8; i += kGemmThreads) ym[i] = 0u;
-  __syncthreads();
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int l = 32 * j + (lane & 31);
+            const int b = wm * 64 + 32 * i + 8 * q + 4 * (lane >> 5);
+            f32x4 z;
+            z[0] = acc[i][j][4 * q]; z[1] = acc[i][j][4 * q + 1]; z[2] = acc[i][j][4 * q + 2]; z[3] = acc[i][j][4 * q + 3];
+            *reinterpret_cast<f32x4*>(zs + l * kZPitch + b) = z;
+          }
+    }
+    for (int i = tid; i < 128 * 8; i += kGemmThreads) ym[i] = 0u;
+    __syncthreads();
 
-  // ---- positives of this label tile that fall into this batch tile
-  float loss = 0.0f;
-  {
-    const int gt = tile0 + lt;
-    const int p0 = binptr[gt], p1 = binptr[gt + 1];
-    for (int p = p0 + tid; p < p1; p += kGemmThreads) {
-      const int2 e = pos[p];
-      const int lr_ = e.x - (gt << 7), br = e.y - b0;
-      if (br >= 0 && br < 256 && lr_ >= 0 && lr_ < 128) {
-        atomicOr(&ym[lr_ * 8 + (br >> 5)], 1u << (br & 31));
-        if (LOSS) loss -= zs[lr_ * kZPitch + br];
+    // ---- positives of this 128-label bin that fall into this batch tile
+    float loss = 0.0f;
+    const int gt = tile0 + 2 * lt + h;
+    {
+      const int p0 = binptr[gt], p1 = binptr[gt + 1];
+      for (int p = p0 + tid; p < p1; p += kGemmThreads) {
+        const int2 e = pos[p];
+        const int lr_ = e.x - (gt << 7), br = e.y - b0;
+        if (br >= 0 && br < 256 && lr_ >= 0 && lr_ < 128) {
+          atomicOr(&ym[lr_ * 8 + (br >> 5)], 1u << (br & 31));
+          if (LOSS) loss -= zs[lr_ * kZPitch + br];
+        }
       }
     }
-  }
-  __syncthreads();
+    __syncthreads();
 
-  // ---- G = sigmoid(Z) - Y, BF16, coalesced rows of G^T
+    // ---- G = sigmoid(Z) - Y, BF16, coalesced rows of G^T
 #pragma unroll
-  for (int it = 0; it < 8; ++it) {
-    const int id = it * kGemmThreads + tid;
-    const int row = id >> 5, seg = id & 31;
-    const f32x4 z0 = *reinterpret_cast<const f32x4*>(zs + row * kZPitch + seg * 8);
-    const f32x4 z1 = *reinterpret_cast<const f32x4*>(zs + row * kZPitch + seg * 8 + 4);
-    const uint32_t yb = (ym[row * 8 + (seg >> 2)] >> ((seg & 3) * 8)) & 0xFFu;
-    const float z[8] = {z0[0], z0[1], z0[2], z0[3], z1[0], z1[1], z1[2], z1[3]};
-    float g[8];
-    const bool row_ok = l0 + row < n;
+    for (int it = 0; it < 8; ++it) {
+      const int id = it * kGemmThreads + tid;
+      const int row = id >> 5, seg = id & 31;
+      const f32x4 z0 = *reinterpret_cast<const f32x4*>(zs + row * kZPitch + seg * 8);
+      const f32x4 z1 = *reinterpret_cast<const f32x4*>(zs + row * kZPitch + seg * 8 + 4);
+      const uint32_t yb = (ym[row * 8 + (seg >> 2)] >> ((seg & 3) * 8)) & 0xFFu;
+      const float z[8] = {z0[0], z0[1], z0[2], z0[3], z1[0], z1[1], z1[2], z1[3]};
+      float g[8];
+      const bool row_ok = lh + row < n;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float ge = sigmoidf_fast(z[e]) - (float)((yb >> e) & 1u);
-      g[e] = row_ok ? ge : 0.0f;
-      if (LOSS) loss += (row_ok && b0 + seg * 8 + e < B) ? softplusf_fast(z[e]) : 0.0f;
+      for (int e = 0; e < 8; ++e) {
+        const float ge = sigmoidf_fast(z[e]) - (float)((yb >> e) & 1u);
+        g[e] = row_ok ? ge : 0.0f;
+        if (LOSS) loss += (row_ok && b0 + seg * 8 + e < B) ? softplusf_fast(z[e]) : 0.0f;
+      }
+      if (b0 + seg * 8 < Bp) {
+        u32x4 o;
+        o[0] = pack2_bf16(g[0], g[1]); o[1] = pack2_bf16(g[2], g[3]);
+        o[2] = pack2_bf16(g[4], g[5]); o[3] = pack2_bf16(g[6], g[7]);
+        *reinterpret_cast<u32x4*>(Gt + (size_t)(lh + row) * Bp + b0 + seg * 8) = o;
+      }
     }
-    if (b0 + seg * 8 < Bp) {
-      u32x4 o;
-      o[0] = pack2_bf16(g[0], g[1]); o[1] = pack2_bf16(g[2], g[3]);
-      o[2] = pack2_bf16(g[4], g[5]); o[3] = pack2_bf16(g[6], g[7]);
-      *reinterpret_cast<u32x4*>(Gt + (size_t)(l0 + row) * Bp + b0 + seg * 8) = o;
+    if (LOSS) {
+      const float s = block_sum<kGemmWaves>(loss, red);
+      if (tid == 0) loss_slots[(size_t)gt * tiles_b + bt] = s;
     }
-  }
-  if (LOSS) {
-    const float s = block_sum<kGemmWaves>(loss, red);
-    if (tid == 0) loss_slots[(size_t)(tile0 + lt) * tiles_b + bt] = s;
   }
 }
 
@@ -267,10 +283,11 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
 // weights as they are before this step's update.  The contraction runs over the labels; both
 // operands are stored label-major, so fragments come from transposing LDS reads and E4M3
 // weights are widened to BF16 in registers (no up-cast copy of W in memory).
-// Workgroup = 256 samples x 128 embedding columns x one slice s of the chunk's labels; the FP32
+// Workgroup = 256 samples x 256 embedding columns x one slice s of the chunk's labels; the FP32
 // partial goes to dXacc[s] (owned by exactly this workgroup, so plain read-modify-write).
 // Label rows beyond n inside the last 64-label slab are harmless: G^T holds zeros there and the
-// weight rows are re-reads of row n-1.
+// weight rows are re-reads of row n-1.  Columns beyond d in the last column tile re-read the
+// row's last 16 bytes and are not stored.
 // ---------------------------------------------------------------------------------------------
 // dst[32 x 32 block, row pitch d] += one 32x32 accumulator tile.  All sixteen loads are issued
 // before the first store, so the read-modify-write costs one memory round trip, not sixteen.
@@ -282,43 +299,45 @@ __device__ inline void add_acc_to_global(float* __restrict__ dst, int d, int lan
   for (int v = 0; v < 16; ++v) dst[(size_t)acc_row(v, lane) * d + (lane & 31)] = old[v] + acc[v];
 }
 
-template <bool FP8> constexpr int dx_smem_bytes() { return kStages * (64 * 512 + 64 * (FP8 ? 128 : 256)); }
+// ring stage: [G^T slab 64 labels x 256 samples (512-byte rows) | W slab 64 labels x 256 columns]
+template <bool FP8> constexpr int dx_stages() { return FP8 ? 3 : 2; }
+template <bool FP8> constexpr int dx_smem_bytes() { return dx_stages<FP8>() * (64 * 512 + 64 * (FP8 ? 256 : 512)); }
 
 template <bool FP8>
 __global__ void __launch_bounds__(kGemmThreads, 1)
 k_dx(const char* __restrict__ Gt, const char* __restrict__ Wc, float* __restrict__ dXacc, int n, int d, int Bp,
      int Bp256, int S) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  constexpr int WROWB = FP8 ? 128 : 256;
+  constexpr int ESZ = FP8 ? 1 : 2, WROWB = 256 * ESZ;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
-  const int tiles_b = Bp256 >> 8, tiles_j = d >> 7;
+  const int tiles_b = Bp256 >> 8, tiles_j = (d + 255) >> 8;
   const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
   const int jt = wg % tiles_j, bt = (wg / tiles_j) % tiles_b, s = wg / (tiles_j * tiles_b);
-  const int b0 = bt << 8, j0 = jt << 7;
+  const int b0 = bt << 8, j0 = jt << 8;
   const int ksteps = (n + 63) >> 6, per = (ksteps + S - 1) / S;
   const int ks0 = s * per, ks1 = min(ks0 + per, ksteps);
   if (ks0 >= ks1) return;
-  const size_t strideA = (size_t)Bp * 2, strideB = (size_t)d * (FP8 ? 1 : 2);
+  const size_t strideA = (size_t)Bp * 2, strideB = (size_t)d * ESZ;
 
-  f32x16 acc[2][2];
+  f32x16 acc[2][4];
   zero_acc(acc);
-  ring_pipeline<64, 512, 64, WROWB, kStages, kGemmWaves>(
-      Gt + (size_t)ks0 * 64 * strideA + (size_t)b0 * 2, strideA, (ksteps - ks0) * 64 /* zero rows past n are real */, 64, 64 * strideA,
-      Wc + (size_t)ks0 * 64 * strideB + (size_t)j0 * (FP8 ? 1 : 2), strideB, n - ks0 * 64, 64, 64 * strideB, ks1 - ks0, smem, wave,
-      lane, [&](const char* sa, const char* sb) {
+  ring_pipeline_pp<64, 512, 64, WROWB, dx_stages<FP8>(), kGemmWaves>(
+      Gt + (size_t)ks0 * 64 * strideA + (size_t)b0 * 2, strideA, (ksteps - ks0) * 64 /* zero rows past n are real */, 64, 64 * strideA, 32,
+      Wc + (size_t)ks0 * 64 * strideB + (size_t)j0 * ESZ, strideB, n - ks0 * 64, 64, 64 * strideB, min(256, d - j0) * ESZ / 16,
+      ks1 - ks0, smem, wave, lane, [&](const char* sa, const char* sb, int half) {
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          bf16x8 a[2], b[2];
+        for (int kk = 2 * half; kk < 2 * half + 2; ++kk) {
+          bf16x8 a[2], b[4];
 #pragma unroll
           for (int i = 0; i < 2; ++i) a[i] = frag_tr_bf16<512>(sa, 16 * kk, wm * 64 + 32 * i, lane);
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
-            b[j] = FP8 ? frag_tr_fp8<WROWB>(sb, 16 * kk, wn * 64 + 32 * j, lane)
-                       : frag_tr_bf16<WROWB>(sb, 16 * kk, wn * 64 + 32 * j, lane);
+          for (int j = 0; j < 4; ++j)
+            b[j] = FP8 ? frag_tr_fp8<WROWB>(sb, 16 * kk, wn * 128 + 32 * j, lane)
+                       : frag_tr_bf16<WROWB>(sb, 16 * kk, wn * 128 + 32 * j, lane);
 #pragma unroll
           for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < 4; ++j)
               acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
         }
       });
@@ -326,8 +345,10 @@ k_dx(const char* __restrict__ Gt, const char* __restrict__ Wc, float* __restrict
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-      add_acc_to_global(out + (size_t)(b0 + wm * 64 + 32 * i) * d + j0 + wn * 64 + 32 * j, d, lane, acc[i][j]);
+    for (int j = 0; j < 4; ++j) {
+      const int col = j0 + wn * 128 + 32 * j;
+      if (col < d) add_acc_to_global(out + (size_t)(b0 + wm * 64 + 32 * i) * d + col, d, lane, acc[i][j]);
+    }
 }
 
 // dX_out = BF16(sum over label slices of the FP32 partials); loss_out = sum of the tile losses.
@@ -353,14 +374,15 @@ __global__ void __launch_bounds__(kThreads) k_finalize(const float* __restrict__
 
 // ---------------------------------------------------------------------------------------------
 // Fused weight gradient + SGD + (Kahan) + rounding, in place (Algorithm 1, fuse_update).
-// One workgroup owns a 256 (labels) x 128 (columns) tile of W_c: grad = G^T X accumulated in FP32
+// One workgroup owns a 256 (labels) x 256 (columns) tile of W_c: grad = G^T X accumulated in FP32
 // over the whole batch on the BF16 matrix cores, then per element the FP32 update of
 // numerics.h, rounded stochastically (Eq. 1) or to nearest, written back in the storage format.
-// The weight gradient only ever exists as MFMA accumulators and one LDS tile.
+// The weight gradient only ever exists as MFMA accumulators and one LDS tile (staged in two
+// halves of 128 columns).
 // ---------------------------------------------------------------------------------------------
 constexpr int kGPitch = 132;
-constexpr int kUpdateSmem = 256 * kGPitch * 4;
-static_assert(kUpdateSmem <= kNtRingBytes, "epilogue reuses the ring memory");
+constexpr int kUpdateEpiBytes = 256 * kGPitch * 4;
+constexpr int kUpdateSmem = kUpdateEpiBytes > kWideRingBytes ? kUpdateEpiBytes : kWideRingBytes;
 
 // Sixteen consecutive elements of one weight row: storage bits in, storage bits out.
 // E4M3: w[0..3] hold 4 codes each; BF16: w[0..7] hold 2 patterns each.  c[0..7]: BF16 compensation.
@@ -420,95 +442,107 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
   constexpr int ESZ = FMT == FMT_E4M3 ? 1 : 2;
   constexpr int WQ = FMT == FMT_E4M3 ? 1 : 2;       // 16-byte loads per 16 weights
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
-  const int tiles_j = d >> 7;
+  const int tiles_j = (d + 255) >> 8;
   const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
   const int lt = wg / tiles_j, jt = wg % tiles_j;
-  const int l0 = lt << 8, j0 = jt << 7;
+  const int l0 = lt << 8, j0 = jt << 8;
   const size_t stride = (size_t)Bp * 2;
-  const int va = n - l0;
+  const bool two_halves = j0 + 128 < d;             // the last column tile of a d = 128 (mod 256) head has one
 
-  // This thread's share of the weight (and compensation) tile, fetched before the product so the
-  // read-modify-write never waits on memory: 4 passes x 16 consecutive columns of one row.
+  // This thread's share of a 256 x 128 half of the weight (and compensation) tile: 4 passes x 16
+  // consecutive columns of one row.  The first half is fetched before the product, the second
+  // one pass at a time while the first half is being updated, so the read-modify-write does not
+  // wait on memory.
   const int urow = tid >> 3, useg = tid & 7;
   u32x4 wreg[4][WQ];
   u32x4 creg[4][2];
-#pragma unroll
-  for (int it = 0; it < 4; ++it) {
+  auto fetch = [&](int it, int jh) {
     const int l = min(l0 + it * 64 + urow, n - 1);
-    const size_t eoff = (size_t)l * d + j0 + useg * 16;
+    const size_t eoff = (size_t)l * d + jh + useg * 16;
 #pragma unroll
     for (int q = 0; q < WQ; ++q) wreg[it][q] = *reinterpret_cast<const u32x4*>(Wc + eoff * ESZ + 16 * q);
     if (KAHAN) {
       creg[it][0] = *reinterpret_cast<const u32x4*>(Cc + eoff);
       creg[it][1] = *reinterpret_cast<const u32x4*>(Cc + eoff + 8);
     }
-  }
+  };
+#pragma unroll
+  for (int it = 0; it < 4; ++it) fetch(it, j0);
 
-  f32x16 acc[2][2];
+  f32x16 acc[2][4];
   zero_acc(acc);
   // K loop over the batch in slabs of 64 samples
-  ring_pipeline<256, 128, 128, 128, kStages, kGemmWaves>(
-      Gt + (size_t)l0 * stride, stride, va, 0, 128, XT + (size_t)j0 * stride, stride, 128, 0, 128, Bp >> 6, smem, wave, lane,
-      [&](const char* sa, const char* sb) {
+  ring_pipeline_pp<256, 128, 256, 128, 2, kGemmWaves>(
+      Gt + (size_t)l0 * stride, stride, n - l0, 0, 128, 8, XT + (size_t)j0 * stride, stride, d - j0, 0, 128, 8, Bp >> 6, smem, wave,
+      lane, [&](const char* sa, const char* sb, int half) {
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          bf16x8 a[2], b[2];
+        for (int kk = 2 * half; kk < 2 * half + 2; ++kk) {
+          bf16x8 a[2], b[4];
 #pragma unroll
           for (int i = 0; i < 2; ++i) a[i] = frag_bf16(sa, wm * 64 + 32 * i, kk, lane);
 #pragma unroll
-          for (int j = 0; j < 2; ++j) b[j] = frag_bf16(sb, wn * 64 + 32 * j, kk, lane);
+          for (int j = 0; j < 4; ++j) b[j] = frag_bf16(sb, wn * 128 + 32 * j, kk, lane);
 #pragma unroll
           for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < 4; ++j)
               acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
         }
       });
 
-  // ---- stage the gradient tile [label][column] in LDS
   float* gs = reinterpret_cast<float*>(smem);
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int h = 0; h < 2; ++h) {
+    if (h && !two_halves) break;                   // the same for the whole workgroup
+    const int jh = j0 + 128 * h;
+    if (h) __syncthreads();                        // the first half has been read out of the stage
+    // ---- stage this half of the gradient tile [label][column] in LDS: the waves that own it write
+    if (wn == h) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v)
-        gs[(wm * 64 + 32 * i + acc_row(v, lane)) * kGPitch + wn * 64 + 32 * j + (lane & 31)] = acc[i][j][v];
-  __syncthreads();
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            gs[(wm * 64 + 32 * i + acc_row(v, lane)) * kGPitch + 32 * j + (lane & 31)] = acc[i][j][v];
+    }
+    __syncthreads();
 
-  // ---- per-element update
+    // ---- per-element update
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int row = it * 64 + urow;
-    const int l = l0 + row;
-    if (l >= n) continue;
-    const size_t eoff = (size_t)l * d + j0 + useg * 16;
-    uint32_t w[8], c[8];
+    for (int it = 0; it < 4; ++it) {
+      const int row = it * 64 + urow;
+      const int l = l0 + row;
+      uint32_t w[8], c[8];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      w[q] = wreg[it][0][q];
-      if (WQ == 2) w[4 + q] = wreg[it][WQ - 1][q];
-      if (KAHAN) { c[q] = creg[it][0][q]; c[4 + q] = creg[it][1][q]; }
-    }
-    float g[16];
+      for (int q = 0; q < 4; ++q) {
+        w[q] = wreg[it][0][q];
+        if (WQ == 2) w[4 + q] = wreg[it][WQ - 1][q];
+        if (KAHAN) { c[q] = creg[it][0][q]; c[4 + q] = creg[it][1][q]; }
+      }
+      if (h == 0 && two_halves) fetch(it, j0 + 128);
+      if (l >= n) continue;
+      const size_t eoff = (size_t)l * d + jh + useg * 16;
+      float g[16];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const f32x4 t = *reinterpret_cast<const f32x4*>(gs + row * kGPitch + useg * 16 + 4 * q);
-      g[4 * q] = t[0]; g[4 * q + 1] = t[1]; g[4 * q + 2] = t[2]; g[4 * q + 3] = t[3];
-    }
-    U4 rb[2];
-    if (SR) {
-      const uint64_t blk = (elem0 + eoff) >> 3;
-      rb[0] = sr_block(blk, seed, step);
-      rb[1] = sr_block(blk + 1, seed, step);
-    }
-    update16<FMT, SR, KAHAN>(w, c, g, lr, rb);
-    char* wp = Wc + eoff * ESZ;
-    *reinterpret_cast<u32x4*>(wp) = u32x4{w[0], w[1], w[2], w[3]};
-    if (WQ == 2) *reinterpret_cast<u32x4*>(wp + 16) = u32x4{w[4], w[5], w[6], w[7]};
-    if (KAHAN) {
-      *reinterpret_cast<u32x4*>(Cc + eoff) = u32x4{c[0], c[1], c[2], c[3]};
-      *reinterpret_cast<u32x4*>(Cc + eoff + 8) = u32x4{c[4], c[5], c[6], c[7]};
+      for (int q = 0; q < 4; ++q) {
+        const f32x4 t = *reinterpret_cast<const f32x4*>(gs + row * kGPitch + useg * 16 + 4 * q);
+        g[4 * q] = t[0]; g[4 * q + 1] = t[1]; g[4 * q + 2] = t[2]; g[4 * q + 3] = t[3];
+      }
+      U4 rb[2];
+      if (SR) {
+        const uint64_t blk = (elem0 + eoff) >> 3;
+        rb[0] = sr_block(blk, seed, step);
+        rb[1] = sr_block(blk + 1, seed, step);
+      }
+      update16<FMT, SR, KAHAN>(w, c, g, lr, rb);
+      char* wp = Wc + eoff * ESZ;
+      *reinterpret_cast<u32x4*>(wp) = u32x4{w[0], w[1], w[2], w[3]};
+      if (WQ == 2) *reinterpret_cast<u32x4*>(wp + 16) = u32x4{w[4], w[5], w[6], w[7]};
+      if (KAHAN) {
+        *reinterpret_cast<u32x4*>(Cc + eoff) = u32x4{c[0], c[1], c[2], c[3]};
+        *reinterpret_cast<u32x4*>(Cc + eoff + 8) = u32x4{c[4], c[5], c[6], c[7]};
+      }
     }
   }
 }
