@@ -212,7 +212,7 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
   for (int h = 0; h < 2; ++h) {
     const int lh = l0 + 128 * h;                 // first label of this half
     if (lh >= n) break;                          // the same for the whole workgroup
-    if (h) __syncthreads();                      // the first half has been read out of the stage
+    if (h) barrier_lds();                        // the first half has been read out of the stage (no wait for its stores)
     // ---- stage Z^T (labels x samples) of this half in LDS as FP32: the waves that own it write
     if (wn == h) {
 #pragma unroll
@@ -229,7 +229,7 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
           }
     }
     for (int i = tid; i < 128 * 8; i += kGemmThreads) ym[i] = 0u;
-    __syncthreads();
+    barrier_lds();
 
     // ---- positives of this 128-label bin that fall into this batch tile
     float loss = 0.0f;
@@ -245,7 +245,7 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
         }
       }
     }
-    __syncthreads();
+    barrier_lds();
 
     // ---- G = sigmoid(Z) - Y, BF16, coalesced rows of G^T
 #pragma unroll
@@ -495,7 +495,7 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
   for (int h = 0; h < 2; ++h) {
     if (h && !two_halves) break;                   // the same for the whole workgroup
     const int jh = j0 + 128 * h;
-    if (h) __syncthreads();                        // the first half has been read out of the stage
+    if (h) barrier_lds();                          // the first half has been read out of the stage (no wait for its stores)
     // ---- stage this half of the gradient tile [label][column] in LDS: the waves that own it write
     if (wn == h) {
 #pragma unroll
@@ -506,7 +506,7 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
           for (int v = 0; v < 16; ++v)
             gs[(wm * 64 + 32 * i + acc_row(v, lane)) * kGPitch + 32 * j + (lane & 31)] = acc[i][j][v];
     }
-    __syncthreads();
+    barrier_lds();
 
     // ---- per-element update
 #pragma unroll
