@@ -30,12 +30,12 @@ PEAK_BF16_TFLOPS = 2500.0
 PEAK_FP8_TFLOPS = 5000.0
 
 
-def profiled_traffic(kernel: str, workload: str):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary of this
-    workload (FETCH_SIZE and WRITE_SIZE, scaled by the factors measured in the same runs), or None."""
-    if workload != "xl":
+def profiled_traffic(kernel: str, profile: str | None, fused: bool = False):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary `profile` under
+    profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by the factors measured in the same runs), or None."""
+    if profile is None:
         return None
-    path = os.path.join(ROOT, "profiles", "head_step_xl_fp8_B1024.txt")
+    path = os.path.join(ROOT, "profiles", profile)
     try:
         lines = open(path).read().splitlines()
     except OSError:
@@ -45,7 +45,7 @@ def profiled_traffic(kernel: str, workload: str):
         ln = ln.strip()
         if ln.startswith("FETCH_SIZE:") or ln.startswith("WRITE_SIZE:"):
             scale[ln.split(":")[0]] = float(ln.rsplit("by", 1)[1])
-    name = {"logits": "k_logits", "dx": "k_dx", "update": "k_update"}[kernel]
+    name = {"logits": "k_logits", "dx": "k_dx", "update": "k_dx_update" if fused else "k_update"}[kernel]
     for ln in lines:
         f = ln.split()
         if len(f) >= 4 and f[0].startswith(name + "<") and "FETCH" not in ln:
@@ -184,9 +184,14 @@ def main():
                 "peak": (PEAK_FP8_TFLOPS if (dom == "logits" and fp8) else PEAK_BF16_TFLOPS), "frac": kd["mfma_frac"]}
     else:
         roof = {"bound": "hbm", "achieved": kd["algo_gbs"], "unit": "GB/s", "peak": PEAK_HBM_GBS, "frac": kd["hbm_frac"]}
-    unchanged = not (args.batch or args.chunk or args.no_kahan or args.no_dx)
-    roof.update({"kernel": dom, "avg_launch_ms": kd["avg_ms"],
-                 "traffic": profiled_traffic(dom, args.workload) if unchanged else None})
+    # committed counter summaries exist for exactly these two workloads
+    profile = None
+    if not args.no_dx and not args.no_kahan:
+        if args.workload == "xl" and not (args.batch or args.chunk):
+            profile = "head_step_xl_fp8_B1024.txt"
+        elif args.workload == "xl_sweep" and B == 128 and cfg.chunk == 262144:
+            profile = "head_step_xl_fp8_B128.txt"
+    roof.update({"kernel": dom, "avg_launch_ms": kd["avg_ms"], "traffic": profiled_traffic(dom, profile, fused)})
 
     # whole-step figures of the headline metric: flop/s against the FP8 MFMA peak (6 B L d flop per
     # step) and weight read-modify-write bytes against HBM peak
