@@ -227,11 +227,18 @@ int poll_validation(elmo_head* h) {
   return 0;
 }
 
+template <bool FP8, bool LOSS, int TB>
+void launch_logits_tb(hipStream_t st, int grid, const char* Xa, int a_rows, const char* Wc, int n, int d, int Bp, int B,
+                      uint16_t* Gt, const int* binptr, const int2* pos, int tile0, float* loss_slots) {
+  elmo::k_logits<FP8, LOSS, TB><<<grid, elmo::kGemmThreads, elmo::logits_smem<TB>(), st>>>(Xa, a_rows, Wc, n, d, Bp, B, Gt, binptr,
+                                                                                       pos, tile0, loss_slots);
+}
+// tb = rows of the batch tile (256, or 128 when the whole padded batch fits in 128 rows)
 template <bool FP8, bool LOSS>
-void launch_logits(hipStream_t st, int grid, const char* Xa, int a_rows, const char* Wc, int n, int d, int Bp, int B,
+void launch_logits(hipStream_t st, int tb, int grid, const char* Xa, int a_rows, const char* Wc, int n, int d, int Bp, int B,
                    uint16_t* Gt, const int* binptr, const int2* pos, int tile0, float* loss_slots) {
-  elmo::k_logits<FP8, LOSS><<<grid, elmo::kGemmThreads, elmo::kLogitsSmem, st>>>(Xa, a_rows, Wc, n, d, Bp, B, Gt, binptr, pos,
-                                                                             tile0, loss_slots);
+  if (tb == 128) launch_logits_tb<FP8, LOSS, 128>(st, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, binptr, pos, tile0, loss_slots);
+  else launch_logits_tb<FP8, LOSS, 256>(st, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, binptr, pos, tile0, loss_slots);
 }
 
 template <int FMT>
@@ -283,10 +290,14 @@ int raise_lds_limits() {
   static bool done = false;
   if (done) return 0;
 #define ELMO_ATTR(k, bytes) ELMO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))
-  ELMO_ATTR((elmo::k_logits<true, true>), elmo::kLogitsSmem);
-  ELMO_ATTR((elmo::k_logits<true, false>), elmo::kLogitsSmem);
-  ELMO_ATTR((elmo::k_logits<false, true>), elmo::kLogitsSmem);
-  ELMO_ATTR((elmo::k_logits<false, false>), elmo::kLogitsSmem);
+  ELMO_ATTR((elmo::k_logits<true, true, 256>), elmo::logits_smem<256>());
+  ELMO_ATTR((elmo::k_logits<true, true, 128>), elmo::logits_smem<128>());
+  ELMO_ATTR((elmo::k_logits<true, false, 256>), elmo::logits_smem<256>());
+  ELMO_ATTR((elmo::k_logits<true, false, 128>), elmo::logits_smem<128>());
+  ELMO_ATTR((elmo::k_logits<false, true, 256>), elmo::logits_smem<256>());
+  ELMO_ATTR((elmo::k_logits<false, true, 128>), elmo::logits_smem<128>());
+  ELMO_ATTR((elmo::k_logits<false, false, 256>), elmo::logits_smem<256>());
+  ELMO_ATTR((elmo::k_logits<false, false, 128>), elmo::logits_smem<128>());
   ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, true, true>), elmo::kUpdateSmem);
   ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, true, false>), elmo::kUpdateSmem);
   ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, false, true>), elmo::kUpdateSmem);
@@ -385,13 +396,14 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
     const int tile0 = (int)(c0 / 128);
     prof.mark(st, CLS_LOGITS);
     {
-      const int grid = tiles_l * tiles_b;
+      const int tb = Bp <= 128 ? 128 : 256;        // rows of the logits kernel's batch tile
+      const int grid = tiles_l * ((Bp + tb - 1) / tb);
       if (fp8) {
-        if (loss_out) launch_logits<true, true>(st, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots);
-        else launch_logits<true, false>(st, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots);
+        if (loss_out) launch_logits<true, true>(st, tb, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots);
+        else launch_logits<true, false>(st, tb, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots);
       } else {
-        if (loss_out) launch_logits<false, true>(st, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots);
-        else launch_logits<false, false>(st, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots);
+        if (loss_out) launch_logits<false, true>(st, tb, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots);
+        else launch_logits<false, false>(st, tb, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots);
       }
       if (int rc = check_launch("k_logits")) return rc;
     }

@@ -155,80 +155,88 @@ __device__ inline void zero_acc(f32x16 (&acc)[2][4]) {
 // each), staged through LDS as FP32.  Rows of G^T between n and the next multiple of 128 are
 // written as zeros (the input-gradient product reads whole 64-label slabs).
 // ---------------------------------------------------------------------------------------------
-constexpr int kZPitch = 260;                                         // floats per staged row (256 + 4)
-constexpr int kLogitsEpiBytes = 128 * kZPitch * 4 + 128 * 8 * 4 + 32;    // Z^T stage + positives mask + reduce
-constexpr int kLogitsSmem = kLogitsEpiBytes > kWideRingBytes ? kLogitsEpiBytes : kWideRingBytes;
+// TB = rows of the batch tile: 256, or 128 for padded batches of at most 128 rows (waves as 2 x 4,
+// 64 x 64 outputs each, three ring stages), where half of a 256-row tile would be padding.
+template <int TB> constexpr int logits_zpitch() { return TB + 4; }                  // floats per staged row
+template <int TB> constexpr int logits_stages() { return TB == 256 ? 2 : 3; }
+template <int TB> constexpr int logits_smem() {
+  constexpr int epi = 128 * logits_zpitch<TB>() * 4 + 128 * (TB / 32) * 4 + 32;     // Z^T stage + positives mask + reduce
+  constexpr int ring = logits_stages<TB>() * (TB + 256) * 128;
+  return epi > ring ? epi : ring;
+}
 
-template <bool FP8, bool LOSS>
+template <bool FP8, bool LOSS, int TB>
 __global__ void __launch_bounds__(kGemmThreads, 1)
 k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, int n, int d, int Bp, int B,
          uint16_t* __restrict__ Gt, const int* __restrict__ binptr, const int2* __restrict__ pos, int tile0,
          float* __restrict__ loss_slots) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
-  const int tiles_b = (Bp + 255) >> 8;
+  constexpr int WGN = TB == 256 ? 2 : 4, FN = 8 / WGN;      // waves along the labels, 32-label blocks per wave
+  constexpr int ZP = logits_zpitch<TB>(), MW = TB / 32, SEGS = TB / 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave / WGN, wn = wave % WGN;
+  const int tiles_b = (Bp + TB - 1) / TB;
   const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
   const int lt = wg / tiles_b, bt = wg % tiles_b;
-  const int b0 = bt << 8, l0 = lt << 8;
+  const int b0 = bt * TB, l0 = lt << 8;
   const size_t rowb = (size_t)d * (FP8 ? 1 : 2);
 
-  f32x16 acc[2][4];
+  f32x16 acc[2][FN];
   zero_acc(acc);
-  ring_pipeline_pp<256, 128, 256, 128, 2, kGemmWaves>(
+  ring_pipeline_pp<TB, 128, 256, 128, logits_stages<TB>(), kGemmWaves>(
       Xa + (size_t)b0 * rowb, rowb, a_rows - b0, 0, 128, 8, Wc + (size_t)l0 * rowb, rowb, n - l0, 0, 128, 8, (int)(rowb >> 7), smem,
       wave, lane, [&](const char* sa, const char* sb, int half) {
         if (FP8) {
-          i32x8 a[2], b[4];
+          i32x8 a[2], b[FN];
 #pragma unroll
           for (int i = 0; i < 2; ++i) a[i] = frag_fp8(sa, wm * 64 + 32 * i, half, lane);
 #pragma unroll
-          for (int j = 0; j < 4; ++j) b[j] = frag_fp8(sb, wn * 128 + 32 * j, half, lane);
+          for (int j = 0; j < FN; ++j) b[j] = frag_fp8(sb, wn * 32 * FN + 32 * j, half, lane);
 #pragma unroll
           for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < FN; ++j)
               acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 0, 0, 0, 0, 0, 0);
         } else {
 #pragma unroll
           for (int kk = 2 * half; kk < 2 * half + 2; ++kk) {
-            bf16x8 a[2], b[4];
+            bf16x8 a[2], b[FN];
 #pragma unroll
             for (int i = 0; i < 2; ++i) a[i] = frag_bf16(sa, wm * 64 + 32 * i, kk, lane);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) b[j] = frag_bf16(sb, wn * 128 + 32 * j, kk, lane);
+            for (int j = 0; j < FN; ++j) b[j] = frag_bf16(sb, wn * 32 * FN + 32 * j, kk, lane);
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
-              for (int j = 0; j < 4; ++j)
+              for (int j = 0; j < FN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
           }
         }
       });
 
   float* zs = reinterpret_cast<float*>(smem);
-  uint32_t* ym = reinterpret_cast<uint32_t*>(smem + 128 * kZPitch * 4);
-  float* red = reinterpret_cast<float*>(smem + 128 * kZPitch * 4 + 128 * 8 * 4);
+  uint32_t* ym = reinterpret_cast<uint32_t*>(smem + 128 * ZP * 4);
+  float* red = reinterpret_cast<float*>(smem + 128 * ZP * 4 + 128 * MW * 4);
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const int lh = l0 + 128 * h;                 // first label of this half
     if (lh >= n) break;                          // the same for the whole workgroup
     if (h) barrier_lds();                        // the first half has been read out of the stage (no wait for its stores)
     // ---- stage Z^T (labels x samples) of this half in LDS as FP32: the waves that own it write
-    if (wn == h) {
+    if (wn * FN / 4 == h) {
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < FN; ++j)
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
-            const int l = 32 * j + (lane & 31);
+            const int l = (wn * 32 * FN + 32 * j + (lane & 31)) & 127;
             const int b = wm * 64 + 32 * i + 8 * q + 4 * (lane >> 5);
             f32x4 z;
             z[0] = acc[i][j][4 * q]; z[1] = acc[i][j][4 * q + 1]; z[2] = acc[i][j][4 * q + 2]; z[3] = acc[i][j][4 * q + 3];
-            *reinterpret_cast<f32x4*>(zs + l * kZPitch + b) = z;
+            *reinterpret_cast<f32x4*>(zs + l * ZP + b) = z;
           }
     }
-    for (int i = tid; i < 128 * 8; i += kGemmThreads) ym[i] = 0u;
+    for (int i = tid; i < 128 * MW; i += kGemmThreads) ym[i] = 0u;
     barrier_lds();
 
     // ---- positives of this 128-label bin that fall into this batch tile
@@ -239,9 +247,9 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
       for (int p = p0 + tid; p < p1; p += kGemmThreads) {
         const int2 e = pos[p];
         const int lr_ = e.x - (gt << 7), br = e.y - b0;
-        if (br >= 0 && br < 256 && lr_ >= 0 && lr_ < 128) {
-          atomicOr(&ym[lr_ * 8 + (br >> 5)], 1u << (br & 31));
-          if (LOSS) loss -= zs[lr_ * kZPitch + br];
+        if (br >= 0 && br < TB && lr_ >= 0 && lr_ < 128) {
+          atomicOr(&ym[lr_ * MW + (br >> 5)], 1u << (br & 31));
+          if (LOSS) loss -= zs[lr_ * ZP + br];
         }
       }
     }
@@ -249,12 +257,12 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
 
     // ---- G = sigmoid(Z) - Y, BF16, coalesced rows of G^T
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
+    for (int it = 0; it < 128 * SEGS / kGemmThreads; ++it) {
       const int id = it * kGemmThreads + tid;
-      const int row = id >> 5, seg = id & 31;
-      const f32x4 z0 = *reinterpret_cast<const f32x4*>(zs + row * kZPitch + seg * 8);
-      const f32x4 z1 = *reinterpret_cast<const f32x4*>(zs + row * kZPitch + seg * 8 + 4);
-      const uint32_t yb = (ym[row * 8 + (seg >> 2)] >> ((seg & 3) * 8)) & 0xFFu;
+      const int row = id / SEGS, seg = id % SEGS;
+      const f32x4 z0 = *reinterpret_cast<const f32x4*>(zs + row * ZP + seg * 8);
+      const f32x4 z1 = *reinterpret_cast<const f32x4*>(zs + row * ZP + seg * 8 + 4);
+      const uint32_t yb = (ym[row * MW + (seg >> 2)] >> ((seg & 3) * 8)) & 0xFFu;
       const float z[8] = {z0[0], z0[1], z0[2], z0[3], z1[0], z1[1], z1[2], z1[3]};
       float g[8];
       const bool row_ok = lh + row < n;

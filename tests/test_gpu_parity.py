@@ -202,6 +202,26 @@ def test_ragged_shapes_all_modes(b, fmt, flags, tol):
     check_step(case, X, indptr, indices, 0.1, 42, 7, tol)
 
 
+@pytest.mark.parametrize("fmt,flags,d,tol", [
+    (o.E4M3, o.FLAG_SR | o.FLAG_KAHAN, 384, 6e-2),
+    (o.E4M3, o.FLAG_SR, 256, 6e-2),
+    (o.BF16, o.FLAG_KAHAN, 384, 2e-2),
+    (o.BF16, o.FLAG_SR, 128, 2e-2),
+])
+def test_large_batch_kernels_on_ragged_tiles(b, fmt, flags, d, tol):
+    """Batches above 128 rows take the three separate 256 x 256-tile kernels.  Element-by-element
+    parity where nothing is a multiple of a tile: 300 samples (two batch tiles, the second one
+    mostly padding), widths with a half column tile (384, 128), three label tiles with a ragged
+    tail, two chunks of different length, non-zero compensation on entry."""
+    L, B, chunk = 3 * 256 + 77, 300, 512
+    case = Case(b, L, d, fmt, chunk, flags, B, w_std=0.05, comp_std=2e-4, seed=6)
+    rng = np.random.default_rng(11)
+    X = synth.make_x(rng, B, d)
+    indptr, indices = synth.ZipfLabels(L, 1.0).draw_csr(rng, B, "lognormal5")
+    say(f"[large-batch ragged] fmt={fmt} flags={flags} L={L} d={d} B={B} chunk={chunk} nnz={len(indices)}")
+    check_step(case, X, indptr, indices, 0.1, 17, 3, tol)
+
+
 def test_same_operand_error_is_at_bf16_roundoff(b):
     """Sharper than the contract: G is held in BF16 (unit roundoff 2^-9), so dX should agree with
     the FP64 oracle to a few 1e-3 when both start from the same bits."""
