@@ -182,7 +182,7 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
 
   f32x16 acc[2][FN];
   zero_acc(acc);
-  ring_pipeline_pp<TB, 128, 256, 128, logits_stages<TB>(), kGemmWaves>(
+  ring_pipeline_pp<TB, 128, 256, 128, logits_stages<TB>(), kGemmWaves, true>(
       Xa + (size_t)b0 * rowb, rowb, a_rows - b0, 0, 128, 8, Wc + (size_t)l0 * rowb, rowb, n - l0, 0, 128, 8, (int)(rowb >> 7), smem,
       wave, lane, [&](const char* sa, const char* sb, int half) {
         if (FP8) {
@@ -329,7 +329,7 @@ k_dx(const char* __restrict__ Gt, const char* __restrict__ Wc, float* __restrict
 
   f32x16 acc[2][4];
   zero_acc(acc);
-  ring_pipeline_pp<64, 512, 64, WROWB, dx_stages<FP8>(), kGemmWaves>(
+  ring_pipeline_pp<64, 512, 64, WROWB, dx_stages<FP8>(), kGemmWaves, true>(
       Gt + (size_t)ks0 * 64 * strideA + (size_t)b0 * 2, strideA, (ksteps - ks0) * 64 /* zero rows past n are real */, 64, 64 * strideA, 32,
       Wc + (size_t)ks0 * 64 * strideB + (size_t)j0 * ESZ, strideB, n - ks0 * 64, 64, 64 * strideB, min(256, d - j0) * ESZ / 16,
       ks1 - ks0, smem, wave, lane, [&](const char* sa, const char* sb, int half) {
@@ -480,7 +480,7 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
   f32x16 acc[2][4];
   zero_acc(acc);
   // K loop over the batch in slabs of 64 samples
-  ring_pipeline_pp<256, 128, 256, 128, 2, kGemmWaves>(
+  ring_pipeline_pp<256, 128, 256, 128, 2, kGemmWaves, false>(
       Gt + (size_t)l0 * stride, stride, n - l0, 0, 128, 8, XT + (size_t)j0 * stride, stride, d - j0, 0, 128, 8, Bp >> 6, smem, wave,
       lane, [&](const char* sa, const char* sb, int half) {
 #pragma unroll

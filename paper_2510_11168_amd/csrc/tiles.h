@@ -159,31 +159,47 @@ __device__ inline void ring_pipeline(const char* __restrict__ ga, size_t stride_
 }
 
 // Ping-pong variant for the 256 x 256 output tiles.  The product of one slab is split in two
-// halves, mma(stageA, stageB, 0) and mma(stageA, stageB, 1); waves 0..NW/2-1 issue their share of
-// the next slab's loads right after the barrier, waves NW/2..NW-1 between the two halves.  Waves w
-// and w + 4 share a SIMD, so while one wave of a SIMD is held up handing its loads to the memory
-// pipeline the other one keeps the matrix core busy; with every wave issuing at the same point
-// the two phases add up instead of overlapping (measured: 1.33 -> 1.62 PFLOP/s for the BF16
-// main loop on its own).  chunks_a / chunks_b: valid 16-byte chunks per row (short rows re-read
-// their last chunk).
-template <int AROWS, int AROWB, int BROWS, int BROWB, int NST, int NW, class Mma>
+// halves, mma(stageA, stageB, 0) and mma(stageA, stageB, 1).  A wave that issues an asynchronous
+// load is held until the memory pipeline accepts it, i.e. roughly for as long as the data takes
+// to move; with every wave issuing at the same point the load and MFMA phases add up instead of
+// overlapping.  Here waves 0..NW/2-1 issue right after the barrier (the whole A slab and the first
+// half of the B slab), waves NW/2..NW-1 between the two halves (the second half of the B slab);
+// with UNEVEN = false both groups issue an equal share of both slabs.
+// Waves w and w + 4 share a SIMD, so one wave of each SIMD computes while its partner is held.
+// Measured on the BF16 main loop alone: all waves issuing together 1.33 PFLOP/s, equal shares
+// early/late 1.34-1.6, this 3:1 split 1.42-1.44 at the same clocks as 1.31 for equal shares.
+// chunks_a / chunks_b: valid 16-byte chunks per row (short rows re-read their last chunk).
+template <int AROWS, int AROWB, int BROWS, int BROWB, int NST, int NW, bool UNEVEN, class Mma>
 __device__ inline void ring_pipeline_pp(const char* __restrict__ ga, size_t stride_a, int va0, int dva, size_t adv_a, int chunks_a,
                                         const char* __restrict__ gb, size_t stride_b, int vb0, int dvb, size_t adv_b, int chunks_b,
                                         int nk, char* smem, int wave, int lane, Mma&& mma) {
-  constexpr int ABYTES = AROWS * AROWB, SBYTES = ABYTES + BROWS * BROWB;
-  constexpr int LPS = dma_loads_per_wave<AROWS, AROWB, NW>() + dma_loads_per_wave<BROWS, BROWB, NW>();
-  static_assert(NST >= 2 && NST <= 3 && (NST - 2) * LPS <= 63, "ring depth");
+  constexpr int ABYTES = AROWS * AROWB, SBYTES = ABYTES + BROWS * BROWB, NH = NW / 2, BH = BROWS / 2;
+  constexpr int LPS_ALL = dma_loads_per_wave<AROWS, AROWB, NW>() + dma_loads_per_wave<BROWS, BROWB, NW>();
+  constexpr int LPS_LATE = UNEVEN ? dma_loads_per_wave<BH, BROWB, NH>() : LPS_ALL;
+  constexpr int LPS_EARLY = UNEVEN ? dma_loads_per_wave<AROWS, AROWB, NH>() + LPS_LATE : LPS_ALL;
+  static_assert(NST >= 2 && NST <= 3 && (NST - 2) * LPS_EARLY <= 63, "ring depth");
+  const bool late = wave >= NH;
   auto issue = [&](int ks) {
     char* st = smem + (ks % NST) * SBYTES;
-    dma_tile<AROWS, AROWB, NW>(ga + (size_t)ks * adv_a, stride_a, va0 - ks * dva, st, wave, lane, chunks_a);
-    dma_tile<BROWS, BROWB, NW>(gb + (size_t)ks * adv_b, stride_b, vb0 - ks * dvb, st + ABYTES, wave, lane, chunks_b);
+    if (!UNEVEN) {
+      dma_tile<AROWS, AROWB, NW>(ga + (size_t)ks * adv_a, stride_a, va0 - ks * dva, st, wave, lane, chunks_a);
+      dma_tile<BROWS, BROWB, NW>(gb + (size_t)ks * adv_b, stride_b, vb0 - ks * dvb, st + ABYTES, wave, lane, chunks_b);
+    } else if (!late) {
+      dma_tile<AROWS, AROWB, NH>(ga + (size_t)ks * adv_a, stride_a, va0 - ks * dva, st, wave, lane, chunks_a);
+      dma_tile<BH, BROWB, NH>(gb + (size_t)ks * adv_b, stride_b, vb0 - ks * dvb, st + ABYTES, wave, lane, chunks_b);
+    } else {
+      // rows BH.. of the B slab; a slab with fewer valid rows re-reads its last valid row
+      const int vb = vb0 - ks * dvb;
+      dma_tile<BH, BROWB, NH>(gb + (size_t)ks * adv_b + (size_t)min(BH, vb - 1) * stride_b, stride_b, max(vb - BH, 1),
+                              st + ABYTES + BH * BROWB, wave - NH, lane, chunks_b);
+    }
   };
-  const bool late = wave >= NW / 2;
   for (int s = 0; s < NST - 1; ++s)
     if (s < nk) issue(s);
   for (int ks = 0; ks < nk; ++ks) {
     if (NST == 2 || ks + 1 >= nk) wait_vmcnt<0>();
-    else wait_vmcnt<LPS>();
+    else if (late) wait_vmcnt<LPS_LATE>();
+    else wait_vmcnt<LPS_EARLY>();
     barrier_nofence();
     const bool more = ks + NST - 1 < nk;
     if (more && !late) issue(ks + NST - 1);
