@@ -308,8 +308,10 @@ int raise_lds_limits() {
   ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, false, false>), elmo::kUpdateSmem);
   ELMO_ATTR((elmo::k_dx<true>), elmo::dx_smem_bytes<true>());
   ELMO_ATTR((elmo::k_dx<false>), elmo::dx_smem_bytes<false>());
-  ELMO_ATTR((elmo::k_topk_filter<true>), elmo::kNtRingBytes);
-  ELMO_ATTR((elmo::k_topk_filter<false>), elmo::kNtRingBytes);
+  ELMO_ATTR((elmo::k_topk_filter<true, true>), elmo::logits_smem<256>());
+  ELMO_ATTR((elmo::k_topk_filter<true, false>), elmo::logits_smem<256>());
+  ELMO_ATTR((elmo::k_topk_filter<false, true>), elmo::logits_smem<256>());
+  ELMO_ATTR((elmo::k_topk_filter<false, false>), elmo::logits_smem<256>());
   ELMO_ATTR((elmo::k_topk_chunk<true>), elmo::kTopkSmem);
   ELMO_ATTR((elmo::k_topk_chunk<false>), elmo::kTopkSmem);
 #undef ELMO_ATTR

@@ -124,23 +124,14 @@ __global__ void __launch_bounds__(kThreads) k_label_scatter(const int* __restric
 // ---------------------------------------------------------------------------------------------
 constexpr int kGemmThreads = 512;
 constexpr int kGemmWaves = 8;
-constexpr int kStages = 3;
-constexpr int kNtRingBytes = kStages * (256 + 128) * 128;        // top-k filter: 256 x 128 tiles, 3 stages
+constexpr int kStages = 3;                                       // ring depth of the small-batch kernel
 constexpr int kWideRingBytes = 2 * (256 + 256) * 128;            // K-contiguous operands, 128-byte slabs, 2 stages
 
-__device__ inline void zero_acc(f32x16 (&acc)[2][2]) {
+template <int FN> __device__ inline void zero_acc(f32x16 (&acc)[2][FN]) {
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-}
-__device__ inline void zero_acc(f32x16 (&acc)[2][4]) {
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < FN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 }
@@ -165,26 +156,19 @@ template <int TB> constexpr int logits_smem() {
   return epi > ring ? epi : ring;
 }
 
-template <bool FP8, bool LOSS, int TB>
-__global__ void __launch_bounds__(kGemmThreads, 1)
-k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, int n, int d, int Bp, int B,
-         uint16_t* __restrict__ Gt, const int* __restrict__ binptr, const int2* __restrict__ pos, int tile0,
-         float* __restrict__ loss_slots) {
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  constexpr int WGN = TB == 256 ? 2 : 4, FN = 8 / WGN;      // waves along the labels, 32-label blocks per wave
-  constexpr int ZP = logits_zpitch<TB>(), MW = TB / 32, SEGS = TB / 8;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave / WGN, wn = wave % WGN;
-  const int tiles_b = (Bp + TB - 1) / TB;
-  const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
-  const int lt = wg / tiles_b, bt = wg % tiles_b;
-  const int b0 = bt * TB, l0 = lt << 8;
-  const size_t rowb = (size_t)d * (FP8 ? 1 : 2);
-
-  f32x16 acc[2][FN];
+// Z tile = Xa[TB rows] . Wc[256 rows]^T over the full embedding width (rowb bytes per row), FP32
+// accumulators.  Waves as (8 / WGN) x WGN with WGN = 2 (TB = 256) or 4 (TB = 128); wave (wm, wn)
+// owns samples 64 wm .. +63 and labels 32 FN wn .. +32 FN - 1, acc[i][j] = its 32 x 32 block (i, j).
+template <bool FP8, int TB, int FN>
+__device__ __forceinline__ void logits_tile_product(const char* __restrict__ Xa, int a_valid, const char* __restrict__ Wc, int w_valid,
+                                                    size_t rowb, char* smem, int wave, int lane, f32x16 (&acc)[2][FN]) {
+  constexpr int WGN = 8 / FN;
+  static_assert(WGN == (TB == 256 ? 2 : 4), "wave layout");
+  const int wm = wave / WGN, wn = wave % WGN;
   zero_acc(acc);
   ring_pipeline_pp<TB, 128, 256, 128, logits_stages<TB>(), kGemmWaves, true>(
-      Xa + (size_t)b0 * rowb, rowb, a_rows - b0, 0, 128, 8, Wc + (size_t)l0 * rowb, rowb, n - l0, 0, 128, 8, (int)(rowb >> 7), smem,
-      wave, lane, [&](const char* sa, const char* sb, int half) {
+      Xa, rowb, a_valid, 0, 128, 8, Wc, rowb, w_valid, 0, 128, 8, (int)(rowb >> 7), smem, wave, lane,
+      [&](const char* sa, const char* sb, int half) {
         if (FP8) {
           i32x8 a[2], b[FN];
 #pragma unroll
@@ -212,6 +196,25 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
           }
         }
       });
+}
+
+template <bool FP8, bool LOSS, int TB>
+__global__ void __launch_bounds__(kGemmThreads, 1)
+k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, int n, int d, int Bp, int B,
+         uint16_t* __restrict__ Gt, const int* __restrict__ binptr, const int2* __restrict__ pos, int tile0,
+         float* __restrict__ loss_slots) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  constexpr int WGN = TB == 256 ? 2 : 4, FN = 8 / WGN;      // waves along the labels, 32-label blocks per wave
+  constexpr int ZP = logits_zpitch<TB>(), MW = TB / 32, SEGS = TB / 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave / WGN, wn = wave % WGN;
+  const int tiles_b = (Bp + TB - 1) / TB;
+  const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
+  const int lt = wg / tiles_b, bt = wg % tiles_b;
+  const int b0 = bt * TB, l0 = lt << 8;
+  const size_t rowb = (size_t)d * (FP8 ? 1 : 2);
+
+  f32x16 acc[2][FN];
+  logits_tile_product<FP8, TB, FN>(Xa + (size_t)b0 * rowb, a_rows - b0, Wc + (size_t)l0 * rowb, n - l0, rowb, smem, wave, lane, acc);
 
   float* zs = reinterpret_cast<float*>(smem);
   uint32_t* ym = reinterpret_cast<uint32_t*>(smem + 128 * ZP * 4);

@@ -128,37 +128,10 @@ template <int ROWS, int ROWB> struct TileLoader {
 // Software pipeline over K slabs with a ring of NST LDS stages (stage = [A tile | B tile]) filled
 // by asynchronous global->LDS loads that run NST-1 slabs ahead of the matrix cores.  Per slab:
 // wait until at most the younger slabs' loads are outstanding (vmcnt counts in issue order), one
-// barrier, refill the stage that was consumed one step earlier, then mma(stageA, stageB).
+// barrier, refill the stage that was consumed one step earlier, then the slab's products.
 // Operand slab ks starts at g + ks*adv and has v0 - ks*dv valid rows.
-template <int AROWS, int AROWB, int BROWS, int BROWB, int NST, int NW, class Mma>
-__device__ inline void ring_pipeline(const char* __restrict__ ga, size_t stride_a, int va0, int dva, size_t adv_a,
-                                     const char* __restrict__ gb, size_t stride_b, int vb0, int dvb, size_t adv_b,
-                                     int nk, char* smem, int wave, int lane, Mma&& mma) {
-  constexpr int ABYTES = AROWS * AROWB, SBYTES = ABYTES + BROWS * BROWB;
-  constexpr int LPS = dma_loads_per_wave<AROWS, AROWB, NW>() + dma_loads_per_wave<BROWS, BROWB, NW>();
-  static_assert(NST >= 2 && NST <= 5 && (NST - 2) * LPS <= 63, "ring depth");
-  auto issue = [&](int ks) {
-    char* st = smem + (ks % NST) * SBYTES;
-    dma_tile<AROWS, AROWB, NW>(ga + (size_t)ks * adv_a, stride_a, va0 - ks * dva, st, wave, lane);
-    dma_tile<BROWS, BROWB, NW>(gb + (size_t)ks * adv_b, stride_b, vb0 - ks * dvb, st + ABYTES, wave, lane);
-  };
-  for (int s = 0; s < NST - 1; ++s)
-    if (s < nk) issue(s);
-  for (int ks = 0; ks < nk; ++ks) {
-    const int younger = min(NST - 2, nk - 1 - ks);
-    if (younger <= 0) wait_vmcnt<0>();
-    else if (younger == 1) wait_vmcnt<LPS>();
-    else if (younger == 2) wait_vmcnt<(NST > 3 ? 2 : 0) * LPS>();
-    else wait_vmcnt<(NST > 4 ? 3 : 0) * LPS>();
-    barrier_nofence();
-    if (ks + NST - 1 < nk) issue(ks + NST - 1);
-    const char* st = smem + (ks % NST) * SBYTES;
-    mma(st, st + ABYTES);
-  }
-  barrier_nofence();   // every wave is done with the ring: the caller may reuse the memory
-}
-
-// Ping-pong variant for the 256 x 256 output tiles.  The product of one slab is split in two
+//
+// Ping-pong issue order.  The product of one slab is split in two
 // halves, mma(stageA, stageB, 0) and mma(stageA, stageB, 1).  A wave that issues an asynchronous
 // load is held until the memory pipeline accepts it, i.e. roughly for as long as the data takes
 // to move; with every wave issuing at the same point the load and MFMA phases add up instead of

@@ -228,14 +228,19 @@ __global__ void __launch_bounds__(kThreads) k_topk_merge(const float* __restrict
 // ---------------------------------------------------------------------------------------------
 // Main path: threshold filter fused into the logits tile, and the per-row select.
 // ---------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(kThreads) k_topk_init(float* __restrict__ tau, int* __restrict__ cnt, int* __restrict__ ovf, int rows) {
+// cnt0: candidates per row that the first level writes without counting (all of its labels).
+__global__ void __launch_bounds__(kThreads) k_topk_init(float* __restrict__ tau, int* __restrict__ cnt, int* __restrict__ ovf, int rows,
+                                                        int cnt0) {
   const int i = blockIdx.x * kThreads + threadIdx.x;
-  if (i < rows) { tau[i] = -INFINITY; cnt[i] = 0; ovf[i] = 0; }
+  if (i < rows) { tau[i] = -INFINITY; cnt[i] = cnt0; ovf[i] = 0; }
 }
 
-// Logits of labels [l_begin, l_begin + n) for all rows, 256 x 128 tiles as in the training step;
-// every score above its row's threshold is appended to that row's candidate list.
-template <bool FP8>
+// Logits of labels [l_begin, l_begin + n) for all rows, 256 x 256 tiles as in the training step;
+// every score above its row's threshold is appended to that row's candidate list.  FIRST: the
+// first level has no threshold yet and at most kTopkCand labels: label l of the level goes to slot l
+// of every row, no counting (scores that could never be selected, NaN or -inf, are stored as
+// empty slots).
+template <bool FP8, bool FIRST>
 __global__ void __launch_bounds__(kGemmThreads, 1)
 k_topk_filter(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wl, int n, int l_begin, int d, int Bp, int B,
               const float* __restrict__ tau, int* __restrict__ cnt, int* __restrict__ ovf, float* __restrict__ cand_sc,
@@ -245,57 +250,31 @@ k_topk_filter(const char* __restrict__ Xa, int a_rows, const char* __restrict__ 
   const int tiles_b = (Bp + 255) >> 8;
   const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
   const int lt = wg / tiles_b, bt = wg % tiles_b;
-  const int b0 = bt << 8, l0 = lt << 7;
+  const int b0 = bt << 8, l0 = lt << 8;
   const size_t rowb = (size_t)d * (FP8 ? 1 : 2);
-  f32x16 acc[2][2];
-  zero_acc(acc);
-  ring_pipeline<256, 128, 128, 128, kStages, kGemmWaves>(
-      Xa + (size_t)b0 * rowb, rowb, a_rows - b0, 0, 128, Wl + (size_t)l0 * rowb, rowb, n - l0, 0, 128, (int)(rowb >> 7), smem,
-      wave, lane, [&](const char* sa, const char* sb) {
-        if (FP8) {
-#pragma unroll
-          for (int kk = 0; kk < 2; ++kk) {
-            i32x8 a[2], b[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) a[i] = frag_fp8(sa, wm * 64 + 32 * i, kk, lane);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) b[j] = frag_fp8(sb, wn * 64 + 32 * j, kk, lane);
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-              for (int j = 0; j < 2; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 0, 0, 0, 0, 0, 0);
-          }
-        } else {
-#pragma unroll
-          for (int kk = 0; kk < 4; ++kk) {
-            bf16x8 a[2], b[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) a[i] = frag_bf16(sa, wm * 64 + 32 * i, kk, lane);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) b[j] = frag_bf16(sb, wn * 64 + 32 * j, kk, lane);
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-              for (int j = 0; j < 2; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-          }
-        }
-      });
+  f32x16 acc[2][4];
+  logits_tile_product<FP8, 256, 4>(Xa + (size_t)b0 * rowb, a_rows - b0, Wl + (size_t)l0 * rowb, n - l0, rowb, smem, wave, lane, acc);
   float* tau_s = reinterpret_cast<float*>(smem);
   for (int i = tid; i < 256; i += kGemmThreads) tau_s[i] = b0 + i < B ? tau[b0 + i] : INFINITY;   // padding rows never emit
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int v = 0; v < 16; ++v) {
+      const int b = wm * 64 + 32 * i + acc_row(v, lane);
+      const int row = b0 + b;
+      const float t = tau_s[b];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int b = wm * 64 + 32 * i + acc_row(v, lane);
-        const int l = l0 + wn * 64 + 32 * j + (lane & 31);
+      for (int j = 0; j < 4; ++j) {
+        const int l = l0 + wn * 128 + 32 * j + (lane & 31);
         const float z = acc[i][j][v];
-        if (l < n && z > tau_s[b]) {
-          const int row = b0 + b;
+        if (FIRST) {
+          if (l < n && row < B) {
+            const bool live = z > -INFINITY;
+            cand_sc[(size_t)row * kTopkCand + l] = live ? z : -INFINITY;
+            cand_id[(size_t)row * kTopkCand + l] = live ? l_begin + l : INT_MAX;
+          }
+        } else if (l < n && z > t) {
           const int slot = atomicAdd(&cnt[row], 1);
           if (slot < kTopkCand) {
             cand_sc[(size_t)row * kTopkCand + slot] = z;
@@ -305,6 +284,7 @@ k_topk_filter(const char* __restrict__ Xa, int a_rows, const char* __restrict__ 
           }
         }
       }
+    }
 }
 
 // Per row: sort the candidates, keep the k best at the front of the list, raise the threshold.
@@ -357,15 +337,20 @@ inline int topk_run(hipStream_t st, bool fp8, const char* Xa, int a_rows, const 
   int* cand_id = reinterpret_cast<int*>(scratch + rows * 12 + rows * (size_t)kTopkCand * 4);
   char* fb_scratch = scratch + topk_main_bytes(Bp);
   const size_t rowb = (size_t)d * (fp8 ? 1 : 2);
-  k_topk_init<<<(int)((rows + kThreads - 1) / kThreads), kThreads, 0, st>>>(tau, cnt, ovf, (int)rows);
+  static_assert(kTopkLevel0 <= kTopkCand, "the first level writes one slot per label");
+  k_topk_init<<<(int)((rows + kThreads - 1) / kThreads), kThreads, 0, st>>>(tau, cnt, ovf, (int)rows,
+                                                                             (int)std::min<int64_t>(L, kTopkLevel0));
   if (int rc = topk_launch_error("k_topk_init", err, errsz)) return rc;
   const int tiles_b256 = (Bp + 255) / 256;
   for (int64_t begin = 0, end = std::min<int64_t>(L, kTopkLevel0); begin < L; begin = end, end = std::min<int64_t>(L, end * 17)) {
     const int n = (int)(end - begin);
-    const int grid = (n + 127) / 128 * tiles_b256;
+    const int grid = (n + 255) / 256 * tiles_b256;
     const char* Wl = W + (size_t)begin * rowb;
-    if (fp8) k_topk_filter<true><<<grid, kGemmThreads, kNtRingBytes, st>>>(Xa, a_rows, Wl, n, (int)begin, d, Bp, B, tau, cnt, ovf, cand_sc, cand_id);
-    else k_topk_filter<false><<<grid, kGemmThreads, kNtRingBytes, st>>>(Xa, a_rows, Wl, n, (int)begin, d, Bp, B, tau, cnt, ovf, cand_sc, cand_id);
+    const bool first = begin == 0;
+    if (fp8 && first) k_topk_filter<true, true><<<grid, kGemmThreads, logits_smem<256>(), st>>>(Xa, a_rows, Wl, n, (int)begin, d, Bp, B, tau, cnt, ovf, cand_sc, cand_id);
+    else if (fp8) k_topk_filter<true, false><<<grid, kGemmThreads, logits_smem<256>(), st>>>(Xa, a_rows, Wl, n, (int)begin, d, Bp, B, tau, cnt, ovf, cand_sc, cand_id);
+    else if (first) k_topk_filter<false, true><<<grid, kGemmThreads, logits_smem<256>(), st>>>(Xa, a_rows, Wl, n, (int)begin, d, Bp, B, tau, cnt, ovf, cand_sc, cand_id);
+    else k_topk_filter<false, false><<<grid, kGemmThreads, logits_smem<256>(), st>>>(Xa, a_rows, Wl, n, (int)begin, d, Bp, B, tau, cnt, ovf, cand_sc, cand_id);
     if (int rc = topk_launch_error("k_topk_filter", err, errsz)) return rc;
     const bool last = end == L;
     k_topk_select<<<B, kThreads, 0, st>>>(tau, cnt, cand_sc, cand_id, k, last ? idx_out : nullptr, last ? score_out : nullptr);
