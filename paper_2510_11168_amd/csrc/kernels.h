@@ -156,9 +156,42 @@ template <int TB> constexpr int logits_smem() {
   return epi > ring ? epi : ring;
 }
 
+// One half (0 or 1) of the product of a 128-byte K slab of the logits tile: A = TB sample rows,
+// B = 256 label rows, K-contiguous in LDS.  Wave (wm, wn) owns samples 64 wm .. +63 and labels
+// 32 FN wn .. +32 FN - 1; acc[i][j] is its 32 x 32 block (i, j).
+template <bool FP8, int FN>
+__device__ __forceinline__ void logits_slab_product(const char* sa, const char* sb, int half, int wm, int wn, int lane,
+                                                    f32x16 (&acc)[2][FN]) {
+  if (FP8) {
+    i32x8 a[2], b[FN];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) a[i] = frag_fp8(sa, wm * 64 + 32 * i, half, lane);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) b[j] = frag_fp8(sb, wn * 32 * FN + 32 * j, half, lane);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 0, 0, 0, 0, 0, 0);
+  } else {
+#pragma unroll
+    for (int kk = 2 * half; kk < 2 * half + 2; ++kk) {
+      bf16x8 a[2], b[FN];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) a[i] = frag_bf16(sa, wm * 64 + 32 * i, kk, lane);
+#pragma unroll
+      for (int j = 0; j < FN; ++j) b[j] = frag_bf16(sb, wn * 32 * FN + 32 * j, kk, lane);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+  }
+}
+
 // Z tile = Xa[TB rows] . Wc[256 rows]^T over the full embedding width (rowb bytes per row), FP32
-// accumulators.  Waves as (8 / WGN) x WGN with WGN = 2 (TB = 256) or 4 (TB = 128); wave (wm, wn)
-// owns samples 64 wm .. +63 and labels 32 FN wn .. +32 FN - 1, acc[i][j] = its 32 x 32 block (i, j).
+// accumulators.  Waves as (8 / WGN) x WGN with WGN = 2 (TB = 256) or 4 (TB = 128).
 template <bool FP8, int TB, int FN>
 __device__ __forceinline__ void logits_tile_product(const char* __restrict__ Xa, int a_valid, const char* __restrict__ Wc, int w_valid,
                                                     size_t rowb, char* smem, int wave, int lane, f32x16 (&acc)[2][FN]) {
@@ -168,34 +201,7 @@ __device__ __forceinline__ void logits_tile_product(const char* __restrict__ Xa,
   zero_acc(acc);
   ring_pipeline_pp<TB, 128, 256, 128, logits_stages<TB>(), kGemmWaves, true>(
       Xa, rowb, a_valid, 0, 128, 8, Wc, rowb, w_valid, 0, 128, 8, (int)(rowb >> 7), smem, wave, lane,
-      [&](const char* sa, const char* sb, int half) {
-        if (FP8) {
-          i32x8 a[2], b[FN];
-#pragma unroll
-          for (int i = 0; i < 2; ++i) a[i] = frag_fp8(sa, wm * 64 + 32 * i, half, lane);
-#pragma unroll
-          for (int j = 0; j < FN; ++j) b[j] = frag_fp8(sb, wn * 32 * FN + 32 * j, half, lane);
-#pragma unroll
-          for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 0, 0, 0, 0, 0, 0);
-        } else {
-#pragma unroll
-          for (int kk = 2 * half; kk < 2 * half + 2; ++kk) {
-            bf16x8 a[2], b[FN];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) a[i] = frag_bf16(sa, wm * 64 + 32 * i, kk, lane);
-#pragma unroll
-            for (int j = 0; j < FN; ++j) b[j] = frag_bf16(sb, wn * 32 * FN + 32 * j, kk, lane);
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-              for (int j = 0; j < FN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-          }
-        }
-      });
+      [&](const char* sa, const char* sb, int half) { logits_slab_product<FP8, FN>(sa, sb, half, wm, wn, lane, acc); });
 }
 
 template <bool FP8, bool LOSS, int TB>

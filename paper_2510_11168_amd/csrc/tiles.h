@@ -129,7 +129,6 @@ template <int ROWS, int ROWB> struct TileLoader {
 // by asynchronous global->LDS loads that run NST-1 slabs ahead of the matrix cores.  Per slab:
 // wait until at most the younger slabs' loads are outstanding (vmcnt counts in issue order), one
 // barrier, refill the stage that was consumed one step earlier, then the slab's products.
-// Operand slab ks starts at g + ks*adv and has v0 - ks*dv valid rows.
 //
 // Ping-pong issue order.  The product of one slab is split in two
 // halves, mma(stageA, stageB, 0) and mma(stageA, stageB, 1).  A wave that issues an asynchronous
@@ -142,10 +141,16 @@ template <int ROWS, int ROWB> struct TileLoader {
 // Measured on the BF16 main loop alone: all waves issuing together 1.33 PFLOP/s, equal shares
 // early/late 1.34-1.6, this 3:1 split 1.42-1.44 at the same clocks as 1.31 for equal shares.
 // chunks_a / chunks_b: valid 16-byte chunks per row (short rows re-read their last chunk).
-template <int AROWS, int AROWB, int BROWS, int BROWB, int NST, int NW, bool UNEVEN, class Mma>
-__device__ inline void ring_pipeline_pp(const char* __restrict__ ga, size_t stride_a, int va0, int dva, size_t adv_a, int chunks_a,
-                                        const char* __restrict__ gb, size_t stride_b, int vb0, int dvb, size_t adv_b, int chunks_b,
-                                        int nk, char* smem, int wave, int lane, Mma&& mma) {
+//
+// ring_stream_pp is the general form: src(ks, off_a, va, off_b, vb) names slab ks of each operand
+// (byte offset from ga / gb and number of valid rows), so a workgroup can run the ring across the
+// output tiles it owns without draining it; mma(stageA, stageB, half, ks).  The base pointers are
+// restrict-qualified parameters on purpose: inlining then tags every LDS access inside with alias
+// information, without which the compiler puts a vmcnt(0) in front of LDS reads it cannot tell
+// from the asynchronous loads still in flight.
+template <int AROWS, int AROWB, int BROWS, int BROWB, int NST, int NW, bool UNEVEN, class Src, class Mma>
+__device__ inline void ring_stream_pp(const char* __restrict__ ga, size_t stride_a, int chunks_a, const char* __restrict__ gb,
+                                      size_t stride_b, int chunks_b, int nk, char* smem, int wave, int lane, Src&& src, Mma&& mma) {
   constexpr int ABYTES = AROWS * AROWB, SBYTES = ABYTES + BROWS * BROWB, NH = NW / 2, BH = BROWS / 2;
   constexpr int LPS_ALL = dma_loads_per_wave<AROWS, AROWB, NW>() + dma_loads_per_wave<BROWS, BROWB, NW>();
   constexpr int LPS_LATE = UNEVEN ? dma_loads_per_wave<BH, BROWB, NH>() : LPS_ALL;
@@ -154,16 +159,18 @@ __device__ inline void ring_pipeline_pp(const char* __restrict__ ga, size_t stri
   const bool late = wave >= NH;
   auto issue = [&](int ks) {
     char* st = smem + (ks % NST) * SBYTES;
+    size_t off_a, off_b;
+    int va, vb;
+    src(ks, off_a, va, off_b, vb);
     if (!UNEVEN) {
-      dma_tile<AROWS, AROWB, NW>(ga + (size_t)ks * adv_a, stride_a, va0 - ks * dva, st, wave, lane, chunks_a);
-      dma_tile<BROWS, BROWB, NW>(gb + (size_t)ks * adv_b, stride_b, vb0 - ks * dvb, st + ABYTES, wave, lane, chunks_b);
+      dma_tile<AROWS, AROWB, NW>(ga + off_a, stride_a, va, st, wave, lane, chunks_a);
+      dma_tile<BROWS, BROWB, NW>(gb + off_b, stride_b, vb, st + ABYTES, wave, lane, chunks_b);
     } else if (!late) {
-      dma_tile<AROWS, AROWB, NH>(ga + (size_t)ks * adv_a, stride_a, va0 - ks * dva, st, wave, lane, chunks_a);
-      dma_tile<BH, BROWB, NH>(gb + (size_t)ks * adv_b, stride_b, vb0 - ks * dvb, st + ABYTES, wave, lane, chunks_b);
+      dma_tile<AROWS, AROWB, NH>(ga + off_a, stride_a, va, st, wave, lane, chunks_a);
+      dma_tile<BH, BROWB, NH>(gb + off_b, stride_b, vb, st + ABYTES, wave, lane, chunks_b);
     } else {
       // rows BH.. of the B slab; a slab with fewer valid rows re-reads its last valid row
-      const int vb = vb0 - ks * dvb;
-      dma_tile<BH, BROWB, NH>(gb + (size_t)ks * adv_b + (size_t)min(BH, vb - 1) * stride_b, stride_b, max(vb - BH, 1),
+      dma_tile<BH, BROWB, NH>(gb + off_b + (size_t)min(BH, vb - 1) * stride_b, stride_b, max(vb - BH, 1),
                               st + ABYTES + BH * BROWB, wave - NH, lane, chunks_b);
     }
   };
@@ -178,13 +185,27 @@ __device__ inline void ring_pipeline_pp(const char* __restrict__ ga, size_t stri
     if (more && !late) issue(ks + NST - 1);
     const char* st = smem + (ks % NST) * SBYTES;
     __builtin_amdgcn_sched_barrier(0);
-    mma(st, st + ABYTES, 0);
+    mma(st, st + ABYTES, 0, ks);
     __builtin_amdgcn_sched_barrier(0);
     if (more && late) issue(ks + NST - 1);
     __builtin_amdgcn_sched_barrier(0);
-    mma(st, st + ABYTES, 1);
+    mma(st, st + ABYTES, 1, ks);
   }
   barrier_nofence();   // every wave is done with the ring: the caller may reuse the memory
+}
+
+// One output tile: slab ks of an operand starts at g + ks*adv and has v0 - ks*dv valid rows.
+template <int AROWS, int AROWB, int BROWS, int BROWB, int NST, int NW, bool UNEVEN, class Mma>
+__device__ inline void ring_pipeline_pp(const char* __restrict__ ga, size_t stride_a, int va0, int dva, size_t adv_a, int chunks_a,
+                                        const char* __restrict__ gb, size_t stride_b, int vb0, int dvb, size_t adv_b, int chunks_b,
+                                        int nk, char* smem, int wave, int lane, Mma&& mma) {
+  ring_stream_pp<AROWS, AROWB, BROWS, BROWB, NST, NW, UNEVEN>(
+      ga, stride_a, chunks_a, gb, stride_b, chunks_b, nk, smem, wave, lane,
+      [&](int ks, size_t& off_a, int& va, size_t& off_b, int& vb) {
+        off_a = (size_t)ks * adv_a; va = va0 - ks * dva;
+        off_b = (size_t)ks * adv_b; vb = vb0 - ks * dvb;
+      },
+      [&](const char* sa, const char* sb, int half, int) { mma(sa, sb, half); });
 }
 
 // ---------------------------------------------------------------------------------------------
