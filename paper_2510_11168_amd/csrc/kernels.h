@@ -142,19 +142,21 @@ template <int FN> __device__ inline void zero_acc(f32x16 (&acc)[2][FN]) {
 // accumulation over the full embedding width, then G = sigmoid(Z) - Y, and stores G^T[l][b] as
 // BF16 (labels x batch, the layout the paper's logits buffer has).  Z never reaches memory.
 // FP8: both operands E4M3, v_mfma_f32_32x32x64_f8f6f4.  BF16: v_mfma_f32_32x32x16_bf16.
-// The epilogue handles the tile as two halves of 128 labels (one bin of the positives index
-// each), staged through LDS as FP32.  Rows of G^T between n and the next multiple of 128 are
-// written as zeros (the input-gradient product reads whole 64-label slabs).
+// Epilogue: the positives of the tile's two 128-label bins are turned into a bit mask in LDS, then
+// every thread finishes its accumulators in registers (sigmoid, minus the mask bit, BF16) and
+// writes them transposed into an LDS stage of G^T, from which whole rows are stored coalesced.
+// Rows of G^T between n and the next multiple of 128 are written as zeros (the input-gradient
+// product reads whole 64-label slabs).
 // ---------------------------------------------------------------------------------------------
 // TB = rows of the batch tile: 256, or 128 for padded batches of at most 128 rows (waves as 2 x 4,
 // 64 x 64 outputs each, three ring stages), where half of a 256-row tile would be padding.
-template <int TB> constexpr int logits_zpitch() { return TB + 4; }                  // floats per staged row
+template <int TB> constexpr int logits_gpitch() { return (TB + 4) * 2; }            // bytes per staged G^T row (odd multiple of 8)
 template <int TB> constexpr int logits_stages() { return TB == 256 ? 2 : 3; }
-template <int TB> constexpr int logits_smem() {
-  constexpr int epi = 128 * logits_zpitch<TB>() * 4 + 128 * (TB / 32) * 4 + 32;     // Z^T stage + positives mask + reduce
-  constexpr int ring = logits_stages<TB>() * (TB + 256) * 128;
-  return epi > ring ? epi : ring;
+template <int TB> constexpr int logits_ring_bytes() { return logits_stages<TB>() * (TB + 256) * 128; }
+template <int TB> constexpr int logits_mask_offset() {                              // positives mask: behind ring and G^T stage
+  return 256 * logits_gpitch<TB>() > logits_ring_bytes<TB>() ? 256 * logits_gpitch<TB>() : logits_ring_bytes<TB>();
 }
+template <int TB> constexpr int logits_smem() { return logits_mask_offset<TB>() + 256 * (TB / 32) * 4 + 32; }
 
 // One half (0 or 1) of the product of a 128-byte K slab of the logits tile: A = TB sample rows,
 // B = 256 label rows, K-contiguous in LDS.  Wave (wm, wn) owns samples 64 wm .. +63 and labels
@@ -211,7 +213,7 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
          float* __restrict__ loss_slots) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int WGN = TB == 256 ? 2 : 4, FN = 8 / WGN;      // waves along the labels, 32-label blocks per wave
-  constexpr int ZP = logits_zpitch<TB>(), MW = TB / 32, SEGS = TB / 8;
+  constexpr int MW = TB / 32, SEGS = TB / 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave / WGN, wn = wave % WGN;
   const int tiles_b = (Bp + TB - 1) / TB;
   const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
@@ -222,75 +224,70 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
   f32x16 acc[2][FN];
   logits_tile_product<FP8, TB, FN>(Xa + (size_t)b0 * rowb, a_rows - b0, Wc + (size_t)l0 * rowb, n - l0, rowb, smem, wave, lane, acc);
 
-  float* zs = reinterpret_cast<float*>(smem);
-  uint32_t* ym = reinterpret_cast<uint32_t*>(smem + 128 * ZP * 4);
-  float* red = reinterpret_cast<float*>(smem + 128 * ZP * 4 + 128 * MW * 4);
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int lh = l0 + 128 * h;                 // first label of this half
-    if (lh >= n) break;                          // the same for the whole workgroup
-    if (h) barrier_lds();                        // the first half has been read out of the stage (no wait for its stores)
-    // ---- stage Z^T (labels x samples) of this half in LDS as FP32: the waves that own it write
-    if (wn * FN / 4 == h) {
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int l = (wn * 32 * FN + 32 * j + (lane & 31)) & 127;
-            const int b = wm * 64 + 32 * i + 8 * q + 4 * (lane >> 5);
-            f32x4 z;
-            z[0] = acc[i][j][4 * q]; z[1] = acc[i][j][4 * q + 1]; z[2] = acc[i][j][4 * q + 2]; z[3] = acc[i][j][4 * q + 3];
-            *reinterpret_cast<f32x4*>(zs + l * ZP + b) = z;
-          }
-    }
-    for (int i = tid; i < 128 * MW; i += kGemmThreads) ym[i] = 0u;
-    barrier_lds();
+  constexpr int GP = logits_gpitch<TB>();
+  char* gts = smem;                                                      // G^T stage: 256 rows of GP bytes
+  uint32_t* ym = reinterpret_cast<uint32_t*>(smem + logits_mask_offset<TB>());   // [256 labels][MW] bits over the samples
+  float* red = reinterpret_cast<float*>(smem + logits_mask_offset<TB>() + 256 * MW * 4);
+  const int rows_out = min(256, ((n - l0 + 127) >> 7) << 7);             // rows of G^T this tile writes
+  const int gt0 = tile0 + 2 * lt;                                        // first of the tile's (at most) two bins
 
-    // ---- positives of this 128-label bin that fall into this batch tile
-    float loss = 0.0f;
-    const int gt = tile0 + 2 * lt + h;
-    {
-      const int p0 = binptr[gt], p1 = binptr[gt + 1];
-      for (int p = p0 + tid; p < p1; p += kGemmThreads) {
-        const int2 e = pos[p];
-        const int lr_ = e.x - (gt << 7), br = e.y - b0;
-        if (br >= 0 && br < TB && lr_ >= 0 && lr_ < 128) {
-          atomicOr(&ym[lr_ * MW + (br >> 5)], 1u << (br & 31));
-          if (LOSS) loss -= zs[lr_ * ZP + br];
+  // ---- positives of this tile's bins that fall into this batch tile -> bit mask
+  for (int i = tid; i < 256 * MW; i += kGemmThreads) ym[i] = 0u;
+  barrier_lds();
+  {
+    const int p0 = binptr[gt0], p1 = binptr[gt0 + (rows_out >> 7)];
+    for (int p = p0 + tid; p < p1; p += kGemmThreads) {
+      const int2 e = pos[p];
+      const int lr_ = e.x - (gt0 << 7), br = e.y - b0;
+      if (br >= 0 && br < TB && lr_ >= 0 && lr_ < 256) atomicOr(&ym[lr_ * MW + (br >> 5)], 1u << (br & 31));
+    }
+  }
+  barrier_lds();
+
+  // ---- G = sigmoid(Z) - Y in registers, BF16, transposed into the stage (4 samples = 8 bytes per write)
+  float loss = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const int l = wn * 32 * FN + 32 * j + (lane & 31);
+      const bool row_ok = l0 + l < n;
+      const uint32_t ybits = ym[l * MW + 2 * wm + i] >> (4 * (lane >> 5));
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int b = wm * 64 + 32 * i + 8 * q + 4 * (lane >> 5);
+        float g[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float z = acc[i][j][4 * q + e];
+          const float y = (float)((ybits >> (8 * q + e)) & 1u);
+          g[e] = row_ok ? sigmoidf_fast(z) - y : 0.0f;
+          if (LOSS) loss += (row_ok && b0 + b + e < B) ? softplusf_fast(z) - y * z : 0.0f;
         }
+        uint2 o;
+        o.x = pack2_bf16(g[0], g[1]);
+        o.y = pack2_bf16(g[2], g[3]);
+        *reinterpret_cast<uint2*>(gts + l * GP + b * 2) = o;
       }
     }
-    barrier_lds();
+  barrier_lds();
 
-    // ---- G = sigmoid(Z) - Y, BF16, coalesced rows of G^T
+  // ---- coalesced rows of G^T
 #pragma unroll
-    for (int it = 0; it < 128 * SEGS / kGemmThreads; ++it) {
-      const int id = it * kGemmThreads + tid;
-      const int row = id / SEGS, seg = id % SEGS;
-      const f32x4 z0 = *reinterpret_cast<const f32x4*>(zs + row * ZP + seg * 8);
-      const f32x4 z1 = *reinterpret_cast<const f32x4*>(zs + row * ZP + seg * 8 + 4);
-      const uint32_t yb = (ym[row * MW + (seg >> 2)] >> ((seg & 3) * 8)) & 0xFFu;
-      const float z[8] = {z0[0], z0[1], z0[2], z0[3], z1[0], z1[1], z1[2], z1[3]};
-      float g[8];
-      const bool row_ok = lh + row < n;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float ge = sigmoidf_fast(z[e]) - (float)((yb >> e) & 1u);
-        g[e] = row_ok ? ge : 0.0f;
-        if (LOSS) loss += (row_ok && b0 + seg * 8 + e < B) ? softplusf_fast(z[e]) : 0.0f;
-      }
-      if (b0 + seg * 8 < Bp) {
-        u32x4 o;
-        o[0] = pack2_bf16(g[0], g[1]); o[1] = pack2_bf16(g[2], g[3]);
-        o[2] = pack2_bf16(g[4], g[5]); o[3] = pack2_bf16(g[6], g[7]);
-        *reinterpret_cast<u32x4*>(Gt + (size_t)(lh + row) * Bp + b0 + seg * 8) = o;
-      }
+  for (int it = 0; it < 256 * SEGS / kGemmThreads; ++it) {
+    const int id = it * kGemmThreads + tid;
+    const int row = id / SEGS, seg = id % SEGS;
+    if (row < rows_out && b0 + seg * 8 < Bp) {
+      const uint2 lo = *reinterpret_cast<const uint2*>(gts + row * GP + seg * 16);
+      const uint2 hi = *reinterpret_cast<const uint2*>(gts + row * GP + seg * 16 + 8);
+      *reinterpret_cast<u32x4*>(Gt + (size_t)(l0 + row) * Bp + b0 + seg * 8) = u32x4{lo.x, lo.y, hi.x, hi.y};
     }
-    if (LOSS) {
-      const float s = block_sum<kGemmWaves>(loss, red);
-      if (tid == 0) loss_slots[(size_t)gt * tiles_b + bt] = s;
+  }
+  if (LOSS) {
+    const float s = block_sum<kGemmWaves>(loss, red);
+    if (tid == 0) {
+      loss_slots[(size_t)gt0 * tiles_b + bt] = s;                        // both bins' loss in the first bin's slot
+      if (rows_out > 128) loss_slots[(size_t)(gt0 + 1) * tiles_b + bt] = 0.0f;
     }
   }
 }
