@@ -398,8 +398,8 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
     const int tile0 = (int)(c0 / 128);
     prof.mark(st, CLS_LOGITS);
     {
-      const int tb = Bp <= 128 ? 128 : 256;        // rows of the logits kernel's batch tile
-      const int grid = tiles_l * ((Bp + tb - 1) / tb);
+      const int tb = Bp <= 128 ? 128 : 256;        // the logits kernel's tile is tb samples x tb labels
+      const int grid = ((n + tb - 1) / tb) * ((Bp + tb - 1) / tb);
       if (fp8) {
         if (loss_out) launch_logits<true, true>(st, tb, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots);
         else launch_logits<true, false>(st, tb, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots);

@@ -148,18 +148,18 @@ template <int FN> __device__ inline void zero_acc(f32x16 (&acc)[2][FN]) {
 // Rows of G^T between n and the next multiple of 128 are written as zeros (the input-gradient
 // product reads whole 64-label slabs).
 // ---------------------------------------------------------------------------------------------
-// TB = rows of the batch tile: 256, or 128 for padded batches of at most 128 rows (waves as 2 x 4,
-// 64 x 64 outputs each, three ring stages), where half of a 256-row tile would be padding.
+// TB x TB output tiles: TB = 256, or 128 for padded batches of at most 128 rows, where half of a
+// 256-row tile would be padding and the kernel is bound by the stream of W: 128 x 128 tiles need
+// 66 KiB of LDS, so two workgroups share a CU and one's epilogue overlaps the other's loads.
 template <int TB> constexpr int logits_gpitch() { return (TB + 4) * 2; }            // bytes per staged G^T row (odd multiple of 8)
-template <int TB> constexpr int logits_stages() { return TB == 256 ? 2 : 3; }
-template <int TB> constexpr int logits_ring_bytes() { return logits_stages<TB>() * (TB + 256) * 128; }
+template <int TB> constexpr int logits_ring_bytes() { return 2 * (TB + TB) * 128; }
 template <int TB> constexpr int logits_mask_offset() {                              // positives mask: behind ring and G^T stage
-  return 256 * logits_gpitch<TB>() > logits_ring_bytes<TB>() ? 256 * logits_gpitch<TB>() : logits_ring_bytes<TB>();
+  return TB * logits_gpitch<TB>() > logits_ring_bytes<TB>() ? TB * logits_gpitch<TB>() : logits_ring_bytes<TB>();
 }
-template <int TB> constexpr int logits_smem() { return logits_mask_offset<TB>() + 256 * (TB / 32) * 4 + 32; }
+template <int TB> constexpr int logits_smem() { return logits_mask_offset<TB>() + TB * (TB / 32) * 4 + 32; }
 
 // One half (0 or 1) of the product of a 128-byte K slab of the logits tile: A = TB sample rows,
-// B = 256 label rows, K-contiguous in LDS.  Wave (wm, wn) owns samples 64 wm .. +63 and labels
+// B = TB label rows, K-contiguous in LDS.  Wave (wm, wn) owns samples 64 wm .. +63 and labels
 // 32 FN wn .. +32 FN - 1; acc[i][j] is its 32 x 32 block (i, j).
 template <bool FP8, int FN>
 __device__ __forceinline__ void logits_slab_product(const char* sa, const char* sb, int half, int wm, int wn, int lane,
@@ -192,54 +192,55 @@ __device__ __forceinline__ void logits_slab_product(const char* sa, const char* 
   }
 }
 
-// Z tile = Xa[TB rows] . Wc[256 rows]^T over the full embedding width (rowb bytes per row), FP32
-// accumulators.  Waves as (8 / WGN) x WGN with WGN = 2 (TB = 256) or 4 (TB = 128).
+// Z tile = Xa[TB rows] . Wc[TB rows]^T over the full embedding width (rowb bytes per row), FP32
+// accumulators.  Waves as (8 / WGN) x WGN with WGN = 2 (TB = 256, 64 x 128 per wave) or 4
+// (TB = 128, 64 x 32 per wave).
 template <bool FP8, int TB, int FN>
 __device__ __forceinline__ void logits_tile_product(const char* __restrict__ Xa, int a_valid, const char* __restrict__ Wc, int w_valid,
                                                     size_t rowb, char* smem, int wave, int lane, f32x16 (&acc)[2][FN]) {
-  constexpr int WGN = 8 / FN;
+  constexpr int WGN = TB / 32 / FN;
   static_assert(WGN == (TB == 256 ? 2 : 4), "wave layout");
   const int wm = wave / WGN, wn = wave % WGN;
   zero_acc(acc);
-  ring_pipeline_pp<TB, 128, 256, 128, logits_stages<TB>(), kGemmWaves, true>(
+  ring_pipeline_pp<TB, 128, TB, 128, 2, kGemmWaves, true>(
       Xa, rowb, a_valid, 0, 128, 8, Wc, rowb, w_valid, 0, 128, 8, (int)(rowb >> 7), smem, wave, lane,
       [&](const char* sa, const char* sb, int half) { logits_slab_product<FP8, FN>(sa, sb, half, wm, wn, lane, acc); });
 }
 
 template <bool FP8, bool LOSS, int TB>
-__global__ void __launch_bounds__(kGemmThreads, 1)
+__global__ void __launch_bounds__(kGemmThreads, TB == 256 ? 1 : 2)
 k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, int n, int d, int Bp, int B,
          uint16_t* __restrict__ Gt, const int* __restrict__ binptr, const int2* __restrict__ pos, int tile0,
          float* __restrict__ loss_slots) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  constexpr int WGN = TB == 256 ? 2 : 4, FN = 8 / WGN;      // waves along the labels, 32-label blocks per wave
+  constexpr int WGN = TB == 256 ? 2 : 4, FN = TB / 32 / WGN;   // waves along the labels, 32-label blocks per wave
   constexpr int MW = TB / 32, SEGS = TB / 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave / WGN, wn = wave % WGN;
   const int tiles_b = (Bp + TB - 1) / TB;
   const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
   const int lt = wg / tiles_b, bt = wg % tiles_b;
-  const int b0 = bt * TB, l0 = lt << 8;
+  const int b0 = bt * TB, l0 = lt * TB;
   const size_t rowb = (size_t)d * (FP8 ? 1 : 2);
 
   f32x16 acc[2][FN];
   logits_tile_product<FP8, TB, FN>(Xa + (size_t)b0 * rowb, a_rows - b0, Wc + (size_t)l0 * rowb, n - l0, rowb, smem, wave, lane, acc);
 
   constexpr int GP = logits_gpitch<TB>();
-  char* gts = smem;                                                      // G^T stage: 256 rows of GP bytes
-  uint32_t* ym = reinterpret_cast<uint32_t*>(smem + logits_mask_offset<TB>());   // [256 labels][MW] bits over the samples
-  float* red = reinterpret_cast<float*>(smem + logits_mask_offset<TB>() + 256 * MW * 4);
-  const int rows_out = min(256, ((n - l0 + 127) >> 7) << 7);             // rows of G^T this tile writes
-  const int gt0 = tile0 + 2 * lt;                                        // first of the tile's (at most) two bins
+  char* gts = smem;                                                      // G^T stage: TB rows of GP bytes
+  uint32_t* ym = reinterpret_cast<uint32_t*>(smem + logits_mask_offset<TB>());   // [TB labels][MW] bits over the samples
+  float* red = reinterpret_cast<float*>(smem + logits_mask_offset<TB>() + TB * MW * 4);
+  const int rows_out = min(TB, ((n - l0 + 127) >> 7) << 7);              // rows of G^T this tile writes
+  const int gt0 = tile0 + lt * (TB / 128);                               // first of the tile's one or two bins
 
   // ---- positives of this tile's bins that fall into this batch tile -> bit mask
-  for (int i = tid; i < 256 * MW; i += kGemmThreads) ym[i] = 0u;
+  for (int i = tid; i < TB * MW; i += kGemmThreads) ym[i] = 0u;
   barrier_lds();
   {
     const int p0 = binptr[gt0], p1 = binptr[gt0 + (rows_out >> 7)];
     for (int p = p0 + tid; p < p1; p += kGemmThreads) {
       const int2 e = pos[p];
       const int lr_ = e.x - (gt0 << 7), br = e.y - b0;
-      if (br >= 0 && br < TB && lr_ >= 0 && lr_ < 256) atomicOr(&ym[lr_ * MW + (br >> 5)], 1u << (br & 31));
+      if (br >= 0 && br < TB && lr_ >= 0 && lr_ < TB) atomicOr(&ym[lr_ * MW + (br >> 5)], 1u << (br & 31));
     }
   }
   barrier_lds();
@@ -274,7 +275,7 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
 
   // ---- coalesced rows of G^T
 #pragma unroll
-  for (int it = 0; it < 256 * SEGS / kGemmThreads; ++it) {
+  for (int it = 0; it < TB * SEGS / kGemmThreads; ++it) {
     const int id = it * kGemmThreads + tid;
     const int row = id / SEGS, seg = id % SEGS;
     if (row < rows_out && b0 + seg * 8 < Bp) {
