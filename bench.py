@@ -72,7 +72,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run one plain 1 GiB device copy (a kernel of known traffic for scaling rocprofv3 counters)")
-    ap.add_argument("--cpu-sample-labels", type=int, default=8192)
+    ap.add_argument("--cpu-sample-labels", type=int, default=131072)
     return ap.parse_args()
 
 
