@@ -377,11 +377,12 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
       elmo::k_fill_u32<<<1, elmo::kThreads, 0, st>>>((uint32_t*)flag, 1, 0u);
       if (int rc = check_launch("k_fill_u32")) return rc;
     }
-    elmo::k_label_hist<<<(B + 255) / 256, elmo::kThreads, 0, st>>>(indptr, indices, B, p.L, nnz, cnt, flag);
+    const int row_grid = (B * elmo::kRowLanes + elmo::kThreads - 1) / elmo::kThreads;
+    elmo::k_label_hist<<<row_grid, elmo::kThreads, 0, st>>>(indptr, indices, B, p.L, nnz, cnt, flag);
     if (int rc = check_launch("k_label_hist")) return rc;
     elmo::k_label_scan<<<1, 1024, 0, st>>>(cnt, p.ntiles, ptr, cur);
     if (int rc = check_launch("k_label_scan")) return rc;
-    elmo::k_label_scatter<<<(B + 255) / 256, elmo::kThreads, 0, st>>>(indptr, indices, B, p.L, nnz, cur, pos);
+    elmo::k_label_scatter<<<row_grid, elmo::kThreads, 0, st>>>(indptr, indices, B, p.L, nnz, cur, pos);
     if (int rc = check_launch("k_label_scatter")) return rc;
     if (flag) h->validated_step_pending = true;
   }

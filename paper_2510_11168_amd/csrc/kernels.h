@@ -58,55 +58,58 @@ __global__ void __launch_bounds__(kThreads) k_prep_x(const uint16_t* __restrict_
 // logits epilogue of a tile finds its few positives with two loads (Algorithm 1 filters the
 // COO pairs of each chunk; here the filter is a counting sort done once per step).
 // ---------------------------------------------------------------------------------------------
+// Eight lanes share a sample row (its positives are few, and one lane per row would walk them as a
+// chain of dependent loads).
+constexpr int kRowLanes = 8;
 __global__ void __launch_bounds__(kThreads) k_label_hist(const int* __restrict__ indptr, const int* __restrict__ indices,
                                                          int B, int64_t L, int64_t nnz, int* __restrict__ cnt,
                                                          int* __restrict__ bad) {
-  const int b = blockIdx.x * kThreads + threadIdx.x;
+  const int t = blockIdx.x * kThreads + threadIdx.x;
+  const int b = t / kRowLanes, sub = t % kRowLanes;
   if (b >= B) return;
   const int p0 = indptr[b], p1 = indptr[b + 1];
-  if (p0 < 0 || p1 < p0 || p1 > nnz) { if (bad) atomicOr(bad, 1); return; }
-  int prev = -1;
-  for (int p = p0; p < p1; ++p) {
+  if (p0 < 0 || p1 < p0 || p1 > nnz) { if (bad && sub == 0) atomicOr(bad, 1); return; }
+  for (int p = p0 + sub; p < p1; p += kRowLanes) {
     const int l = indices[p];
-    if (l < 0 || l >= L || l <= prev) { if (bad) atomicOr(bad, 2); if (l < 0 || l >= L) continue; }
-    prev = l;
-    atomicAdd(&cnt[l >> 7], 1);
+    const bool in_range = l >= 0 && l < L;
+    if (bad && (!in_range || (p > p0 && l <= indices[p - 1]))) atomicOr(bad, 2);   // out of range, or not strictly ascending
+    if (in_range) atomicAdd(&cnt[l >> 7], 1);
   }
 }
-// Exclusive scan of cnt[0..nb) into ptr[0..nb] (ptr[nb] = total) and cur[0..nb) = ptr. One workgroup.
+// Exclusive scan of cnt[0..nb) into ptr[0..nb] (ptr[nb] = total) and cur[0..nb) = ptr. One workgroup:
+// every thread sums a contiguous run of bins, the 1024 run totals are scanned in LDS.
 __global__ void __launch_bounds__(1024) k_label_scan(const int* __restrict__ cnt, int nb, int* __restrict__ ptr, int* __restrict__ cur) {
   __shared__ int part[1024];
-  __shared__ int carry_s;
-  if (threadIdx.x == 0) carry_s = 0;
+  const int tid = threadIdx.x;
+  const int per = (nb + 1023) / 1024;
+  const int i0 = min(tid * per, nb), i1 = min(i0 + per, nb);
+  int sum = 0;
+  for (int i = i0; i < i1; ++i) sum += cnt[i];
+  part[tid] = sum;
   __syncthreads();
-  for (int base = 0; base < nb; base += 1024) {
-    const int i = base + threadIdx.x;
-    const int v = i < nb ? cnt[i] : 0;
-    part[threadIdx.x] = v;
+  for (int o = 1; o < 1024; o <<= 1) {
+    const int t = tid >= o ? part[tid - o] : 0;
     __syncthreads();
-    for (int o = 1; o < 1024; o <<= 1) {
-      const int t = threadIdx.x >= o ? part[threadIdx.x - o] : 0;
-      __syncthreads();
-      part[threadIdx.x] += t;
-      __syncthreads();
-    }
-    const int carry = carry_s;
-    const int excl = carry + part[threadIdx.x] - v;
-    if (i < nb) { ptr[i] = excl; cur[i] = excl; }
-    __syncthreads();
-    if (threadIdx.x == 1023) carry_s = carry + part[1023];
+    part[tid] += t;
     __syncthreads();
   }
-  if (threadIdx.x == 0) ptr[nb] = carry_s;
+  int run = part[tid] - sum;                       // exclusive prefix of this thread's run
+  for (int i = i0; i < i1; ++i) {
+    ptr[i] = run;
+    cur[i] = run;
+    run += cnt[i];
+  }
+  if (tid == 1023) ptr[nb] = part[1023];
 }
 __global__ void __launch_bounds__(kThreads) k_label_scatter(const int* __restrict__ indptr, const int* __restrict__ indices,
                                                             int B, int64_t L, int64_t nnz, int* __restrict__ cur,
                                                             int2* __restrict__ pos) {
-  const int b = blockIdx.x * kThreads + threadIdx.x;
+  const int t = blockIdx.x * kThreads + threadIdx.x;
+  const int b = t / kRowLanes, sub = t % kRowLanes;
   if (b >= B) return;
   const int p0 = indptr[b], p1 = indptr[b + 1];
   if (p0 < 0 || p1 < p0 || p1 > nnz) return;
-  for (int p = p0; p < p1; ++p) {
+  for (int p = p0 + sub; p < p1; p += kRowLanes) {
     const int l = indices[p];
     if (l < 0 || l >= L) continue;
     const int slot = atomicAdd(&cur[l >> 7], 1);
