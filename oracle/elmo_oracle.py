@@ -319,8 +319,14 @@ def update_rows(W_bits, comp_bits, dW, lr, fmt, flags, seed, step, elem):
 
 
 def head_step(W_bits, comp_bits, X_bits, indptr, indices, lr, seed, step, fmt, flags,
-              label_ids=None, g_exact=False):
+              label_ids=None, g_exact=False, kahan_rows=None):
     """One training step of the head on the given weight rows.
+
+    kahan_rows (with FLAG_KAHAN; None = every label): only the labels with id < kahan_rows carry a
+    compensation value -- the paper's "Kahan summation for head labels" (appendix "Precision
+    Recovery for Sensitive Applications"), with the labels numbered by falling frequency so that
+    the top-p% head is a prefix.  The other labels are updated as without the flag; their rows of
+    comp_bits are ignored and come back unchanged.
 
     W_bits [n, d] (uint16 BF16 patterns or uint8 E4M3 codes), comp_bits [n, d] uint16 or None,
     X_bits [B, d] uint16 (BF16), CSR positives over global label ids.  label_ids gives the global
@@ -344,7 +350,16 @@ def head_step(W_bits, comp_bits, X_bits, indptr, indices, lr, seed, step, fmt, f
     dX = G @ Wd            # weights before the update (the update comes later in Algorithm 1)
     dW = G.T @ X           # BF16 inputs, summed over the batch, no 1/B
     elem = label_ids[:, None] * np.int64(d) + np.arange(d, dtype=np.int64)[None, :]
-    Wn, cn = update_rows(W_bits, comp_bits, dW, lr, fmt, flags, seed, step, elem)
+    if (flags & FLAG_KAHAN) and kahan_rows is not None:
+        head = label_ids < kahan_rows
+        comp_bits = np.asarray(comp_bits)
+        Wn, cn = np.array(W_bits, copy=True), np.array(comp_bits, copy=True)
+        if head.any():
+            Wn[head], cn[head] = update_rows(W_bits[head], comp_bits[head], dW[head], lr, fmt, flags, seed, step, elem[head])
+        if (~head).any():
+            Wn[~head], _ = update_rows(W_bits[~head], None, dW[~head], lr, fmt, flags & ~FLAG_KAHAN, seed, step, elem[~head])
+    else:
+        Wn, cn = update_rows(W_bits, comp_bits, dW, lr, fmt, flags, seed, step, elem)
     return dict(Z=Z, G=G, dX_partial=dX, dW=dW, W_new=Wn, comp_new=cn, loss=bce_loss(Z, Y))
 
 

@@ -207,6 +207,39 @@ def test_label_subset_gives_rows_of_full_result():
     np.testing.assert_allclose(Z_rows, full["Z"][[1, 4]], atol=1e-13)
 
 
+@pytest.mark.parametrize("fmt", [o.BF16, o.E4M3])
+def test_head_only_kahan_is_kahan_on_the_prefix_and_plain_elsewhere(fmt):
+    """Kahan summation for head labels (appendix "Precision Recovery for Sensitive Applications"):
+    a label's update depends on no other label, so with compensation on labels < k only, those rows
+    must equal the rows of the all-Kahan step and the others the rows of the step without
+    compensation; k = L and k = 0 are the two plain modes themselves."""
+    L, k = 64, 24
+    X_bits, W_bits, indptr, indices = _tiny(L=L, fmt=fmt, w_std=0.05)
+    rng = np.random.default_rng(3)
+    comp = o.round_bf16((rng.standard_normal(W_bits.shape) * 1e-4).astype(np.float32))
+    flags = o.FLAG_SR | o.FLAG_KAHAN
+    args = (X_bits, indptr, indices, 0.05, 7, 2, fmt)
+    allk = o.head_step(W_bits, comp, *args, flags)
+    none = o.head_step(W_bits, None, *args, o.FLAG_SR)
+    head = o.head_step(W_bits, comp, *args, flags, kahan_rows=k)
+    np.testing.assert_array_equal(head["W_new"][:k], allk["W_new"][:k])
+    np.testing.assert_array_equal(head["comp_new"][:k], allk["comp_new"][:k])
+    np.testing.assert_array_equal(head["W_new"][k:], none["W_new"][k:])
+    np.testing.assert_array_equal(head["comp_new"][k:], comp[k:])          # untouched
+    assert np.any(allk["W_new"][k:] != none["W_new"][k:])                  # the two modes do differ
+    np.testing.assert_array_equal(head["dX_partial"], allk["dX_partial"])  # gradients do not depend on it
+    full = o.head_step(W_bits, comp, *args, flags, kahan_rows=L)
+    np.testing.assert_array_equal(full["W_new"], allk["W_new"])
+    np.testing.assert_array_equal(full["comp_new"], allk["comp_new"])
+    zero = o.head_step(W_bits, comp, *args, flags, kahan_rows=0)
+    np.testing.assert_array_equal(zero["W_new"], none["W_new"])
+    # a label subset straddling the boundary still gives the rows of the full result
+    ids = np.array([3, 23, 24, 40])
+    part = o.head_step(W_bits[ids], comp[ids], *args, flags, label_ids=ids, kahan_rows=k)
+    np.testing.assert_array_equal(part["W_new"], head["W_new"][ids])
+    np.testing.assert_array_equal(part["comp_new"], head["comp_new"][ids])
+
+
 def test_different_steps_draw_different_roundings_same_step_repeats():
     X_bits, W_bits, indptr, indices = _tiny(fmt=o.E4M3, w_std=0.05)
     a = o.head_step(W_bits, None, X_bits, indptr, indices, 0.05, 1, 0, o.E4M3, o.FLAG_SR)["W_new"]
