@@ -67,6 +67,8 @@ def parse():
     ap.add_argument("--batch", type=int, default=None, help="override B (xl_sweep: 32 / 128 / 4096)")
     ap.add_argument("--chunk", type=int, default=None, help="override the label chunk")
     ap.add_argument("--no-kahan", action="store_true", help="xl_sweep without the compensation buffer")
+    ap.add_argument("--kahan-head", type=float, default=None,
+                    help="compensation for this fraction of the labels only (the most frequent ones, ids 0..)")
     ap.add_argument("--no-dx", action="store_true", help="skip the input gradient (weights-only step)")
     ap.add_argument("--topk", type=int, default=0, help="also time elmo_head_topk with this k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -114,7 +116,11 @@ def main():
     n_steps, n_warm = args.steps, args.warmup
 
     # ---------------- head + weights (N(0, 0.02) drawn on the device, rounded by the library)
-    head = b.Head(L, d, cfg.fmt, cfg.chunk, cfg.flags, B, 64 * B, device=dev)
+    kahan_rows = 0
+    if kahan and args.kahan_head is not None:
+        kahan_rows = min(L, max(128, int(round(args.kahan_head * L / 128.0)) * 128))
+    kahan_frac = (kahan_rows or L) / L if kahan else 0.0      # share of the labels that carry compensation
+    head = b.Head(L, d, cfg.fmt, cfg.chunk, cfg.flags, B, 64 * B, device=dev, kahan_rows=kahan_rows)
     g = torch.Generator(device=dev)
     g.manual_seed(0)
     W = head.weights()
@@ -163,7 +169,7 @@ def main():
     for name, flops, byts, peak_tf in (
         ("logits", 2.0 * B * n_avg * d, n_avg * d * s_w + B * n_avg * 2 + B * d * s_w, PEAK_FP8_TFLOPS if fp8 else PEAK_BF16_TFLOPS),
         ("dx", 2.0 * B * n_avg * d, n_avg * d * s_w + B * n_avg * 2, PEAK_BF16_TFLOPS),
-        ("update", (4.0 if fused else 2.0) * B * n_avg * d, n_avg * d * (2 * s_w + (4 if kahan else 0)) + B * n_avg * 2 + B * d * 2,
+        ("update", (4.0 if fused else 2.0) * B * n_avg * d, n_avg * d * (2 * s_w + 4 * kahan_frac) + B * n_avg * 2 + B * d * 2,
          PEAK_BF16_TFLOPS),
     ):
         ms, n = prof[name]
@@ -186,7 +192,7 @@ def main():
         roof = {"bound": "hbm", "achieved": kd["algo_gbs"], "unit": "GB/s", "peak": PEAK_HBM_GBS, "frac": kd["hbm_frac"]}
     # committed counter summaries exist for exactly these two workloads
     profile = None
-    if not args.no_dx and not args.no_kahan:
+    if not args.no_dx and not args.no_kahan and args.kahan_head is None:
         if args.workload == "xl" and not (args.batch or args.chunk):
             profile = "head_step_xl_fp8_B1024.txt"
         elif args.workload == "xl_sweep" and B == 128 and cfg.chunk == 262144:
@@ -196,7 +202,7 @@ def main():
     # whole-step figures of the headline metric: flop/s against the FP8 MFMA peak (6 B L d flop per
     # step) and weight read-modify-write bytes against HBM peak
     step_flops = (6.0 if not args.no_dx else 4.0) * B * L * d
-    step_bytes = L * d * (2 * s_w + (4 if kahan else 0))
+    step_bytes = L * d * (2 * s_w + 4 * kahan_frac)
     whole = {
         "step_tflops": step_flops / ms_per_step * 1e-9,
         "frac_of_fp8_mfma_peak": step_flops / ms_per_step * 1e-9 / PEAK_FP8_TFLOPS,
@@ -236,7 +242,8 @@ def main():
         Wb = Wb.view(np.uint16) if not fp8 else Wb
         Cb = np.zeros((n_s, d), np.uint16) if kahan else None
         t2 = time.perf_counter()
-        o.head_step(Wb, Cb, X0, ip0, ix0, cfg.lr, 0, 0, cfg.fmt, cfg.flags, label_ids=np.arange(n_s))
+        o.head_step(Wb, Cb, X0, ip0, ix0, cfg.lr, 0, 0, cfg.fmt, cfg.flags, label_ids=np.arange(n_s),
+                    kahan_rows=(kahan_rows or None) if kahan else None)
         dt = time.perf_counter() - t2
         cpu = {"value": B / (dt * L / n_s), "unit": "samples/s", "cores": int(cores), "kind": "oracle",
                "sample": f"one full oracle step (FP64 logits, gradients, update with the same Philox fields) on labels "
@@ -250,7 +257,8 @@ def main():
         "dtype": "fp8" if fp8 else "bf16",
         "data": "synthetic",
         "config": {"workload": cfg.name, "L": L, "d": d, "B": B, "chunk": cfg.chunk, "chunks": n_chunks,
-                   "weights": "e4m3" if fp8 else "bf16", "kahan_bf16": kahan, "stochastic_rounding": bool(cfg.flags & synth.FLAG_SR),
+                   "weights": "e4m3" if fp8 else "bf16", "kahan_bf16": kahan, "kahan_label_fraction": kahan_frac,
+                   "stochastic_rounding": bool(cfg.flags & synth.FLAG_SR),
                    "positives_per_sample": float(len(batches[0][2]) / B), "zipf_s": cfg.zipf_s, "lr": cfg.lr,
                    "input_gradient": not args.no_dx},
         "roofline": roof, "kernels": kern, "whole_step": whole, "cpu_baseline": cpu,

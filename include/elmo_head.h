@@ -36,8 +36,9 @@ typedef struct elmo_head elmo_head_t; /* opaque, host-side */
 enum { ELMO_BF16 = 0, ELMO_FP8_E4M3 = 1 };
 
 /* ELMO_SR: the update rounds with stochastic rounding (Eq. 1), otherwise to nearest even.
- * ELMO_KAHAN: a BF16 compensation buffer of the shape of W carries the rounding error of every
- *             update into the next one (the recurrence of Section 3 with s = w, v = -lr*grad).
+ * ELMO_KAHAN: a BF16 compensation buffer carries the rounding error of every update into the
+ *             next one (the recurrence of Section 3 with s = w, v = -lr*grad), for all labels or,
+ *             with elmo_head_opts.kahan_rows, for the head labels only.
  * ELMO_VALIDATE: each step checks the label data on the device (ids inside [0, L), ascending
  *             within a row) and the NEXT call on the head reads that flag back (one blocking
  *             4-byte copy) and fails with -4 if it was raised. */
@@ -49,8 +50,13 @@ typedef struct {
   int64_t max_nnz;        /* largest number of positives in one batch (>= 1) */
   void* W;                /* [L, d] weights in weight_dtype, updated in place by every step */
   size_t W_bytes;
-  void* comp;             /* [L, d] BF16 compensation, required iff ELMO_KAHAN, start at zero */
+  void* comp;             /* [kahan_rows, d] BF16 compensation, required iff ELMO_KAHAN, start at zero */
   size_t comp_bytes;
+  int64_t kahan_rows;     /* with ELMO_KAHAN: only the labels [0, kahan_rows) carry compensation, the rest
+                             are updated as without the flag ("Kahan summation for head labels", appendix
+                             "Precision Recovery for Sensitive Applications": number the labels by falling
+                             frequency and the top-p% head is this prefix; memory 2 bytes x kahan_rows x d).
+                             0 = every label.  Otherwise L or a multiple of 128.  Must be 0 without the flag. */
   void* workspace;        /* scratch; contents need not survive between calls */
   size_t workspace_bytes;
 } elmo_head_opts;
@@ -60,8 +66,8 @@ typedef struct {
  * plus O(max_B * d) staging for the inputs and the input-gradient partial sums, plus the
  * per-batch label index.  Any of the three output pointers may be NULL. */
 int elmo_head_sizes(int64_t L, int32_t d, int weight_dtype, int64_t chunk, int32_t max_B,
-                    int64_t max_nnz, uint32_t flags, size_t* W_bytes, size_t* comp_bytes,
-                    size_t* workspace_bytes);
+                    int64_t max_nnz, uint32_t flags, int64_t kahan_rows, size_t* W_bytes,
+                    size_t* comp_bytes, size_t* workspace_bytes);
 
 /* Bytes of the logit / logit-gradient buffer for `batch` samples and `labels` labels held in
  * 16 bits, batch * labels * 2 -- the quantity Section 4.4 divides by the number of chunks. */

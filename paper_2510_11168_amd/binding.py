@@ -38,7 +38,7 @@ class elmo_head_opts(C.Structure):
     _fields_ = [
         ("flags", C.c_uint32), ("max_B", C.c_int32), ("max_nnz", C.c_int64),
         ("W", C.c_void_p), ("W_bytes", C.c_size_t),
-        ("comp", C.c_void_p), ("comp_bytes", C.c_size_t),
+        ("comp", C.c_void_p), ("comp_bytes", C.c_size_t), ("kahan_rows", C.c_int64),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
     ]
 
@@ -48,7 +48,7 @@ _lib.elmo_last_error.argtypes = []
 _lib.elmo_logit_buffer_bytes.restype = C.c_size_t
 _lib.elmo_logit_buffer_bytes.argtypes = [C.c_int64, C.c_int64]
 _lib.elmo_head_sizes.restype = C.c_int
-_lib.elmo_head_sizes.argtypes = [C.c_int64, C.c_int32, C.c_int, C.c_int64, C.c_int32, C.c_int64, C.c_uint32,
+_lib.elmo_head_sizes.argtypes = [C.c_int64, C.c_int32, C.c_int, C.c_int64, C.c_int32, C.c_int64, C.c_uint32, C.c_int64,
                                  C.POINTER(C.c_size_t), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
 _lib.elmo_head_create.restype = C.c_int
 _lib.elmo_head_create.argtypes = [C.c_int64, C.c_int32, C.c_int, C.c_int64, C.POINTER(elmo_head_opts),
@@ -101,17 +101,18 @@ def elmo_logit_buffer_bytes(batch: int, labels: int) -> int:
     return int(_lib.elmo_logit_buffer_bytes(batch, labels))
 
 
-def elmo_head_sizes(L, d, weight_dtype, chunk, max_B, max_nnz, flags):
+def elmo_head_sizes(L, d, weight_dtype, chunk, max_B, max_nnz, flags, kahan_rows=0):
     w, c, s = C.c_size_t(), C.c_size_t(), C.c_size_t()
-    _check(_lib.elmo_head_sizes(L, d, weight_dtype, chunk, max_B, max_nnz, flags, C.byref(w), C.byref(c), C.byref(s)))
+    _check(_lib.elmo_head_sizes(L, d, weight_dtype, chunk, max_B, max_nnz, flags, kahan_rows, C.byref(w), C.byref(c), C.byref(s)))
     return w.value, c.value, s.value
 
 
-def elmo_head_create(L, d, weight_dtype, chunk, *, flags, max_B, max_nnz, W, comp, workspace) -> int:
+def elmo_head_create(L, d, weight_dtype, chunk, *, flags, max_B, max_nnz, W, comp, workspace, kahan_rows=0) -> int:
     """W, comp, workspace: 1-D torch.uint8 device tensors (comp may be None).  Returns the handle."""
     o = elmo_head_opts(flags=flags, max_B=max_B, max_nnz=max_nnz,
                        W=_ptr(W), W_bytes=0 if W is None else W.numel() * W.element_size(),
                        comp=_ptr(comp), comp_bytes=0 if comp is None else comp.numel() * comp.element_size(),
+                       kahan_rows=kahan_rows,
                        workspace=_ptr(workspace),
                        workspace_bytes=0 if workspace is None else workspace.numel() * workspace.element_size())
     h = C.c_void_p()
@@ -163,16 +164,17 @@ def elmo_philox4x32_10(ctr, key):
 class Head:
     """Allocates W / comp / workspace as torch device tensors and keeps the handle alive."""
 
-    def __init__(self, L, d, weight_dtype, chunk, flags, max_B, max_nnz, device="cuda:0"):
+    def __init__(self, L, d, weight_dtype, chunk, flags, max_B, max_nnz, device="cuda:0", kahan_rows=0):
         self.L, self.d, self.fmt, self.chunk, self.flags = L, d, weight_dtype, chunk, flags
         self.max_B, self.max_nnz = max_B, max_nnz
-        wb, cb, sb = elmo_head_sizes(L, d, weight_dtype, chunk, max_B, max_nnz, flags)
+        self.kahan_rows = (kahan_rows or L) if flags & ELMO_KAHAN else 0   # label rows that carry compensation
+        wb, cb, sb = elmo_head_sizes(L, d, weight_dtype, chunk, max_B, max_nnz, flags, kahan_rows)
         self.W = torch.zeros(wb, dtype=torch.uint8, device=device)
         self.comp = torch.zeros(cb, dtype=torch.uint8, device=device) if cb else None
         self.workspace = torch.empty(sb, dtype=torch.uint8, device=device)
         self.bytes = (wb, cb, sb)
         self.h = elmo_head_create(L, d, weight_dtype, chunk, flags=flags, max_B=max_B, max_nnz=max_nnz,
-                                  W=self.W, comp=self.comp, workspace=self.workspace)
+                                  W=self.W, comp=self.comp, workspace=self.workspace, kahan_rows=kahan_rows)
 
     def weights(self):
         """[L, d] view of the raw weight bits: uint8 codes (E4M3) or int16 patterns (BF16)."""
@@ -181,7 +183,7 @@ class Head:
         return self.W.view(torch.int16).view(self.L, self.d)
 
     def compensation(self):
-        return None if self.comp is None else self.comp.view(torch.int16).view(self.L, self.d)
+        return None if self.comp is None else self.comp.view(torch.int16).view(self.kahan_rows, self.d)
 
     def step(self, X, indptr, indices, lr, seed, step, dX_out=None, loss_out=None, stream=None):
         elmo_head_step(self.h, X, X.shape[0], indptr, indices, int(indices.numel()), lr, seed, step,

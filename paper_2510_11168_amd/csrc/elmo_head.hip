@@ -38,13 +38,14 @@ inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 // buffer is ever alive; everything else is O(max_B * d) or O(L / 128) integers).
 struct Plan {
   int64_t L; int d; int fmt; int64_t chunk; int maxB; int64_t max_nnz; uint32_t flags;
+  int64_t kahan_rows;                   // leading label rows that carry compensation (0 without ELMO_KAHAN)
   int Bp_max, tiles_b_max, ntiles;      // padded batch, batch tiles, 128-label tiles of the whole head
   int dx_rows;                          // rows of FP32 input-gradient partials (slices x padded batch)
   size_t off_xq, off_xt, off_g, off_dx, off_loss, off_cnt, off_ptr, off_cur, off_pos, off_flag, off_topk, total;
   size_t W_bytes, comp_bytes;
 };
 
-int make_plan(int64_t L, int d, int fmt, int64_t chunk, int maxB, int64_t max_nnz, uint32_t flags, Plan& p) {
+int make_plan(int64_t L, int d, int fmt, int64_t chunk, int maxB, int64_t max_nnz, uint32_t flags, int64_t kahan_rows, Plan& p) {
   if (L < 1) return fail(-1, "L must be >= 1 (got %lld)", (long long)L);
   if (L > (int64_t)1 << 31) return fail(-1, "L must fit 31 bits (got %lld)", (long long)L);
   if (d < 128 || d % 128 != 0) return fail(-1, "d must be a positive multiple of 128 (got %d)", d);
@@ -54,7 +55,12 @@ int make_plan(int64_t L, int d, int fmt, int64_t chunk, int maxB, int64_t max_nn
   if (max_nnz < 1 || max_nnz > ((int64_t)1 << 30)) return fail(-1, "max_nnz must be in [1, 2^30] (got %lld)", (long long)max_nnz);
   if (fmt != ELMO_BF16 && fmt != ELMO_FP8_E4M3) return fail(-2, "unsupported weight_dtype %d", fmt);
   if (flags & ~(uint32_t)(ELMO_SR | ELMO_KAHAN | ELMO_VALIDATE)) return fail(-2, "unknown flag bits 0x%x", flags);
+  if (kahan_rows < 0 || kahan_rows > L) return fail(-1, "kahan_rows must be in [0, L] (got %lld)", (long long)kahan_rows);
+  if (!(flags & ELMO_KAHAN) && kahan_rows != 0) return fail(-1, "kahan_rows = %lld without ELMO_KAHAN", (long long)kahan_rows);
+  if (kahan_rows != 0 && kahan_rows != L && kahan_rows % 128 != 0)
+    return fail(-1, "kahan_rows must be 0 (all labels), L, or a multiple of 128 (got %lld)", (long long)kahan_rows);
   p.L = L; p.d = d; p.fmt = fmt; p.chunk = chunk; p.maxB = maxB; p.max_nnz = max_nnz; p.flags = flags;
+  p.kahan_rows = (flags & ELMO_KAHAN) ? (kahan_rows ? kahan_rows : L) : 0;
   p.Bp_max = round_up(maxB, 64);
   p.tiles_b_max = (p.Bp_max + 255) / 256;      // 256-sample tiles of the matrix products
   p.ntiles = (int)((L + 127) / 128);
@@ -77,7 +83,7 @@ int make_plan(int64_t L, int d, int fmt, int64_t chunk, int maxB, int64_t max_nn
   p.off_topk = o; o += align256(elmo::topk_scratch_bytes(p.Bp_max, chunk_eff));
   p.total = o;
   p.W_bytes = (size_t)L * d * (fmt == ELMO_FP8_E4M3 ? 1 : 2);
-  p.comp_bytes = (flags & ELMO_KAHAN) ? (size_t)L * d * 2 : 0;
+  p.comp_bytes = (size_t)p.kahan_rows * d * 2;
   return 0;
 }
 
@@ -127,9 +133,9 @@ size_t elmo_logit_buffer_bytes(int64_t batch, int64_t labels) {
 }
 
 int elmo_head_sizes(int64_t L, int32_t d, int weight_dtype, int64_t chunk, int32_t max_B, int64_t max_nnz,
-                    uint32_t flags, size_t* W_bytes, size_t* comp_bytes, size_t* workspace_bytes) {
+                    uint32_t flags, int64_t kahan_rows, size_t* W_bytes, size_t* comp_bytes, size_t* workspace_bytes) {
   Plan p;
-  const int rc = make_plan(L, d, weight_dtype, chunk, max_B, max_nnz, flags, p);
+  const int rc = make_plan(L, d, weight_dtype, chunk, max_B, max_nnz, flags, kahan_rows, p);
   if (rc) return rc;
   if (W_bytes) *W_bytes = p.W_bytes;
   if (comp_bytes) *comp_bytes = p.comp_bytes;
@@ -141,7 +147,7 @@ int elmo_head_create(int64_t L, int32_t d, int weight_dtype, int64_t chunk, cons
                      elmo_head_t** out) {
   if (!opts || !out) return fail(-1, "opts and out must not be NULL");
   Plan p;
-  const int rc = make_plan(L, d, weight_dtype, chunk, opts->max_B, opts->max_nnz, opts->flags, p);
+  const int rc = make_plan(L, d, weight_dtype, chunk, opts->max_B, opts->max_nnz, opts->flags, opts->kahan_rows, p);
   if (rc) return rc;
   if (!opts->W || opts->W_bytes < p.W_bytes) return fail(-1, "W buffer missing or smaller than %zu bytes", p.W_bytes);
   if ((opts->flags & ELMO_KAHAN) && (!opts->comp || opts->comp_bytes < p.comp_bytes))
@@ -393,7 +399,6 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
   const int a_rows = fp8 ? Bp : B;
   for (int64_t c0 = 0; c0 < p.L; c0 += p.chunk) {
     const int n = (int)std::min<int64_t>(p.chunk, p.L - c0);
-    const int tiles_l = (n + 255) / 256;
     char* Wc = h->W + (size_t)c0 * d * esz;
     uint16_t* Cc = h->comp ? (uint16_t*)h->comp + (size_t)c0 * d : nullptr;
     const int tile0 = (int)(c0 / 128);
@@ -410,17 +415,28 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
       }
       if (int rc = check_launch("k_logits")) return rc;
     }
+    // Update of the chunk in at most two parts: labels below kahan_rows carry compensation
+    // (Kahan summation for head labels), the others are updated without it.
+    const bool sr = p.flags & ELMO_SR;
+    const int n_head = (int)std::max<int64_t>(0, std::min<int64_t>(n, p.kahan_rows - c0));
     if (small_batch) {
       prof.mark(st, CLS_UPDATE);
-      const int ntiles32 = (n + 31) / 32, tpg = (ntiles32 + label_groups - 1) / label_groups;
-      const int groups_used = (ntiles32 + tpg - 1) / tpg;
-      const bool sr = p.flags & ELMO_SR, kahan = p.flags & ELMO_KAHAN;
-      const uint64_t elem0 = (uint64_t)c0 * (uint64_t)d;
-      int rc;
-      if (fp8) rc = launch_dx_update<elmo::FMT_E4M3>(st, groups_used * col_blocks, sr, kahan, dX_out != nullptr, (const char*)Gt, (const char*)XT, Wc, Cc, dXacc, n, d, Bp, lr, seed, step, elem0, tpg);
-      else rc = launch_dx_update<elmo::FMT_BF16>(st, groups_used * col_blocks, sr, kahan, dX_out != nullptr, (const char*)Gt, (const char*)XT, Wc, Cc, dXacc, n, d, Bp, lr, seed, step, elem0, tpg);
-      if (rc) return rc;
-      if (int rc2 = check_launch("k_dx_update")) return rc2;
+      for (int part = 0; part < 2; ++part) {
+        const int l_off = part ? n_head : 0, n_part = part ? n - n_head : n_head;   // n_head is a multiple of 32 or all of n
+        if (n_part == 0) continue;
+        const bool kahan = part == 0;
+        const int ntiles32 = (n_part + 31) / 32, tpg = (ntiles32 + label_groups - 1) / label_groups;
+        const int groups_used = (ntiles32 + tpg - 1) / tpg;
+        const uint64_t elem0 = (uint64_t)(c0 + l_off) * (uint64_t)d;
+        const char* Gp = (const char*)(Gt + (size_t)l_off * Bp);
+        char* Wp = Wc + (size_t)l_off * d * esz;
+        uint16_t* Cp = kahan ? Cc + (size_t)l_off * d : nullptr;
+        int rc;
+        if (fp8) rc = launch_dx_update<elmo::FMT_E4M3>(st, groups_used * col_blocks, sr, kahan, dX_out != nullptr, Gp, (const char*)XT, Wp, Cp, dXacc, n_part, d, Bp, lr, seed, step, elem0, tpg);
+        else rc = launch_dx_update<elmo::FMT_BF16>(st, groups_used * col_blocks, sr, kahan, dX_out != nullptr, Gp, (const char*)XT, Wp, Cp, dXacc, n_part, d, Bp, lr, seed, step, elem0, tpg);
+        if (rc) return rc;
+        if (int rc2 = check_launch("k_dx_update")) return rc2;
+      }
       continue;
     }
     if (dX_out) {
@@ -431,12 +447,17 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
       if (int rc = check_launch("k_dx")) return rc;
     }
     prof.mark(st, CLS_UPDATE);
-    {
-      const int grid = tiles_l * tiles_j;
-      const bool sr = p.flags & ELMO_SR, kahan = p.flags & ELMO_KAHAN;
-      const uint64_t elem0 = (uint64_t)c0 * (uint64_t)d;
-      if (fp8) launch_update<elmo::FMT_E4M3>(st, grid, sr, kahan, (const char*)Gt, (const char*)XT, Wc, Cc, n, d, Bp, lr, seed, step, elem0);
-      else launch_update<elmo::FMT_BF16>(st, grid, sr, kahan, (const char*)Gt, (const char*)XT, Wc, Cc, n, d, Bp, lr, seed, step, elem0);
+    for (int part = 0; part < 2; ++part) {
+      const int l_off = part ? n_head : 0, n_part = part ? n - n_head : n_head;
+      if (n_part == 0) continue;
+      const bool kahan = part == 0;
+      const int grid = ((n_part + 255) / 256) * tiles_j;
+      const uint64_t elem0 = (uint64_t)(c0 + l_off) * (uint64_t)d;
+      const char* Gp = (const char*)(Gt + (size_t)l_off * Bp);
+      char* Wp = Wc + (size_t)l_off * d * esz;
+      uint16_t* Cp = kahan ? Cc + (size_t)l_off * d : nullptr;
+      if (fp8) launch_update<elmo::FMT_E4M3>(st, grid, sr, kahan, Gp, (const char*)XT, Wp, Cp, n_part, d, Bp, lr, seed, step, elem0);
+      else launch_update<elmo::FMT_BF16>(st, grid, sr, kahan, Gp, (const char*)XT, Wp, Cp, n_part, d, Bp, lr, seed, step, elem0);
       if (int rc = check_launch("k_update")) return rc;
     }
   }

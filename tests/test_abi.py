@@ -49,6 +49,23 @@ def test_logit_buffer_closed_form_reproduces_the_papers_figures(b):
     assert round(w16 / 2**30) == 4 and round(w8 / 2**30) == 2
 
 
+def test_head_only_kahan_costs_two_bytes_per_head_weight(b):
+    """Kahan summation for head labels (appendix "Precision Recovery for Sensitive Applications"):
+    compensation for the top-p% labels adds about 2 x p% of the FP8 weight memory."""
+    L, d = 1_305_600, 768
+    k = L // 5                                   # 20 % head, a multiple of 128 here
+    assert k % 128 == 0
+    w8, c_all, _ = b.elmo_head_sizes(L, d, b.ELMO_FP8_E4M3, 131072, 512, 8192, b.ELMO_KAHAN)
+    _, c_head, ws = b.elmo_head_sizes(L, d, b.ELMO_FP8_E4M3, 131072, 512, 8192, b.ELMO_KAHAN, k)
+    assert c_all == 2 * w8 and c_head == k * d * 2
+    assert abs(c_head / w8 - 2 * 0.2) < 1e-3
+    assert b.elmo_head_sizes(L, d, b.ELMO_FP8_E4M3, 131072, 512, 8192, b.ELMO_KAHAN, L)[1] == c_all
+    for bad_k, flags in ((100, b.ELMO_KAHAN), (-128, b.ELMO_KAHAN), (L + 128, b.ELMO_KAHAN), (128, 0)):
+        with pytest.raises(b.ElmoError) as e:
+            b.elmo_head_sizes(L, d, b.ELMO_FP8_E4M3, 131072, 512, 8192, flags, bad_k)
+        assert e.value.code == -1
+
+
 def test_workspace_is_one_chunks_buffer_plus_small_terms(b):
     L, d, B, chunk = 3_000_000, 768, 1024, 131072
     _, _, ws = b.elmo_head_sizes(L, d, b.ELMO_FP8_E4M3, chunk, B, 16384, b.ELMO_SR)

@@ -112,14 +112,14 @@ def test_quantize_empty_is_a_no_op(b):
 class Case:
     """A head on the device initialised from host bits, plus the host copies the oracle needs."""
 
-    def __init__(self, b, L, d, fmt, chunk, flags, B, max_nnz=None, seed=0, w_std=0.02, comp_std=0.0):
+    def __init__(self, b, L, d, fmt, chunk, flags, B, max_nnz=None, seed=0, w_std=0.02, comp_std=0.0, kahan_rows=0):
         rng = np.random.default_rng([seed, L, d])
         self.b, self.L, self.d, self.fmt, self.flags = b, L, d, fmt, flags
         self.W0 = o.quantize(synth.make_w0_f32(rng, L, d, w_std), fmt)
         self.C0 = None
         if flags & o.FLAG_KAHAN:
-            self.C0 = o.round_bf16((rng.standard_normal((L, d)) * comp_std).astype(np.float32))
-        self.head = b.Head(L, d, fmt, chunk, flags, B, max_nnz or 64 * B)
+            self.C0 = o.round_bf16((rng.standard_normal((kahan_rows or L, d)) * comp_std).astype(np.float32))
+        self.head = b.Head(L, d, fmt, chunk, flags, B, max_nnz or 64 * B, kahan_rows=kahan_rows)
         self.load(self.W0, self.C0)
 
     def load(self, W, C):
@@ -220,6 +220,39 @@ def test_large_batch_kernels_on_ragged_tiles(b, fmt, flags, d, tol):
     indptr, indices = synth.ZipfLabels(L, 1.0).draw_csr(rng, B, "lognormal5")
     say(f"[large-batch ragged] fmt={fmt} flags={flags} L={L} d={d} B={B} chunk={chunk} nnz={len(indices)}")
     check_step(case, X, indptr, indices, 0.1, 17, 3, tol)
+
+
+@pytest.mark.parametrize("B", [70, 300])
+def test_kahan_for_head_labels_only(b, B):
+    """Compensation on the first 256 labels only, boundary inside the second chunk (384 labels per
+    chunk), for the single-pass small-batch kernel (B = 70) and the separate kernels (B = 300):
+    head rows against the oracle's Kahan update with their compensation, the other rows against
+    its plain update."""
+    L, d, chunk, k = 5 * 128 + 77, 256, 384, 256
+    fmt, flags = o.E4M3, o.FLAG_SR | o.FLAG_KAHAN
+    case = Case(b, L, d, fmt, chunk, flags, B, w_std=0.05, comp_std=2e-4, seed=9, kahan_rows=k)
+    assert case.head.compensation().shape == (k, d)
+    rng = np.random.default_rng(21)
+    X = synth.make_x(rng, B, d)
+    indptr, indices = synth.ZipfLabels(L, 1.0).draw_csr(rng, B, "lognormal5")
+    say(f"[head-only kahan] B={B} L={L} kahan_rows={k} chunk={chunk}")
+    C_pad = np.zeros((L, d), np.uint16)
+    C_pad[:k] = case.C0
+    dX, loss = case.step(X, indptr, indices, 0.1, 3, 5)
+    ref = o.head_step(case.W0, C_pad, X, indptr, indices, 0.1, 3, 5, fmt, flags, kahan_rows=k)
+    Wn = case.W()
+    dist = np.abs(ordered(Wn, fmt) - ordered(ref["W_new"], fmt))
+    say(f"   W': within 1 ulp head {np.mean(dist[:k] <= 1):.6f}, rest {np.mean(dist[k:] <= 1):.6f};  dX rel-Fro {rel_fro(dX, ref['dX_partial']):.2e}")
+    assert np.mean(dist[:k] <= 1) >= 0.999 and np.mean(dist[k:] <= 1) >= 0.999
+    assert_far_misses_are_tiny(Wn, ref["W_new"], dist, fmt, 0.1)
+    assert rel_fro(dX, ref["dX_partial"]) <= 6e-2
+    same = dist[:k] == 0
+    cg, cr = o.decode_bf16(case.C()), o.decode_bf16(ref["comp_new"][:k])
+    scale = np.maximum(np.abs(o.decode(ref["W_new"][:k], fmt)), 2.0**-9)
+    assert np.quantile((np.abs(cg - cr) / scale)[same], 0.999) <= 2.0**-8
+    # the mode is not the all-Kahan one: rows past the boundary equal the oracle's plain update
+    plain = o.head_step(case.W0[k:], None, X, indptr, indices, 0.1, 3, 5, fmt, o.FLAG_SR, label_ids=np.arange(k, L))
+    assert np.mean(np.abs(ordered(Wn[k:], fmt) - ordered(plain["W_new"], fmt)) <= 1) >= 0.999
 
 
 def test_same_operand_error_is_at_bf16_roundoff(b):
