@@ -103,6 +103,15 @@ int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const int32_t* indp
 int elmo_head_topk(elmo_head_t* h, const void* X, int32_t B, int32_t k, int32_t* idx_out,
                    float* score_out, void* hip_stream);
 
+/* Precision at k (evaluation section, P@k(y, y^) = (1/k) sum over l in top_k(y^) of y_l), as exact
+ * integer numerators: hits_out[j-1] = number of (row, label) pairs with the label among the row's
+ * first j entries of idx and among the row's positives, summed over the B rows, j = 1..k; then
+ * P@j = hits_out[j-1] / (j * B).  idx [B, k] int32 as written by elmo_head_topk (best first);
+ * indptr / indices: the CSR positives of the same B rows (ids ascending within a row); hits_out
+ * [k] int64.  All device pointers; 1 <= k <= 128.  Needs no head. */
+int elmo_precision_hits(const int32_t* idx, int32_t B, int32_t k, const int32_t* indptr,
+                        const int32_t* indices, int64_t* hits_out, void* hip_stream);
+
 int elmo_head_destroy(elmo_head_t* h);
 
 /* Measurement hooks.  elmo_head_profile(h, 1) makes every later step / top-k call record a HIP

@@ -400,6 +400,21 @@ def topk(Z, k):
     return idx, np.take_along_axis(Z, idx, axis=1)
 
 
+def precision_hits(idx, indptr, indices):
+    """Numerators of P@k (evaluation section, "Precision at k"): hits[j-1] = number of (row, label)
+    pairs with the label among the row's first j predictions and among its true labels, summed
+    over the rows, for j = 1..k.  P@j = hits[j-1] / (j * rows).  idx [rows, k], best first."""
+    idx = np.asarray(idx)
+    rows, k = idx.shape
+    hits = np.zeros(k, dtype=np.int64)
+    for i in range(rows):
+        truth = set(int(l) for l in indices[indptr[i]:indptr[i + 1]])
+        for j in range(k):
+            if int(idx[i, j]) in truth:
+                hits[j:] += 1
+    return hits
+
+
 def kahan_sum_stream(s_bits, c_bits, addends, fmt):
     """Apply the Kahan recurrence of Section 3 repeatedly to one stored value: s in `fmt`,
     c in BF16, each v of `addends` added with FP32 arithmetic and round-to-nearest storage.

@@ -501,3 +501,19 @@ extern "C" int elmo_head_topk(elmo_head_t* h, const void* X, int32_t B, int32_t 
   h->prof.mark(st, CLS_END);
   return rc;
 }
+
+extern "C" int elmo_precision_hits(const int32_t* idx, int32_t B, int32_t k, const int32_t* indptr, const int32_t* indices,
+                                   int64_t* hits_out, void* hip_stream) {
+  if (!idx || !indptr || !hits_out) return fail(-1, "idx, indptr and hits_out must not be NULL");
+  if (B < 1) return fail(-1, "B must be >= 1 (got %d)", B);
+  if (k < 1 || k > elmo::kTopkMaxK) return fail(-1, "k = %d outside [1, %d]", k, elmo::kTopkMaxK);
+  hipStream_t st = (hipStream_t)hip_stream;
+  unsigned long long* hits = reinterpret_cast<unsigned long long*>(hits_out);
+  elmo::k_fill_u32<<<1, elmo::kThreads, 0, st>>>((uint32_t*)hits, (size_t)k * 2, 0u);
+  if (int rc = check_launch("k_fill_u32")) return rc;
+  const int64_t n = (int64_t)B * k;
+  elmo::k_hits_at<<<(int)((n + elmo::kThreads - 1) / elmo::kThreads), elmo::kThreads, 0, st>>>(idx, B, k, indptr, indices, hits);
+  if (int rc = check_launch("k_hits_at")) return rc;
+  elmo::k_hits_scan<<<1, elmo::kThreads, 0, st>>>(hits, k);
+  return check_launch("k_hits_scan");
+}

@@ -319,6 +319,31 @@ __global__ void __launch_bounds__(kThreads) k_topk_select(float* __restrict__ ta
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// P@k numerators: per position j the number of rows whose j-th prediction is a true label, then
+// the running sum over positions.  Integer counts: the result does not depend on the order of the
+// atomic additions.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kThreads) k_hits_at(const int* __restrict__ idx, int B, int k, const int* __restrict__ indptr,
+                                                      const int* __restrict__ indices, unsigned long long* __restrict__ hits) {
+  const int t = blockIdx.x * kThreads + threadIdx.x;
+  if (t >= B * k) return;
+  const int b = t / k, j = t - b * k;
+  const int l = idx[t];
+  int lo = indptr[b], hi = indptr[b + 1];          // binary search in the row's ascending ids
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (indices[mid] < l) lo = mid + 1; else hi = mid;
+  }
+  if (lo < indptr[b + 1] && indices[lo] == l) atomicAdd(&hits[j], 1ull);
+}
+__global__ void __launch_bounds__(kThreads) k_hits_scan(unsigned long long* __restrict__ hits, int k) {
+  if (threadIdx.x == 0) {
+    unsigned long long run = 0;
+    for (int j = 0; j < k; ++j) { run += hits[j]; hits[j] = run; }
+  }
+}
+
 inline int topk_launch_error(const char* what, char* err, size_t errsz) {
   const hipError_t e = hipGetLastError();
   if (e == hipSuccess) return 0;

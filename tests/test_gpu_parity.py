@@ -491,6 +491,33 @@ def test_topk_rising_scores_take_the_unbounded_path(b):
     assert exact > 0.9
 
 
+def test_precision_hits_bit_exact(b):
+    """P@k numerators on the device against the oracle's count, on the head's own top-k and on
+    hand-made predictions that contain every true label (ids up front)."""
+    L, d, B, k = 3000, 256, 200, 10
+    case = Case(b, L, d, o.E4M3, 1024, 0, B, w_std=0.05, seed=14)
+    rng = np.random.default_rng(15)
+    X = synth.make_x(rng, B, d)
+    indptr, indices = synth.ZipfLabels(L, 1.0).draw_csr(rng, B, "lognormal5")
+    idx = torch.zeros((B, k), dtype=torch.int32, device=DEV)
+    case.head.topk(dev(X), k, idx, None)
+    hits = torch.zeros(k, dtype=torch.int64, device=DEV)
+    b.elmo_precision_hits(idx, B, k, dev(indptr), dev(indices), hits)
+    torch.cuda.synchronize()
+    want = o.precision_hits(idx.cpu().numpy(), indptr, indices)
+    say(f"[P@k] hits {hits.cpu().numpy().tolist()}")
+    np.testing.assert_array_equal(hits.cpu().numpy(), want)
+    made = np.full((B, k), L - 1, dtype=np.int32)          # the true labels first, then a filler id
+    for i in range(B):
+        t = indices[indptr[i]:indptr[i + 1]][:k]
+        made[i, :len(t)] = t
+    b.elmo_precision_hits(dev(made), B, k, dev(indptr), dev(indices), hits)
+    torch.cuda.synchronize()
+    want = o.precision_hits(made, indptr, indices)
+    assert want[0] == B                                    # every row has a positive: P@1 = 1
+    np.testing.assert_array_equal(hits.cpu().numpy(), want)
+
+
 def test_topk_mid_size(b):
     cfg = synth.CONFIGS["mid"]
     head = b.Head(cfg.L, cfg.d, cfg.fmt, cfg.chunk, 0, 64, 64)

@@ -258,6 +258,27 @@ def test_topk_brute_force():
         assert val[i].tolist() == [Z[i, l] for l in order]
 
 
+def test_precision_hits_on_a_worked_example():
+    """P@k = (1/k) sum_{l in top_k} y_l (evaluation section).  Two rows, k = 3, counted by hand:
+    row 0 truth {2, 5}, predictions (5, 1, 2) -> hits after 1, 2, 3 predictions: 1, 1, 2;
+    row 1 truth {0},    predictions (3, 0, 4) -> 0, 1, 1."""
+    indptr, indices = np.array([0, 2, 3]), np.array([2, 5, 0])
+    idx = np.array([[5, 1, 2], [3, 0, 4]])
+    hits = o.precision_hits(idx, indptr, indices)
+    np.testing.assert_array_equal(hits, [1, 2, 3])
+    p_at = hits / (np.arange(1, 4) * 2)
+    np.testing.assert_allclose(p_at, [0.5, 0.5, 0.5])
+    # perfect predictions: every true label first -> P@k = min(k, n_i) / k averaged over the rows
+    idx = np.array([[2, 5, 9], [0, 7, 8]])
+    np.testing.assert_array_equal(o.precision_hits(idx, indptr, indices), [2, 3, 3])
+    # scores that rank the positives first give P@1 = 1 through the oracle's own top-k
+    Z = np.full((2, 10), -1.0)
+    Z[0, [2, 5]] = [3.0, 2.0]
+    Z[1, 0] = 1.0
+    top, _ = o.topk(Z, 3)
+    assert o.precision_hits(top, indptr, indices)[0] == 2
+
+
 def test_synthetic_label_recipe():
     zipf = synth.ZipfLabels(1000, 1.0)
     rng = np.random.default_rng(0)
