@@ -57,6 +57,10 @@ typedef struct {
                              "Precision Recovery for Sensitive Applications": number the labels by falling
                              frequency and the top-p% head is this prefix; memory 2 bytes x kahan_rows x d).
                              0 = every label.  Otherwise L or a multiple of 128.  Must be 0 without the flag. */
+  float weight_decay;     /* L2 weight decay of the classifier (the "WD ... XMC" column of the paper's
+                             hyper-parameter table; Algorithm 1 itself has none): the update uses
+                             g + weight_decay * w in place of the gradient g, two more FP32 operations, each
+                             rounded.  0 = none (the two operations are skipped).  In [0, 1]. */
   void* workspace;        /* scratch; contents need not survive between calls */
   size_t workspace_bytes;
 } elmo_head_opts;

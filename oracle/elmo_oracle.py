@@ -290,7 +290,7 @@ def bce_loss(Z, Y):
     return float(np.sum(np.maximum(Z, 0.0) + np.log1p(np.exp(-np.abs(Z))) - Y * Z))
 
 
-def update_rows(W_bits, comp_bits, dW, lr, fmt, flags, seed, step, elem):
+def update_rows(W_bits, comp_bits, dW, lr, fmt, flags, seed, step, elem, weight_decay=0.0):
     """Fused SGD update of weight elements (Algorithm 1, fuse_update; Section 3 Kahan).
 
     W_bits/comp_bits/dW/elem have the same shape; elem holds the flat element indices that pick
@@ -299,10 +299,16 @@ def update_rows(W_bits, comp_bits, dW, lr, fmt, flags, seed, step, elem):
       plain : t = fl(w - u);                      w' = Q(t)
       Kahan : y = fl(-u - c); t = fl(w + y);      w' = Q(t);  c' = RNE_BF16(fl(fl(w' - w) - y))
     Q is SR (flag SR) or round-to-nearest-even.  Returns (W_bits', comp_bits' or None).
+
+    weight_decay (the classifier's "WD" of the hyper-parameter table; Algorithm 1 leaves it out,
+    reading: the L2 term of plain SGD added to the gradient): g = fl(g + fl(wd w)) before the
+    steps above; 0 skips the two operations.
     """
     f32 = np.float32
     w = decode(W_bits, fmt).astype(f32)  # exact
     g = np.asarray(dW, dtype=np.float64).astype(f32)
+    if weight_decay != 0.0:
+        g = (g + (f32(weight_decay) * w).astype(f32)).astype(f32)
     u = (f32(lr) * g).astype(f32)
     r = sr_fields(seed, step, elem) if (flags & FLAG_SR) else None
     if flags & FLAG_KAHAN:
@@ -319,7 +325,7 @@ def update_rows(W_bits, comp_bits, dW, lr, fmt, flags, seed, step, elem):
 
 
 def head_step(W_bits, comp_bits, X_bits, indptr, indices, lr, seed, step, fmt, flags,
-              label_ids=None, g_exact=False, kahan_rows=None):
+              label_ids=None, g_exact=False, kahan_rows=None, weight_decay=0.0):
     """One training step of the head on the given weight rows.
 
     kahan_rows (with FLAG_KAHAN; None = every label): only the labels with id < kahan_rows carry a
@@ -355,11 +361,11 @@ def head_step(W_bits, comp_bits, X_bits, indptr, indices, lr, seed, step, fmt, f
         comp_bits = np.asarray(comp_bits)
         Wn, cn = np.array(W_bits, copy=True), np.array(comp_bits, copy=True)
         if head.any():
-            Wn[head], cn[head] = update_rows(W_bits[head], comp_bits[head], dW[head], lr, fmt, flags, seed, step, elem[head])
+            Wn[head], cn[head] = update_rows(W_bits[head], comp_bits[head], dW[head], lr, fmt, flags, seed, step, elem[head], weight_decay)
         if (~head).any():
-            Wn[~head], _ = update_rows(W_bits[~head], None, dW[~head], lr, fmt, flags & ~FLAG_KAHAN, seed, step, elem[~head])
+            Wn[~head], _ = update_rows(W_bits[~head], None, dW[~head], lr, fmt, flags & ~FLAG_KAHAN, seed, step, elem[~head], weight_decay)
     else:
-        Wn, cn = update_rows(W_bits, comp_bits, dW, lr, fmt, flags, seed, step, elem)
+        Wn, cn = update_rows(W_bits, comp_bits, dW, lr, fmt, flags, seed, step, elem, weight_decay)
     return dict(Z=Z, G=G, dX_partial=dX, dW=dW, W_new=Wn, comp_new=cn, loss=bce_loss(Z, Y))
 
 

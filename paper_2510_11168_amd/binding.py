@@ -38,7 +38,7 @@ class elmo_head_opts(C.Structure):
     _fields_ = [
         ("flags", C.c_uint32), ("max_B", C.c_int32), ("max_nnz", C.c_int64),
         ("W", C.c_void_p), ("W_bytes", C.c_size_t),
-        ("comp", C.c_void_p), ("comp_bytes", C.c_size_t), ("kahan_rows", C.c_int64),
+        ("comp", C.c_void_p), ("comp_bytes", C.c_size_t), ("kahan_rows", C.c_int64), ("weight_decay", C.c_float),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
     ]
 
@@ -109,12 +109,13 @@ def elmo_head_sizes(L, d, weight_dtype, chunk, max_B, max_nnz, flags, kahan_rows
     return w.value, c.value, s.value
 
 
-def elmo_head_create(L, d, weight_dtype, chunk, *, flags, max_B, max_nnz, W, comp, workspace, kahan_rows=0) -> int:
+def elmo_head_create(L, d, weight_dtype, chunk, *, flags, max_B, max_nnz, W, comp, workspace, kahan_rows=0,
+                     weight_decay=0.0) -> int:
     """W, comp, workspace: 1-D torch.uint8 device tensors (comp may be None).  Returns the handle."""
     o = elmo_head_opts(flags=flags, max_B=max_B, max_nnz=max_nnz,
                        W=_ptr(W), W_bytes=0 if W is None else W.numel() * W.element_size(),
                        comp=_ptr(comp), comp_bytes=0 if comp is None else comp.numel() * comp.element_size(),
-                       kahan_rows=kahan_rows,
+                       kahan_rows=kahan_rows, weight_decay=weight_decay,
                        workspace=_ptr(workspace),
                        workspace_bytes=0 if workspace is None else workspace.numel() * workspace.element_size())
     h = C.c_void_p()
@@ -171,7 +172,7 @@ def elmo_philox4x32_10(ctr, key):
 class Head:
     """Allocates W / comp / workspace as torch device tensors and keeps the handle alive."""
 
-    def __init__(self, L, d, weight_dtype, chunk, flags, max_B, max_nnz, device="cuda:0", kahan_rows=0):
+    def __init__(self, L, d, weight_dtype, chunk, flags, max_B, max_nnz, device="cuda:0", kahan_rows=0, weight_decay=0.0):
         self.L, self.d, self.fmt, self.chunk, self.flags = L, d, weight_dtype, chunk, flags
         self.max_B, self.max_nnz = max_B, max_nnz
         self.kahan_rows = (kahan_rows or L) if flags & ELMO_KAHAN else 0   # label rows that carry compensation
@@ -181,7 +182,8 @@ class Head:
         self.workspace = torch.empty(sb, dtype=torch.uint8, device=device)
         self.bytes = (wb, cb, sb)
         self.h = elmo_head_create(L, d, weight_dtype, chunk, flags=flags, max_B=max_B, max_nnz=max_nnz,
-                                  W=self.W, comp=self.comp, workspace=self.workspace, kahan_rows=kahan_rows)
+                                  W=self.W, comp=self.comp, workspace=self.workspace, kahan_rows=kahan_rows,
+                                  weight_decay=weight_decay)
 
     def weights(self):
         """[L, d] view of the raw weight bits: uint8 codes (E4M3) or int16 patterns (BF16)."""

@@ -39,6 +39,7 @@ inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 struct Plan {
   int64_t L; int d; int fmt; int64_t chunk; int maxB; int64_t max_nnz; uint32_t flags;
   int64_t kahan_rows;                   // leading label rows that carry compensation (0 without ELMO_KAHAN)
+  float weight_decay;                   // L2 term of the update, 0 = none
   int Bp_max, tiles_b_max, ntiles;      // padded batch, batch tiles, 128-label tiles of the whole head
   int dx_rows;                          // rows of FP32 input-gradient partials (slices x padded batch)
   size_t off_xq, off_xt, off_g, off_dx, off_loss, off_cnt, off_ptr, off_cur, off_pos, off_flag, off_topk, total;
@@ -61,6 +62,7 @@ int make_plan(int64_t L, int d, int fmt, int64_t chunk, int maxB, int64_t max_nn
     return fail(-1, "kahan_rows must be 0 (all labels), L, or a multiple of 128 (got %lld)", (long long)kahan_rows);
   p.L = L; p.d = d; p.fmt = fmt; p.chunk = chunk; p.maxB = maxB; p.max_nnz = max_nnz; p.flags = flags;
   p.kahan_rows = (flags & ELMO_KAHAN) ? (kahan_rows ? kahan_rows : L) : 0;
+  p.weight_decay = 0.0f;
   p.Bp_max = round_up(maxB, 64);
   p.tiles_b_max = (p.Bp_max + 255) / 256;      // 256-sample tiles of the matrix products
   p.ntiles = (int)((L + 127) / 128);
@@ -149,6 +151,8 @@ int elmo_head_create(int64_t L, int32_t d, int weight_dtype, int64_t chunk, cons
   Plan p;
   const int rc = make_plan(L, d, weight_dtype, chunk, opts->max_B, opts->max_nnz, opts->flags, opts->kahan_rows, p);
   if (rc) return rc;
+  if (!(opts->weight_decay >= 0.0f) || opts->weight_decay > 1.0f) return fail(-1, "weight_decay must be in [0, 1] (got %g)", (double)opts->weight_decay);
+  p.weight_decay = opts->weight_decay;
   if (!opts->W || opts->W_bytes < p.W_bytes) return fail(-1, "W buffer missing or smaller than %zu bytes", p.W_bytes);
   if ((opts->flags & ELMO_KAHAN) && (!opts->comp || opts->comp_bytes < p.comp_bytes))
     return fail(-1, "ELMO_KAHAN needs a compensation buffer of %zu bytes", p.comp_bytes);
@@ -249,9 +253,9 @@ void launch_logits(hipStream_t st, int tb, int grid, const char* Xa, int a_rows,
 
 template <int FMT>
 void launch_update(hipStream_t st, int grid, bool sr, bool kahan, const char* Gt, const char* XT, char* Wc, uint16_t* Cc,
-                   int n, int d, int Bp, float lr, uint64_t seed, uint64_t step, uint64_t elem0) {
+                   int n, int d, int Bp, float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0) {
 #define ELMO_UPD(SR_, KA_) \
-  elmo::k_update<FMT, SR_, KA_><<<grid, elmo::kGemmThreads, elmo::kUpdateSmem, st>>>(Gt, XT, Wc, Cc, n, d, Bp, lr, seed, step, elem0)
+  elmo::k_update<FMT, SR_, KA_><<<grid, elmo::kGemmThreads, elmo::kUpdateSmem, st>>>(Gt, XT, Wc, Cc, n, d, Bp, lr, wd, seed, step, elem0)
   if (sr && kahan) ELMO_UPD(true, true);
   else if (sr) ELMO_UPD(true, false);
   else if (kahan) ELMO_UPD(false, true);
@@ -263,7 +267,7 @@ void launch_update(hipStream_t st, int grid, bool sr, bool kahan, const char* Gt
 // template so that the attribute call and the launch agree.
 template <int FMT, bool SR, bool KAHAN, bool DX>
 int launch_dx_update_one(hipStream_t st, int grid, const char* Gt, const char* XT, char* Wc, uint16_t* Cc, float* dXacc, int n,
-                         int d, int Bp, float lr, uint64_t seed, uint64_t step, uint64_t elem0, int tpg) {
+                         int d, int Bp, float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0, int tpg) {
   static bool attr_done = false;
   constexpr int smem = elmo::dxu_smem_bytes<FMT, KAHAN>();
   if (!attr_done) {
@@ -271,15 +275,15 @@ int launch_dx_update_one(hipStream_t st, int grid, const char* Gt, const char* X
                                  hipFuncAttributeMaxDynamicSharedMemorySize, smem));
     attr_done = true;
   }
-  elmo::k_dx_update<FMT, SR, KAHAN, DX><<<grid, elmo::kGemmThreads, smem, st>>>(Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, seed, step,
-                                                                               elem0, tpg);
+  elmo::k_dx_update<FMT, SR, KAHAN, DX><<<grid, elmo::kGemmThreads, smem, st>>>(Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, wd, seed,
+                                                                               step, elem0, tpg);
   return 0;
 }
 template <int FMT>
 int launch_dx_update(hipStream_t st, int grid, bool sr, bool kahan, bool dx, const char* Gt, const char* XT, char* Wc, uint16_t* Cc,
-                     float* dXacc, int n, int d, int Bp, float lr, uint64_t seed, uint64_t step, uint64_t elem0, int tpg) {
+                     float* dXacc, int n, int d, int Bp, float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0, int tpg) {
 #define ELMO_DXU(SR_, KA_, DX_) \
-  return launch_dx_update_one<FMT, SR_, KA_, DX_>(st, grid, Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, seed, step, elem0, tpg)
+  return launch_dx_update_one<FMT, SR_, KA_, DX_>(st, grid, Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, wd, seed, step, elem0, tpg)
   if (sr && kahan && dx) ELMO_DXU(true, true, true);
   if (sr && kahan) ELMO_DXU(true, true, false);
   if (sr && dx) ELMO_DXU(true, false, true);
@@ -432,8 +436,8 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
         char* Wp = Wc + (size_t)l_off * d * esz;
         uint16_t* Cp = kahan ? Cc + (size_t)l_off * d : nullptr;
         int rc;
-        if (fp8) rc = launch_dx_update<elmo::FMT_E4M3>(st, groups_used * col_blocks, sr, kahan, dX_out != nullptr, Gp, (const char*)XT, Wp, Cp, dXacc, n_part, d, Bp, lr, seed, step, elem0, tpg);
-        else rc = launch_dx_update<elmo::FMT_BF16>(st, groups_used * col_blocks, sr, kahan, dX_out != nullptr, Gp, (const char*)XT, Wp, Cp, dXacc, n_part, d, Bp, lr, seed, step, elem0, tpg);
+        if (fp8) rc = launch_dx_update<elmo::FMT_E4M3>(st, groups_used * col_blocks, sr, kahan, dX_out != nullptr, Gp, (const char*)XT, Wp, Cp, dXacc, n_part, d, Bp, lr, p.weight_decay, seed, step, elem0, tpg);
+        else rc = launch_dx_update<elmo::FMT_BF16>(st, groups_used * col_blocks, sr, kahan, dX_out != nullptr, Gp, (const char*)XT, Wp, Cp, dXacc, n_part, d, Bp, lr, p.weight_decay, seed, step, elem0, tpg);
         if (rc) return rc;
         if (int rc2 = check_launch("k_dx_update")) return rc2;
       }
@@ -456,8 +460,8 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
       const char* Gp = (const char*)(Gt + (size_t)l_off * Bp);
       char* Wp = Wc + (size_t)l_off * d * esz;
       uint16_t* Cp = kahan ? Cc + (size_t)l_off * d : nullptr;
-      if (fp8) launch_update<elmo::FMT_E4M3>(st, grid, sr, kahan, Gp, (const char*)XT, Wp, Cp, n_part, d, Bp, lr, seed, step, elem0);
-      else launch_update<elmo::FMT_BF16>(st, grid, sr, kahan, Gp, (const char*)XT, Wp, Cp, n_part, d, Bp, lr, seed, step, elem0);
+      if (fp8) launch_update<elmo::FMT_E4M3>(st, grid, sr, kahan, Gp, (const char*)XT, Wp, Cp, n_part, d, Bp, lr, p.weight_decay, seed, step, elem0);
+      else launch_update<elmo::FMT_BF16>(st, grid, sr, kahan, Gp, (const char*)XT, Wp, Cp, n_part, d, Bp, lr, p.weight_decay, seed, step, elem0);
       if (int rc = check_launch("k_update")) return rc;
     }
   }

@@ -405,7 +405,7 @@ constexpr int kUpdateSmem = kUpdateEpiBytes > kWideRingBytes ? kUpdateEpiBytes :
 // Sixteen consecutive elements of one weight row: storage bits in, storage bits out.
 // E4M3: w[0..3] hold 4 codes each; BF16: w[0..7] hold 2 patterns each.  c[0..7]: BF16 compensation.
 template <int FMT, bool SR, bool KAHAN>
-__device__ inline void update16(uint32_t (&w)[8], uint32_t (&c)[8], const float (&g)[16], float lr, const U4 (&rb)[2]) {
+__device__ inline void update16(uint32_t (&w)[8], uint32_t (&c)[8], const float (&g)[16], float lr, float wd, const U4 (&rb)[2]) {
   const uint32_t rw[8] = {rb[0].x, rb[0].y, rb[0].z, rb[0].w, rb[1].x, rb[1].y, rb[1].z, rb[1].w};
   if (FMT == FMT_E4M3) {
 #pragma unroll
@@ -416,7 +416,8 @@ __device__ inline void update16(uint32_t (&w)[8], uint32_t (&c)[8], const float 
       for (int e = 0; e < 4; ++e) {
         const int i = 4 * q + e;
         const float wv = e4m3_decode_byte(w[q], e);
-        const float u = __fmul_rn(lr, g[i]);
+        const float gi = wd != 0.0f ? __fadd_rn(g[i], __fmul_rn(wd, wv)) : g[i];   // L2 weight decay as a gradient term
+        const float u = __fmul_rn(lr, gi);
         float t, y = 0.0f;
         if (KAHAN) {
           const float cv = u2f((i & 1) ? (c[i >> 1] & 0xFFFF0000u) : (c[i >> 1] << 16));
@@ -445,7 +446,7 @@ __device__ inline void update16(uint32_t (&w)[8], uint32_t (&c)[8], const float 
       uint32_t wb = (w[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
       uint32_t cb = KAHAN ? (c[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu : 0u;
       const uint32_t r16 = SR ? ((rw[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu) : 0u;
-      update_element<FMT, SR, KAHAN>(wb, cb, g[i], lr, r16);
+      update_element<FMT, SR, KAHAN>(wb, cb, g[i], lr, wd, r16);
       w[i >> 1] = (i & 1) ? (w[i >> 1] & 0x0000FFFFu) | (wb << 16) : (w[i >> 1] & 0xFFFF0000u) | wb;
       if (KAHAN) c[i >> 1] = (i & 1) ? (c[i >> 1] & 0x0000FFFFu) | (cb << 16) : (c[i >> 1] & 0xFFFF0000u) | cb;
     }
@@ -455,7 +456,7 @@ __device__ inline void update16(uint32_t (&w)[8], uint32_t (&c)[8], const float 
 template <int FMT, bool SR, bool KAHAN>
 __global__ void __launch_bounds__(kGemmThreads, 1)
 k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restrict__ Wc, uint16_t* __restrict__ Cc,
-         int n, int d, int Bp, float lr, uint64_t seed, uint64_t step, uint64_t elem0) {
+         int n, int d, int Bp, float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int ESZ = FMT == FMT_E4M3 ? 1 : 2;
   constexpr int WQ = FMT == FMT_E4M3 ? 1 : 2;       // 16-byte loads per 16 weights
@@ -553,7 +554,7 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
         rb[0] = sr_block(blk, seed, step);
         rb[1] = sr_block(blk + 1, seed, step);
       }
-      update16<FMT, SR, KAHAN>(w, c, g, lr, rb);
+      update16<FMT, SR, KAHAN>(w, c, g, lr, wd, rb);
       char* wp = Wc + eoff * ESZ;
       *reinterpret_cast<u32x4*>(wp) = u32x4{w[0], w[1], w[2], w[3]};
       if (WQ == 2) *reinterpret_cast<u32x4*>(wp + 16) = u32x4{w[4], w[5], w[6], w[7]};
@@ -591,7 +592,7 @@ template <int FMT, bool KAHAN> constexpr int dxu_smem_bytes() { return kStages *
 template <int FMT, bool SR, bool KAHAN, bool DX>
 __device__ __forceinline__ void dx_update_body(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restrict__ Wc,
                                                uint16_t* __restrict__ Cc, float* __restrict__ dXacc, int n, int d, int Bp,
-                                               float lr, uint64_t seed, uint64_t step, uint64_t elem0, int tiles_per_group,
+                                               float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0, int tiles_per_group,
                                                char* smem) {
   constexpr int ESZ = FMT == FMT_E4M3 ? 1 : 2;
   constexpr int WROWB = 256 * ESZ;
@@ -706,7 +707,7 @@ __device__ __forceinline__ void dx_update_body(const char* __restrict__ Gt, cons
         rb[0] = sr_block(blk, seed, step);
         rb[1] = sr_block(blk + 1, seed, step);
       }
-      update16<FMT, SR, KAHAN>(w, cc, gr, lr, rb);
+      update16<FMT, SR, KAHAN>(w, cc, gr, lr, wd, rb);
       char* wp = Wc + eoff * ESZ;
       *reinterpret_cast<u32x4*>(wp) = u32x4{w[0], w[1], w[2], w[3]};
       if (ESZ == 2) *reinterpret_cast<u32x4*>(wp + 16) = u32x4{w[4], w[5], w[6], w[7]};
@@ -727,10 +728,10 @@ __device__ __forceinline__ void dx_update_body(const char* __restrict__ Gt, cons
 template <int FMT, bool SR, bool KAHAN, bool DX>
 __global__ void __launch_bounds__(kGemmThreads, 1)
 k_dx_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restrict__ Wc, uint16_t* __restrict__ Cc,
-            float* __restrict__ dXacc, int n, int d, int Bp, float lr, uint64_t seed, uint64_t step, uint64_t elem0,
+            float* __restrict__ dXacc, int n, int d, int Bp, float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0,
             int tiles_per_group) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  dx_update_body<FMT, SR, KAHAN, DX>(Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, seed, step, elem0, tiles_per_group, smem);
+  dx_update_body<FMT, SR, KAHAN, DX>(Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, wd, seed, step, elem0, tiles_per_group, smem);
 }
 
 // ---------------------------------------------------------------------------------------------

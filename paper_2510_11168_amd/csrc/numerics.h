@@ -153,9 +153,12 @@ template <int FMT> __device__ inline float decode(uint32_t bits) {
 //   plain : t = w - lr*g                    w' = Q(t)
 //   Kahan : y = -(lr*g) - c;  t = w + y     w' = Q(t);  c' = RNE_BF16((w' - w) - y)
 // ---------------------------------------------------------------------------------------------
+// Weight decay (wd != 0; the classifier's WD of the paper's hyper-parameter table, read as the L2
+// term of plain SGD): g <- g + wd*w, two more rounded operations, before the lines above.
 template <int FMT, bool SR, bool KAHAN>
-__device__ inline void update_element(uint32_t& wbits, uint32_t& cbits, float g, float lr, uint32_t r16) {
+__device__ inline void update_element(uint32_t& wbits, uint32_t& cbits, float g, float lr, float wd, uint32_t r16) {
   const float w = decode<FMT>(wbits);
+  if (wd != 0.0f) g = __fadd_rn(g, __fmul_rn(wd, w));
   const float u = __fmul_rn(lr, g);
   float t, y = 0.0f;
   if (KAHAN) {

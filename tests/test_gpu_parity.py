@@ -112,14 +112,15 @@ def test_quantize_empty_is_a_no_op(b):
 class Case:
     """A head on the device initialised from host bits, plus the host copies the oracle needs."""
 
-    def __init__(self, b, L, d, fmt, chunk, flags, B, max_nnz=None, seed=0, w_std=0.02, comp_std=0.0, kahan_rows=0):
+    def __init__(self, b, L, d, fmt, chunk, flags, B, max_nnz=None, seed=0, w_std=0.02, comp_std=0.0, kahan_rows=0,
+                 weight_decay=0.0):
         rng = np.random.default_rng([seed, L, d])
         self.b, self.L, self.d, self.fmt, self.flags = b, L, d, fmt, flags
         self.W0 = o.quantize(synth.make_w0_f32(rng, L, d, w_std), fmt)
         self.C0 = None
         if flags & o.FLAG_KAHAN:
             self.C0 = o.round_bf16((rng.standard_normal((kahan_rows or L, d)) * comp_std).astype(np.float32))
-        self.head = b.Head(L, d, fmt, chunk, flags, B, max_nnz or 64 * B, kahan_rows=kahan_rows)
+        self.head = b.Head(L, d, fmt, chunk, flags, B, max_nnz or 64 * B, kahan_rows=kahan_rows, weight_decay=weight_decay)
         self.load(self.W0, self.C0)
 
     def load(self, W, C):
@@ -253,6 +254,34 @@ def test_kahan_for_head_labels_only(b, B):
     # the mode is not the all-Kahan one: rows past the boundary equal the oracle's plain update
     plain = o.head_step(case.W0[k:], None, X, indptr, indices, 0.1, 3, 5, fmt, o.FLAG_SR, label_ids=np.arange(k, L))
     assert np.mean(np.abs(ordered(Wn[k:], fmt) - ordered(plain["W_new"], fmt)) <= 1) >= 0.999
+
+
+@pytest.mark.parametrize("fmt,flags,B", [
+    (o.E4M3, o.FLAG_SR | o.FLAG_KAHAN, 70),
+    (o.E4M3, o.FLAG_SR, 300),
+    (o.BF16, o.FLAG_KAHAN, 300),
+    (o.BF16, o.FLAG_SR, 70),
+])
+def test_weight_decay(b, fmt, flags, B):
+    """The L2 term g + wd*w in both update kernels (single-pass small-batch and 256 x 256 tiles),
+    with a decay large enough to move many weights by itself."""
+    L, d, chunk, wd, lr = 3 * 128 + 50, 256, 256, 0.1, 0.1
+    case = Case(b, L, d, fmt, chunk, flags, B, w_std=0.2, comp_std=2e-4, seed=16, weight_decay=wd)
+    rng = np.random.default_rng(31)
+    X = synth.make_x(rng, B, d)
+    indptr, indices = synth.ZipfLabels(L, 1.0).draw_csr(rng, B, "lognormal5")
+    say(f"[weight decay] fmt={fmt} flags={flags} B={B} wd={wd}")
+    dX, loss = case.step(X, indptr, indices, lr, 8, 2)
+    ref = o.head_step(case.W0, case.C0, X, indptr, indices, lr, 8, 2, fmt, flags, weight_decay=wd)
+    nowd = o.head_step(case.W0, case.C0, X, indptr, indices, lr, 8, 2, fmt, flags)
+    Wn = case.W()
+    dist = np.abs(ordered(Wn, fmt) - ordered(ref["W_new"], fmt))
+    moved = float(np.mean(ref["W_new"] != nowd["W_new"]))
+    say(f"   W': exact {np.mean(dist == 0):.5f}, within 1 ulp {np.mean(dist <= 1):.6f}; the decay changes {moved:.3f} of the codes")
+    assert moved > 0.01
+    assert np.mean(dist <= 1) >= 0.999
+    assert_far_misses_are_tiny(Wn, ref["W_new"], dist, fmt, lr)
+    assert rel_fro(dX, ref["dX_partial"]) <= 6e-2
 
 
 def test_same_operand_error_is_at_bf16_roundoff(b):

@@ -164,6 +164,36 @@ def test_update_rule_by_scalar_recomputation(fmt, flags):
             assert abs((wn - float(_bf16_to_float(out["comp_new"][l, j]))) - float(t)) <= 2.0**-8 * abs(float(cn)) + 1e-12
 
 
+@pytest.mark.parametrize("fmt", [o.BF16, o.E4M3])
+def test_weight_decay_is_the_l2_term_of_sgd(fmt):
+    """weight_decay adds wd*w to the gradient (plain SGD with an L2 term).  Pins: (i) torch's own
+    SGD step with weight_decay on FP32 copies of the same numbers, rounded to the storage format,
+    gives the same codes (up to the rare element where a fused multiply-add inside torch moves the
+    FP32 result across a rounding boundary); (ii) a closed form with exactly representable
+    numbers; (iii) wd = 0 is the step without it, bit for bit."""
+    rng = np.random.default_rng(12)
+    n, d, lr, wd = 64, 32, 0.05, 0.01
+    W_bits = o.quantize((rng.standard_normal((n, d)) * 0.3).astype(np.float32), fmt)
+    dW = (rng.standard_normal((n, d)) * 0.5).astype(np.float32)
+    elem = np.arange(n * d, dtype=np.int64).reshape(n, d)
+    got, _ = o.update_rows(W_bits, None, dW, lr, fmt, 0, 0, 0, elem, weight_decay=wd)
+    p = torch.nn.Parameter(torch.from_numpy(o.decode(W_bits, fmt).astype(np.float32)))
+    p.grad = torch.from_numpy(dW.copy())
+    torch.optim.SGD([p], lr=lr, weight_decay=wd).step()
+    want = o.quantize(p.detach().numpy(), fmt)
+    assert np.mean(got == want) >= 0.995
+    assert np.max(np.abs(o.decode(got, fmt) - o.decode(want, fmt))) <= np.max(np.abs(o.decode(want, fmt))) * 2.0**-2
+    base, _ = o.update_rows(W_bits, None, dW, lr, fmt, 0, 0, 0, elem)
+    assert np.any(got != base)
+    # (ii) w = 1, g = 0, lr = 1/2, wd = 1/4: t = 1 - (1/2)(0 + 1/4) = 7/8, representable in both formats
+    one = o.quantize(np.ones((1, 8), np.float32), fmt)
+    out, _ = o.update_rows(one, None, np.zeros((1, 8)), 0.5, fmt, 0, 0, 0, np.arange(8).reshape(1, 8), weight_decay=0.25)
+    np.testing.assert_array_equal(o.decode(out, fmt), np.full((1, 8), 0.875))
+    # (iii)
+    zero, _ = o.update_rows(W_bits, None, dW, lr, fmt, 0, 0, 0, elem, weight_decay=0.0)
+    np.testing.assert_array_equal(zero, base)
+
+
 def test_rne_cancels_small_updates_bit_identically():
     """Section 4.1: with round-to-nearest and a tiny learning rate the weights do not move."""
     X_bits, W_bits, indptr, indices = _tiny(w_std=0.3)
