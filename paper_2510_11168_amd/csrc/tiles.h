@@ -1,7 +1,6 @@
 // LDS tile staging and MFMA fragment access shared by the head's three matrix products
 // (Algorithm 1: logits, input gradient, weight gradient).  gfx950 only, 64-wide wavefronts,
-// matrix-product workgroups of 512 threads arranged as 4 x 2 waves, each wave owning 64 x 128 outputs
-// (64 x 64 in the top-k filter).
+// matrix-product workgroups of 512 threads arranged as 4 x 2 waves, each wave owning 64 x 128 outputs.
 //
 // LDS tile layout: ROWS rows of ROWB bytes (ROWB = 64, 128, 256 or 512), cut into 16-byte chunks whose
 // index is XORed with a key derived from the row.  gfx950's LDS has 64 banks of 4 bytes (256 bytes

@@ -284,6 +284,19 @@ def test_weight_decay(b, fmt, flags, B):
     assert rel_fro(dX, ref["dX_partial"]) <= 6e-2
 
 
+def test_many_batch_tiles(b):
+    """A batch of 1100 rows: five 256-row batch tiles (the last one mostly padding), so the
+    input-gradient partials are spread over several label slices per tile and the finalise
+    kernel sums them."""
+    L, d, B, chunk = 600, 128, 1100, 384
+    case = Case(b, L, d, o.E4M3, chunk, o.FLAG_SR | o.FLAG_KAHAN, B, w_std=0.05, seed=18)
+    rng = np.random.default_rng(19)
+    X = synth.make_x(rng, B, d)
+    indptr, indices = synth.ZipfLabels(L, 1.0).draw_csr(rng, B, "fixed5")
+    say(f"[many batch tiles] L={L} d={d} B={B}")
+    check_step(case, X, indptr, indices, 0.02, 4, 1, 6e-2)
+
+
 def test_same_operand_error_is_at_bf16_roundoff(b):
     """Sharper than the contract: G is held in BF16 (unit roundoff 2^-9), so dX should agree with
     the FP64 oracle to a few 1e-3 when both start from the same bits."""
