@@ -19,7 +19,9 @@ What is computed follows the paper (ELMO, arxiv 2510.11168):
                                                              -- Algorithm 1 and Section 4.3
 * momentum-free SGD for the head                             -- Section 4.2
 * Kahan compensation kept in BF16 for head weights           -- Appendix "Precision Recovery"
-* top-k of the score vector                                  -- Appendix, definition of P@k
+* top-k of the score vector and the P@k numerators          -- Appendix, definition of P@k
+* compensation for the head labels only (kahan_rows)         -- Appendix "Precision Recovery"
+* weight decay of the classifier                             -- Appendix, hyper-parameter table
 
 Label chunking (Section 4.2) does not appear here: every label's logit, gradient row and weight
 update depend only on that label's own weight row, so the chunked and unchunked results are the
@@ -49,6 +51,9 @@ Readings taken where the paper is silent (each is repeated at the function that 
   that buffer.  Here Z stays FP64 and G = sigmoid(Z) - Y is rounded once, to nearest even, to
   BF16 before it enters the two products; both products then run in FP64.  `g_exact=True` skips
   that one rounding (used to pin the formulas by finite differences).
+* Weight decay (the table only gives a value): the L2 term of plain SGD, g + wd*w in FP32, each
+  operation rounded; absent (not merely zero) when wd = 0.
+* Head labels are a prefix of the label ids (labels numbered by falling frequency).
 
 Parity pins: every function below is pinned by a CPU test against something other than itself
 (published Philox vectors, torch's CPU casts, exhaustive enumeration of the random field,
