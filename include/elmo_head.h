@@ -137,6 +137,16 @@ const char* elmo_last_error(void);
 int elmo_quantize(const float* src, int64_t n, int dtype, int mode, uint64_t seed, uint64_t step,
                   uint64_t first_elem, void* dst, void* hip_stream);
 
+/* Simulated low-precision formats (the bit-width study of Section 4.3, "simulating floating-point
+ * numbers with a specific number of mantissa and exponent bits"): dst[i] = the FP32 value of src[i]
+ * rounded to a format with exp_bits exponent and man_bits mantissa bits, mode and rounding fields as
+ * in elmo_quantize.  The format follows the IEEE pattern (bias 2^(E-1)-1, top exponent code reserved,
+ * gradual underflow): (8,7) is BF16, (5,10) FP16, (5,2) E5M2; finite overflow and infinities clip to
+ * the largest finite value, NaN passes through.  2 <= exp_bits <= 8, 1 <= man_bits <= 22 (else -2).
+ * src, dst: device FP32, n entries each (may be the same buffer). */
+int elmo_quantize_em(const float* src, int64_t n, int exp_bits, int man_bits, int mode, uint64_t seed,
+                     uint64_t step, uint64_t first_elem, float* dst, void* hip_stream);
+
 /* Host-side Philox4x32-10 (Salmon et al., SC'11) as used for the rounding fields. */
 void elmo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
 

@@ -22,6 +22,7 @@ What is computed follows the paper (ELMO, arxiv 2510.11168):
 * top-k of the score vector and the P@k numerators          -- Appendix, definition of P@k
 * compensation for the head labels only (kahan_rows)         -- Appendix "Precision Recovery"
 * weight decay of the classifier                             -- Appendix, hyper-parameter table
+* simulated (exponent, mantissa) formats                     -- Section 4.3 "8-Bit Training"
 
 Label chunking (Section 4.2) does not appear here: every label's logit, gradient row and weight
 update depend only on that label's own weight row, so the chunked and unchunked results are the
@@ -231,6 +232,41 @@ def round_e4m3(t, r=None):
     code = (e_field * 8 + m_field).astype(np.int64)
     code = np.where(nan, 0x7F, code)
     return ((sign.astype(np.int64) << 7) | code).astype(np.uint8)
+
+
+def round_em(t, exp_bits, man_bits, r=None):
+    """FP32 -> the nearest (r None, ties to even) or stochastically rounded (16-bit field r)
+    value of a simulated floating-point format with `exp_bits` exponent and `man_bits` mantissa
+    bits, returned as FP32 -- the tool of the bit-width study of Section 4.3 ("simulating
+    floating-point numbers with a specific number of mantissa and exponent bits").
+
+    Reading (the paper gives no definition): the IEEE-754 pattern -- bias 2^(E-1)-1, the top
+    exponent code reserved, gradual underflow -- so that (8,7) is BF16, (5,10) FP16 and (5,2)
+    E5M2; finite overflow and infinities clip to the largest finite value, NaN stays NaN, the
+    sign of a zero result is kept.  SR as everywhere here: the position of |t| between its two
+    grid neighbours, cut to 16 fractional bits, plus r carries or not (Eq. 1 with probabilities
+    in steps of 2^-16)."""
+    E, M = int(exp_bits), int(man_bits)
+    assert 2 <= E <= 8 and 1 <= M <= 22
+    sign, mag = _split_f32(t)
+    a = mag.view(np.float32).astype(np.float64)
+    nan = mag > np.uint32(0x7F800000)
+    a = np.where(nan, 0.0, a)
+    emax, emin = 2 ** (E - 1) - 1, 2 - 2 ** (E - 1)
+    top = (2.0 - 2.0 ** -M) * 2.0 ** emax
+    a = np.minimum(a, 2.0 * top)                     # infinities clip like any overflow
+    ex = np.maximum(np.frexp(a)[1].astype(np.float64) - 1.0, float(emin))
+    gap = np.exp2(ex - M)                            # grid spacing in the binade of |t| (subnormal: 2^(emin-M))
+    pos = a / gap
+    lo = np.floor(pos)
+    frac = pos - lo
+    if r is None:
+        up = (frac > 0.5) | ((frac == 0.5) & (np.mod(lo, 2.0) == 1.0))
+    else:
+        up = (np.floor(frac * 65536.0) + np.asarray(r, dtype=np.float64)) >= 65536.0
+    val = np.minimum((lo + up) * gap, top)
+    out = np.where(sign.astype(bool), -val, val).astype(np.float32)
+    return np.where(nan, np.asarray(t, dtype=np.float32), out)
 
 
 def quantize(t, fmt, r=None):

@@ -56,6 +56,9 @@ _lib.elmo_head_create.argtypes = [C.c_int64, C.c_int32, C.c_int, C.c_int64, C.PO
 _lib.elmo_head_step.restype = C.c_int
 _lib.elmo_head_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_float,
                                 C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.elmo_quantize_em.restype = C.c_int
+_lib.elmo_quantize_em.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_uint64, C.c_uint64, C.c_uint64,
+                                  C.c_void_p, C.c_void_p]
 _lib.elmo_precision_hits.restype = C.c_int
 _lib.elmo_precision_hits.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.elmo_head_topk.restype = C.c_int
@@ -74,7 +77,7 @@ _lib.elmo_philox4x32_10.argtypes = [C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)
 
 EXPORTS = ("elmo_last_error", "elmo_logit_buffer_bytes", "elmo_head_sizes", "elmo_head_create",
            "elmo_head_step", "elmo_head_topk", "elmo_head_destroy", "elmo_quantize", "elmo_philox4x32_10",
-           "elmo_head_profile", "elmo_head_profile_read", "elmo_precision_hits")
+           "elmo_head_profile", "elmo_head_profile_read", "elmo_precision_hits", "elmo_quantize_em")
 
 
 def _check(rc: int) -> None:
@@ -130,6 +133,10 @@ def elmo_head_step(h, X, B, indptr, indices, nnz, lr, seed, step, dX_out=None, l
 
 def elmo_head_topk(h, X, B, k, idx_out=None, score_out=None, stream=None) -> None:
     _check(_lib.elmo_head_topk(h, _ptr(X), B, k, _ptr(idx_out), _ptr(score_out), _stream(stream)))
+
+
+def elmo_quantize_em(src, n, exp_bits, man_bits, mode, seed, step, first_elem, dst, stream=None) -> None:
+    _check(_lib.elmo_quantize_em(_ptr(src), n, exp_bits, man_bits, mode, seed, step, first_elem, _ptr(dst), _stream(stream)))
 
 
 def elmo_precision_hits(idx, B, k, indptr, indices, hits_out, stream=None) -> None:

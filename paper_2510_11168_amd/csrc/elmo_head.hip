@@ -521,3 +521,17 @@ extern "C" int elmo_precision_hits(const int32_t* idx, int32_t B, int32_t k, con
   elmo::k_hits_scan<<<1, elmo::kThreads, 0, st>>>(hits, k);
   return check_launch("k_hits_scan");
 }
+
+extern "C" int elmo_quantize_em(const float* src, int64_t n, int exp_bits, int man_bits, int mode, uint64_t seed, uint64_t step,
+                                uint64_t first_elem, float* dst, void* hip_stream) {
+  if (n < 0 || (n > 0 && (!src || !dst))) return fail(-1, "bad src/dst/n");
+  if (exp_bits < 2 || exp_bits > 8 || man_bits < 1 || man_bits > 22)
+    return fail(-2, "unsupported format E%dM%d (2 <= E <= 8, 1 <= M <= 22)", exp_bits, man_bits);
+  if (mode != 0 && mode != 1) return fail(-1, "mode must be 0 (nearest) or 1 (stochastic)");
+  if (n == 0) return 0;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int grid = (int)std::min<int64_t>((n + elmo::kThreads - 1) / elmo::kThreads, 256 * 16);
+  if (mode) elmo::k_quantize_em<true><<<grid, elmo::kThreads, 0, st>>>(src, n, exp_bits, man_bits, seed, step, first_elem, dst);
+  else elmo::k_quantize_em<false><<<grid, elmo::kThreads, 0, st>>>(src, n, exp_bits, man_bits, seed, step, first_elem, dst);
+  return check_launch("k_quantize_em");
+}

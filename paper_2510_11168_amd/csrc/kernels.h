@@ -755,4 +755,18 @@ __global__ void __launch_bounds__(kThreads) k_quantize(const float* __restrict__
   }
 }
 
+// Simulated (E, M) format: dst[i] = FP32 value of src[i] rounded to that format.
+template <bool SR>
+__global__ void __launch_bounds__(kThreads) k_quantize_em(const float* __restrict__ src, int64_t n, int E, int M, uint64_t seed,
+                                                          uint64_t step, uint64_t first, float* __restrict__ dst) {
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kThreads) {
+    int r16 = -1;
+    if (SR) {
+      const uint64_t e = first + (uint64_t)i;
+      r16 = (int)sr_field(sr_block(e >> 3, seed, step), (int)(e & 7));
+    }
+    dst[i] = round_em(src[i], E, M, r16);
+  }
+}
+
 }  // namespace elmo

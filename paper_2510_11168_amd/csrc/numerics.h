@@ -137,6 +137,44 @@ __device__ inline float e4m3_decode_byte(uint32_t packed, int byte) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// FP32 -> a simulated format with E exponent and M mantissa bits, result as FP32 (the bit-width
+// study of Section 4.3).  IEEE pattern: bias 2^(E-1)-1, top exponent code reserved, gradual
+// underflow; overflow and infinities clip to the largest finite value, NaN passes through.
+// 2 <= E <= 8, 1 <= M <= 22.  r16 < 0: round to nearest even; otherwise the 16-bit field of Eq. (1).
+// ---------------------------------------------------------------------------------------------
+__device__ inline float round_em(float t, int E, int M, int r16) {
+  const uint32_t bits = f2u(t), mag = bits & 0x7FFFFFFFu;
+  if (mag > 0x7F800000u) return t;
+  const int emax = (1 << (E - 1)) - 1, emin = 2 - (1 << (E - 1));
+  const uint32_t top = ((uint32_t)(emax + 127) << 23) | (((1u << M) - 1u) << (23 - M));   // (2 - 2^-M) 2^emax
+  const int drop = 23 - M;
+  uint32_t q;
+  if (E == 8 || mag >= ((uint32_t)(emin + 127) << 23)) {
+    // normal range of the format (for E = 8 also FP32's own subnormals, whose encoding is linear)
+    const uint32_t frac = mag & ((1u << drop) - 1u);
+    uint32_t up;
+    if (r16 < 0) {
+      const uint32_t half = 1u << (drop - 1);
+      up = frac > half || (frac == half && ((mag >> drop) & 1u));
+    } else {
+      const uint32_t f16 = drop >= 16 ? frac >> (drop - 16) : frac << (16 - drop);
+      up = (f16 + (uint32_t)r16) >> 16;
+    }
+    q = ((mag >> drop) + up) << drop;
+  } else {
+    // below the smallest normal: uniform grid of spacing 2^(emin - M); |t| / spacing as fixed point
+    const float pos = u2f(mag) * u2f((uint32_t)(M - emin + 127) << 23);      // exact power-of-two scaling
+    float lo = __builtin_floorf(pos);
+    const float frac = pos - lo;                                             // exact
+    if (r16 < 0) lo = __builtin_rintf(pos);
+    else lo += (__builtin_floorf(frac * 65536.0f) + (float)r16 >= 65536.0f) ? 1.0f : 0.0f;
+    q = f2u(lo * u2f((uint32_t)(emin - M + 127) << 23));
+  }
+  q = q > top ? top : q;
+  return u2f((bits & 0x80000000u) | q);
+}
+
 template <int FMT> __device__ inline uint32_t quant_rne(float t) {
   return FMT == FMT_BF16 ? bf16_rne(t) : e4m3_rne(t);
 }

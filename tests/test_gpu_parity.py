@@ -104,6 +104,28 @@ def test_quantize_bit_exact(b, fmt, mode):
     assert bad.size == 0, f"{bad.size} mismatches, first at {bad[0]}: x={x[bad[0]]!r} got={got[bad[0]]:#x} want={want[bad[0]]:#x}"
 
 
+@pytest.mark.parametrize("E,M", [(8, 7), (5, 10), (5, 2), (4, 3), (3, 4), (2, 1), (6, 9), (8, 22)])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_simulated_format_quantiser_bit_exact(b, E, M, mode):
+    """The (exponent, mantissa) format simulator against the oracle on the same 2.1 M inputs as the
+    storage-format quantisers (every FP32 exponent, ties, +-0, subnormals, overflow, inf, NaN)."""
+    x = _quant_inputs()
+    n = x.size
+    seed, step, first = 0x0F1E2D3C4B5A6978, 3, (1 << 33) + 3
+    say(f"[quantize E{E}M{M}] mode={mode} n={n}")
+    src = torch.from_numpy(x).to(DEV)
+    dst = torch.zeros(n, dtype=torch.float32, device=DEV)
+    b.elmo_quantize_em(src, n, E, M, mode, seed, step, first, dst)
+    torch.cuda.synchronize()
+    got = dst.cpu().numpy()
+    r = o.sr_fields(seed, step, first + np.arange(n, dtype=np.uint64)) if mode else None
+    want = o.round_em(x, E, M, r)
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    bad = np.nonzero((got.view(np.uint32) != want.view(np.uint32)) & ~nan)[0]
+    assert bad.size == 0, f"{bad.size} mismatches, first at {bad[0]}: x={x[bad[0]]!r} got={got[bad[0]]!r} want={want[bad[0]]!r}"
+
+
 def test_quantize_empty_is_a_no_op(b):
     b.elmo_quantize(None, 0, o.BF16, 0, 0, 0, 0, None)
 

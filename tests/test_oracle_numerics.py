@@ -288,3 +288,46 @@ def test_kahan_random_walk_error_stays_bounded():
     for x in v:
         sb = o.round_bf16((o.decode_bf16(sb).astype(np.float32) + x).astype(np.float32))
     assert abs(float(np.asarray(o.decode_bf16(sb)).item()) - true) > abs(s - c - true)
+
+
+# --------------------------------------------------------------------------------------------
+# Simulated (exponent, mantissa) formats (Section 4.3): pinned to torch's casts of the three
+# IEEE-pattern formats it has, and to this module's own BF16 / E4M3 rules where they coincide
+# --------------------------------------------------------------------------------------------
+def _em_inputs(limit):
+    rng = np.random.default_rng(77)
+    x = np.concatenate([
+        (rng.standard_normal(20000) * 10.0 ** rng.uniform(-9, 4, 20000)).astype(np.float32),
+        np.array([0.0, -0.0, 1.0, -1.0, 0.1, 1.5, 2.0 ** -14, 2.0 ** -15, 2.0 ** -24, 2.0 ** -25, 3 * 2.0 ** -25,
+                  65504.0, 57344.0, 1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 1.25, 1.375, 1.125], dtype=np.float32)])
+    return x[np.abs(x) <= limit]
+
+
+@pytest.mark.parametrize("E,M,dtype,limit", [
+    (8, 7, torch.bfloat16, 3.0e38),
+    (5, 10, torch.float16, 65504.0),
+    (5, 2, torch.float8_e5m2, 57344.0),
+])
+def test_simulated_format_equals_torch_cast(E, M, dtype, limit):
+    x = _em_inputs(limit)
+    want = torch.from_numpy(x).to(dtype).to(torch.float32).numpy()
+    got = o.round_em(x, E, M)
+    np.testing.assert_array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
+def test_simulated_format_special_values_and_sr():
+    # overflow clips (no infinities), NaN stays, sign of zero kept
+    big = np.array([1e30, -1e30, np.inf, -np.inf], np.float32)
+    np.testing.assert_array_equal(o.round_em(big, 5, 2), np.array([57344, -57344, 57344, -57344], np.float32))
+    assert np.isnan(o.round_em(np.array([np.nan], np.float32), 4, 3)[0])
+    assert np.signbit(o.round_em(np.array([-1e-30], np.float32), 5, 10)[0])
+    # (8,7) with a field is this module's BF16 stochastic rounding, (4,3) its E4M3 one below the
+    # IEEE-pattern limit 240 (E4M3 of Algorithm 1 is the non-IEEE "FN" flavour that goes on to 448)
+    x = _em_inputs(200.0)
+    r = np.random.default_rng(5).integers(0, 65536, x.shape)
+    np.testing.assert_array_equal(o.round_em(x, 8, 7, r), o.decode_bf16(o.round_bf16(x, r)).astype(np.float32))
+    np.testing.assert_array_equal(o.round_em(x, 4, 3, r), o.decode_e4m3(o.round_e4m3(x, r)).astype(np.float32))
+    np.testing.assert_array_equal(o.round_em(x, 4, 3), o.decode_e4m3(o.round_e4m3(x)).astype(np.float32))
+    # Eq. (1) by enumeration for a 3-bit mantissa: x = 1 + 3/32 lies 3/4 of the way from 1 to 1.125
+    ups = sum(float(o.round_em(np.float32(1.09375), 3, 3, np.array(rr))) == 1.125 for rr in range(0, 65536, 64))
+    assert ups == 1024 * 3 // 4
