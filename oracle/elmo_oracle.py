@@ -23,6 +23,8 @@ What is computed follows the paper (ELMO, arxiv 2510.11168):
 * compensation for the head labels only (kahan_rows)         -- Appendix "Precision Recovery"
 * weight decay of the classifier                             -- Appendix, hyper-parameter table
 * simulated (exponent, mantissa) formats                     -- Section 4.3 "8-Bit Training"
+* dropout on the classifier weights inside the products     -- Appendix "Low-Memory Dropout for
+                                                                Classifier"
 
 Label chunking (Section 4.2) does not appear here: every label's logit, gradient row and weight
 update depend only on that label's own weight row, so the chunked and unchunked results are the
@@ -55,6 +57,10 @@ Readings taken where the paper is silent (each is repeated at the function that 
 * Weight decay (the table only gives a value): the L2 term of plain SGD, g + wd*w in FP32, each
   operation rounded; absent (not merely zero) when wd = 0.
 * Head labels are a prefix of the label ids (labels numbered by falling frequency).
+* Classifier dropout: one keep bit per weight element and step (shared by the batch), from a
+  second Philox stream; dropped with probability T/256, kept weights scaled by 256/(256-T); the
+  masked weights serve logits and input gradient and mask the weight gradient (dropout_keep,
+  head_step).
 
 Parity pins: every function below is pinned by a CPU test against something other than itself
 (published Philox vectors, torch's CPU casts, exhaustive enumeration of the random field,
@@ -130,6 +136,42 @@ def sr_fields(seed: int, step: int, elem):
     words = philox4x32_10(ctr, key).astype(np.uint64)
     w = np.take_along_axis(words, (fld >> 1)[..., None], axis=-1)[..., 0]
     return ((w >> (np.uint64(16) * (fld & 1).astype(np.uint64))) & np.uint64(0xFFFF)).astype(np.uint32)
+
+
+def dropout_keep(seed: int, step: int, elem, threshold: int):
+    """Keep mask (bool) of the classifier dropout for the flat weight-element indices `elem`
+    (appendix "Low-Memory Dropout for Classifier": the weights are masked after they are loaded,
+    before the matrix product, so no masked copy of W exists; the mask must therefore be a pure
+    function of (seed, step, element)).
+
+    Reading (the paper gives neither the generator nor the granularity): one mask per weight
+    element and step, shared by all samples of the batch.  Philox4x32-10 with the seed as key and
+    counter = (block low, block high, step low, step high | 2^31) for block = e // 16 -- the top
+    counter bit keeps this stream apart from the rounding fields, which use steps below 2^63.
+    The 128 output bits are sixteen bytes (byte b = bits [8 (b % 4), +8) of word b // 4);
+    element e is kept iff byte e % 16 >= threshold, i.e. dropped with probability threshold / 256.
+    """
+    if not 0 <= threshold <= 255:
+        raise ValueError("threshold must be in [0, 255]")
+    if step >> 63:
+        raise ValueError("step must be below 2^63")
+    elem = np.asarray(elem, dtype=np.uint64)
+    blk = elem >> np.uint64(4)
+    byte = (elem & np.uint64(15)).astype(np.int64)
+    ctr = np.stack(
+        [
+            blk & _U32,
+            blk >> np.uint64(32),
+            np.full(blk.shape, step & 0xFFFFFFFF, dtype=np.uint64),
+            np.full(blk.shape, ((step >> 32) & 0xFFFFFFFF) | 0x80000000, dtype=np.uint64),
+        ],
+        axis=-1,
+    )
+    key = np.array([seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF], dtype=np.uint64)
+    words = philox4x32_10(ctr, key).astype(np.uint64)
+    w = np.take_along_axis(words, (byte >> 2)[..., None], axis=-1)[..., 0]
+    b = (w >> (np.uint64(8) * (byte & 3).astype(np.uint64))) & np.uint64(0xFF)
+    return b >= np.uint64(threshold)
 
 
 # --------------------------------------------------------------------------------------------
@@ -366,8 +408,14 @@ def update_rows(W_bits, comp_bits, dW, lr, fmt, flags, seed, step, elem, weight_
 
 
 def head_step(W_bits, comp_bits, X_bits, indptr, indices, lr, seed, step, fmt, flags,
-              label_ids=None, g_exact=False, kahan_rows=None, weight_decay=0.0):
+              label_ids=None, g_exact=False, kahan_rows=None, weight_decay=0.0, dropout=0):
     """One training step of the head on the given weight rows.
+
+    dropout (threshold T in [0, 255], 0 = none; appendix "Low-Memory Dropout for Classifier"):
+    this step's weights are W o M / (1 - T/256) with the keep mask M of dropout_keep.  Reading: the
+    same masked weights serve the logits and the input gradient, and the weight gradient is that
+    of the masked model (zero where M is zero, scaled elsewhere) -- what differentiating the loss
+    of the masked model gives; the update itself (decay, Kahan, rounding) acts on the stored W.
 
     kahan_rows (with FLAG_KAHAN; None = every label): only the labels with id < kahan_rows carry a
     compensation value -- the paper's "Kahan summation for head labels" (appendix "Precision
@@ -389,6 +437,11 @@ def head_step(W_bits, comp_bits, X_bits, indptr, indices, lr, seed, step, fmt, f
         label_ids = np.arange(n, dtype=np.int64)
     label_ids = np.asarray(label_ids, dtype=np.int64)
     Wd = decode(W_bits, fmt)
+    elem = label_ids[:, None] * np.int64(d) + np.arange(d, dtype=np.int64)[None, :]
+    if dropout:
+        keep = dropout_keep(seed, step, elem, dropout)
+        scale = 256.0 / (256.0 - dropout)
+        Wd = np.where(keep, Wd, 0.0) * scale        # the weights this step's products see
     X = decode_bf16(X_bits)
     Xq = logits_inputs(X_bits, fmt)
     Z = Xq @ Wd.T
@@ -396,7 +449,8 @@ def head_step(W_bits, comp_bits, X_bits, indptr, indices, lr, seed, step, fmt, f
     G = logit_gradient(Z, Y, g_exact)
     dX = G @ Wd            # weights before the update (the update comes later in Algorithm 1)
     dW = G.T @ X           # BF16 inputs, summed over the batch, no 1/B
-    elem = label_ids[:, None] * np.int64(d) + np.arange(d, dtype=np.int64)[None, :]
+    if dropout:
+        dW = np.where(keep, dW, 0.0) * scale
     if (flags & FLAG_KAHAN) and kahan_rows is not None:
         head = label_ids < kahan_rows
         comp_bits = np.asarray(comp_bits)
@@ -410,7 +464,8 @@ def head_step(W_bits, comp_bits, X_bits, indptr, indices, lr, seed, step, fmt, f
     return dict(Z=Z, G=G, dX_partial=dX, dW=dW, W_new=Wn, comp_new=cn, loss=bce_loss(Z, Y))
 
 
-def input_gradient_rows(W_bits, X_bits, indptr, indices, fmt, rows, block=65536, g_exact=False):
+def input_gradient_rows(W_bits, X_bits, indptr, indices, fmt, rows, block=65536, g_exact=False,
+                        dropout=0, seed=0, step=0):
     """Rows `rows` of the full input gradient dX = (sigmoid(Xq W^T) - Y) W over all labels,
     streaming the weight rows in blocks so that millions of labels fit in memory.  Also returns
     the logits of those rows, Z[len(rows), L]."""
@@ -428,6 +483,9 @@ def input_gradient_rows(W_bits, X_bits, indptr, indices, fmt, rows, block=65536,
     for l0 in range(0, L, block):
         l1 = min(L, l0 + block)
         Wd = decode(W_bits[l0:l1], fmt)
+        if dropout:
+            elem = np.arange(l0, l1, dtype=np.int64)[:, None] * np.int64(d) + np.arange(d, dtype=np.int64)[None, :]
+            Wd = np.where(dropout_keep(seed, step, elem, dropout), Wd, 0.0) * (256.0 / (256.0 - dropout))
         z = Xq @ Wd.T
         Y = csr_to_dense(sub_ptr, sub_idx, None, col_ids=np.arange(l0, l1))
         dX += logit_gradient(z, Y, g_exact) @ Wd

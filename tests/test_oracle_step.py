@@ -194,6 +194,77 @@ def test_weight_decay_is_the_l2_term_of_sgd(fmt):
     np.testing.assert_array_equal(zero, base)
 
 
+def test_classifier_dropout_is_the_gradient_of_the_masked_model():
+    """Appendix "Low-Memory Dropout for Classifier".  Pins: (i) torch autograd through an explicit
+    masked, rescaled copy of W (the copy the paper's kernel avoids) gives the oracle's logits, loss,
+    input gradient and weight gradient -- a mask missing from one of the three products, a missing
+    scale or a transposed mask fails here; (ii) threshold 0 is the step without dropout, bit for
+    bit; (iii) dropped elements see a zero gradient: with RNE and no decay they do not move."""
+    X_bits, W_bits, indptr, indices = _tiny(B=5, L=24, d=16)
+    L, d, T, seed, step = 24, 16, 96, 5, 3
+    out = o.head_step(W_bits, None, X_bits, indptr, indices, 0.05, seed, step, o.BF16, 0, g_exact=True, dropout=T)
+    keep = o.dropout_keep(seed, step, np.arange(L * d).reshape(L, d), T)
+    assert 0.4 < keep.mean() < 0.85
+    W = torch.from_numpy(o.decode_bf16(W_bits)).requires_grad_(True)
+    X = torch.from_numpy(o.decode_bf16(X_bits)).requires_grad_(True)
+    Y = torch.from_numpy(o.csr_to_dense(indptr, indices, L))
+    Wm = W * torch.from_numpy(keep.astype(np.float64)) * (256.0 / (256.0 - T))
+    Z = X @ Wm.T
+    loss = torch.nn.functional.binary_cross_entropy_with_logits(Z, Y, reduction="sum")
+    loss.backward()
+    np.testing.assert_allclose(out["Z"], Z.detach().numpy(), rtol=0, atol=1e-12)
+    assert abs(out["loss"] - loss.item()) < 1e-10
+    np.testing.assert_allclose(out["dX_partial"], X.grad.numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(out["dW"], W.grad.numpy(), rtol=0, atol=1e-12)
+    assert np.all(out["dW"][~keep] == 0.0) and np.any(out["dW"][keep] != 0.0)
+    # (ii)
+    a = o.head_step(W_bits, None, X_bits, indptr, indices, 0.05, seed, step, o.BF16, o.FLAG_SR)
+    b = o.head_step(W_bits, None, X_bits, indptr, indices, 0.05, seed, step, o.BF16, o.FLAG_SR, dropout=0)
+    np.testing.assert_array_equal(a["W_new"], b["W_new"])
+    np.testing.assert_array_equal(a["dX_partial"], b["dX_partial"])
+    # (iii)
+    c = o.head_step(W_bits, None, X_bits, indptr, indices, 0.05, seed, step, o.BF16, 0, dropout=T)
+    np.testing.assert_array_equal(c["W_new"][~keep], W_bits[~keep])
+    assert np.any(c["W_new"][keep] != W_bits[keep])
+
+
+def test_dropout_mask_stream():
+    """The keep mask: (i) byte b of a block is byte b of the generator's four little-endian output
+    words, checked through a byte view of the words; (ii) the drop rate is threshold/256 (a
+    binomial bound over 2^20 elements), for every block position alike; (iii) masks of different
+    steps and seeds differ, the same (seed, step) repeats, and a subset of elements gives the same
+    bits as the full range; (iv) the mask blocks are not the blocks of the rounding fields."""
+    seed, step = 0x1234567890ABCDEF, 77
+    elem = np.arange(64, dtype=np.int64)
+    ctr = np.array([[b, 0, step, 0x80000000] for b in range(4)], dtype=np.uint64)
+    key = np.array([seed & 0xFFFFFFFF, seed >> 32], dtype=np.uint64)
+    raw = np.ascontiguousarray(o.philox4x32_10(ctr, key).astype("<u4")).view(np.uint8).reshape(-1)
+    for T in (1, 64, 200, 255):
+        np.testing.assert_array_equal(o.dropout_keep(seed, step, elem, T), raw >= T)
+    assert o.dropout_keep(seed, step, elem, 0).all()
+    n = 1 << 20
+    big = np.arange(n, dtype=np.int64)
+    for T in (26, 128, 230):
+        keep = o.dropout_keep(seed, step, big, T)
+        p = T / 256
+        assert abs((~keep).mean() - p) < 5 * math.sqrt(p * (1 - p) / n)
+        per_pos = (~keep).reshape(-1, 16).mean(axis=0)
+        assert np.all(np.abs(per_pos - p) < 5 * math.sqrt(p * (1 - p) / (n / 16)))
+    k0 = o.dropout_keep(seed, step, big[:4096], 128)
+    assert 0.4 < np.mean(k0 != o.dropout_keep(seed, step + 1, big[:4096], 128)) < 0.6
+    assert 0.4 < np.mean(k0 != o.dropout_keep(seed + 1, step, big[:4096], 128)) < 0.6
+    np.testing.assert_array_equal(k0, o.dropout_keep(seed, step, big[:4096], 128))
+    sub = np.array([4095, 17, 16, 15, 1000], dtype=np.int64)
+    np.testing.assert_array_equal(o.dropout_keep(seed, step, sub, 128), k0[sub])
+    # (iv) block 0 of the rounding fields at the same (seed, step) is another Philox output
+    sr_words = o.philox4x32_10(np.array([0, 0, step, 0], dtype=np.uint64), key)
+    assert not np.array_equal(np.ascontiguousarray(sr_words.astype("<u4")).view(np.uint8), raw[:16])
+    with pytest.raises(ValueError):
+        o.dropout_keep(seed, 1 << 63, elem, 10)
+    with pytest.raises(ValueError):
+        o.dropout_keep(seed, step, elem, 256)
+
+
 def test_rne_cancels_small_updates_bit_identically():
     """Section 4.1: with round-to-nearest and a tiny learning rate the weights do not move."""
     X_bits, W_bits, indptr, indices = _tiny(w_std=0.3)
