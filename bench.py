@@ -69,6 +69,7 @@ def parse():
     ap.add_argument("--no-kahan", action="store_true", help="xl_sweep without the compensation buffer")
     ap.add_argument("--kahan-head", type=float, default=None,
                     help="compensation for this fraction of the labels only (the most frequent ones, ids 0..)")
+    ap.add_argument("--dropout", type=float, default=0.0, help="classifier dropout rate inside the products (default none)")
     ap.add_argument("--no-dx", action="store_true", help="skip the input gradient (weights-only step)")
     ap.add_argument("--topk", type=int, default=0, help="also time elmo_head_topk with this k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -120,7 +121,7 @@ def main():
     if kahan and args.kahan_head is not None:
         kahan_rows = min(L, max(128, int(round(args.kahan_head * L / 128.0)) * 128))
     kahan_frac = (kahan_rows or L) / L if kahan else 0.0      # share of the labels that carry compensation
-    head = b.Head(L, d, cfg.fmt, cfg.chunk, cfg.flags, B, 64 * B, device=dev, kahan_rows=kahan_rows)
+    head = b.Head(L, d, cfg.fmt, cfg.chunk, cfg.flags, B, 64 * B, device=dev, kahan_rows=kahan_rows, dropout_p=args.dropout)
     g = torch.Generator(device=dev)
     g.manual_seed(0)
     W = head.weights()
@@ -192,7 +193,7 @@ def main():
         roof = {"bound": "hbm", "achieved": kd["algo_gbs"], "unit": "GB/s", "peak": PEAK_HBM_GBS, "frac": kd["hbm_frac"]}
     # committed counter summaries exist for exactly these two workloads
     profile = None
-    if not args.no_dx and not args.no_kahan and args.kahan_head is None:
+    if not args.no_dx and not args.no_kahan and args.kahan_head is None and not args.dropout:
         if args.workload == "xl" and not (args.batch or args.chunk):
             profile = "head_step_xl_fp8_B1024.txt"
         elif args.workload == "xl_sweep" and B == 128 and cfg.chunk == 262144:
@@ -243,7 +244,7 @@ def main():
         Cb = np.zeros((n_s, d), np.uint16) if kahan else None
         t2 = time.perf_counter()
         o.head_step(Wb, Cb, X0, ip0, ix0, cfg.lr, 0, 0, cfg.fmt, cfg.flags, label_ids=np.arange(n_s),
-                    kahan_rows=(kahan_rows or None) if kahan else None)
+                    kahan_rows=(kahan_rows or None) if kahan else None, dropout=int(round(args.dropout * 256)))
         dt = time.perf_counter() - t2
         cpu = {"value": B / (dt * L / n_s), "unit": "samples/s", "cores": int(cores), "kind": "oracle",
                "sample": f"one full oracle step (FP64 logits, gradients, update with the same Philox fields) on labels "
@@ -260,7 +261,7 @@ def main():
                    "weights": "e4m3" if fp8 else "bf16", "kahan_bf16": kahan, "kahan_label_fraction": kahan_frac,
                    "stochastic_rounding": bool(cfg.flags & synth.FLAG_SR),
                    "positives_per_sample": float(len(batches[0][2]) / B), "zipf_s": cfg.zipf_s, "lr": cfg.lr,
-                   "input_gradient": not args.no_dx},
+                   "input_gradient": not args.no_dx, "classifier_dropout": round(args.dropout * 256) / 256},
         "roofline": roof, "kernels": kern, "whole_step": whole, "cpu_baseline": cpu,
     }
     if topk:

@@ -61,6 +61,16 @@ typedef struct {
                              hyper-parameter table; Algorithm 1 itself has none): the update uses
                              g + weight_decay * w in place of the gradient g, two more FP32 operations, each
                              rounded.  0 = none (the two operations are skipped).  In [0, 1]. */
+  float dropout_p;        /* dropout on the classifier weights inside the products (appendix "Low-Memory
+                             Dropout for Classifier": the weights are masked after they are loaded, before
+                             the matrix product, so no masked copy of W exists).  Per step every weight
+                             element is dropped with probability T/256, T = round(256 * dropout_p), the
+                             same mask for all samples of the batch; the logits and the input gradient use
+                             the masked weights scaled by 256/(256-T), and the weight gradient is that of
+                             the masked model (zero at dropped elements, scaled elsewhere).  The mask is
+                             byte e % 16 >= T of Philox4x32-10 with key = seed of the step and counter =
+                             (e / 16, step | 2^63), e = label * d + column; steps must stay below 2^63.
+                             elmo_head_topk never drops.  0 = none.  In [0, 255/256]. */
   void* workspace;        /* scratch; contents need not survive between calls */
   size_t workspace_bytes;
 } elmo_head_opts;
@@ -146,6 +156,10 @@ int elmo_quantize(const float* src, int64_t n, int dtype, int mode, uint64_t see
  * src, dst: device FP32, n entries each (may be the same buffer). */
 int elmo_quantize_em(const float* src, int64_t n, int exp_bits, int man_bits, int mode, uint64_t seed,
                      uint64_t step, uint64_t first_elem, float* dst, void* hip_stream);
+
+/* Host-side view of the dropout mask of elmo_head_opts.dropout_p: bit i of the result is 1 iff
+ * weight element 16 * block + i is kept at (seed, step) for the threshold T = threshold (0..255). */
+uint32_t elmo_dropout_keep16(uint64_t seed, uint64_t step, uint64_t block, uint32_t threshold);
 
 /* Host-side Philox4x32-10 (Salmon et al., SC'11) as used for the rounding fields. */
 void elmo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);

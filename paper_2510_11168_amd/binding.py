@@ -39,6 +39,7 @@ class elmo_head_opts(C.Structure):
         ("flags", C.c_uint32), ("max_B", C.c_int32), ("max_nnz", C.c_int64),
         ("W", C.c_void_p), ("W_bytes", C.c_size_t),
         ("comp", C.c_void_p), ("comp_bytes", C.c_size_t), ("kahan_rows", C.c_int64), ("weight_decay", C.c_float),
+        ("dropout_p", C.c_float),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
     ]
 
@@ -74,10 +75,13 @@ _lib.elmo_quantize.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_uint
                                C.c_void_p, C.c_void_p]
 _lib.elmo_philox4x32_10.restype = None
 _lib.elmo_philox4x32_10.argtypes = [C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+_lib.elmo_dropout_keep16.restype = C.c_uint32
+_lib.elmo_dropout_keep16.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint32]
 
 EXPORTS = ("elmo_last_error", "elmo_logit_buffer_bytes", "elmo_head_sizes", "elmo_head_create",
            "elmo_head_step", "elmo_head_topk", "elmo_head_destroy", "elmo_quantize", "elmo_philox4x32_10",
-           "elmo_head_profile", "elmo_head_profile_read", "elmo_precision_hits", "elmo_quantize_em")
+           "elmo_head_profile", "elmo_head_profile_read", "elmo_precision_hits", "elmo_quantize_em",
+           "elmo_dropout_keep16")
 
 
 def _check(rc: int) -> None:
@@ -113,12 +117,12 @@ def elmo_head_sizes(L, d, weight_dtype, chunk, max_B, max_nnz, flags, kahan_rows
 
 
 def elmo_head_create(L, d, weight_dtype, chunk, *, flags, max_B, max_nnz, W, comp, workspace, kahan_rows=0,
-                     weight_decay=0.0) -> int:
+                     weight_decay=0.0, dropout_p=0.0) -> int:
     """W, comp, workspace: 1-D torch.uint8 device tensors (comp may be None).  Returns the handle."""
     o = elmo_head_opts(flags=flags, max_B=max_B, max_nnz=max_nnz,
                        W=_ptr(W), W_bytes=0 if W is None else W.numel() * W.element_size(),
                        comp=_ptr(comp), comp_bytes=0 if comp is None else comp.numel() * comp.element_size(),
-                       kahan_rows=kahan_rows, weight_decay=weight_decay,
+                       kahan_rows=kahan_rows, weight_decay=weight_decay, dropout_p=dropout_p,
                        workspace=_ptr(workspace),
                        workspace_bytes=0 if workspace is None else workspace.numel() * workspace.element_size())
     h = C.c_void_p()
@@ -167,6 +171,10 @@ def elmo_quantize(src, n, dtype, mode, seed, step, first_elem, dst, stream=None)
     _check(_lib.elmo_quantize(_ptr(src), n, dtype, mode, seed, step, first_elem, _ptr(dst), _stream(stream)))
 
 
+def elmo_dropout_keep16(seed, step, block, threshold) -> int:
+    return int(_lib.elmo_dropout_keep16(seed, step, block, threshold))
+
+
 def elmo_philox4x32_10(ctr, key):
     c = (C.c_uint32 * 4)(*ctr)
     k = (C.c_uint32 * 2)(*key)
@@ -179,7 +187,8 @@ def elmo_philox4x32_10(ctr, key):
 class Head:
     """Allocates W / comp / workspace as torch device tensors and keeps the handle alive."""
 
-    def __init__(self, L, d, weight_dtype, chunk, flags, max_B, max_nnz, device="cuda:0", kahan_rows=0, weight_decay=0.0):
+    def __init__(self, L, d, weight_dtype, chunk, flags, max_B, max_nnz, device="cuda:0", kahan_rows=0, weight_decay=0.0,
+                 dropout_p=0.0):
         self.L, self.d, self.fmt, self.chunk, self.flags = L, d, weight_dtype, chunk, flags
         self.max_B, self.max_nnz = max_B, max_nnz
         self.kahan_rows = (kahan_rows or L) if flags & ELMO_KAHAN else 0   # label rows that carry compensation
@@ -190,7 +199,7 @@ class Head:
         self.bytes = (wb, cb, sb)
         self.h = elmo_head_create(L, d, weight_dtype, chunk, flags=flags, max_B=max_B, max_nnz=max_nnz,
                                   W=self.W, comp=self.comp, workspace=self.workspace, kahan_rows=kahan_rows,
-                                  weight_decay=weight_decay)
+                                  weight_decay=weight_decay, dropout_p=dropout_p)
 
     def weights(self):
         """[L, d] view of the raw weight bits: uint8 codes (E4M3) or int16 patterns (BF16)."""

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -40,6 +41,7 @@ struct Plan {
   int64_t L; int d; int fmt; int64_t chunk; int maxB; int64_t max_nnz; uint32_t flags;
   int64_t kahan_rows;                   // leading label rows that carry compensation (0 without ELMO_KAHAN)
   float weight_decay;                   // L2 term of the update, 0 = none
+  uint32_t drop_thresh;                 // classifier dropout: weights dropped with probability drop_thresh / 256, 0 = none
   int Bp_max, tiles_b_max, ntiles;      // padded batch, batch tiles, 128-label tiles of the whole head
   int dx_rows;                          // rows of FP32 input-gradient partials (slices x padded batch)
   size_t off_xq, off_xt, off_g, off_dx, off_loss, off_cnt, off_ptr, off_cur, off_pos, off_flag, off_topk, total;
@@ -63,6 +65,7 @@ int make_plan(int64_t L, int d, int fmt, int64_t chunk, int maxB, int64_t max_nn
   p.L = L; p.d = d; p.fmt = fmt; p.chunk = chunk; p.maxB = maxB; p.max_nnz = max_nnz; p.flags = flags;
   p.kahan_rows = (flags & ELMO_KAHAN) ? (kahan_rows ? kahan_rows : L) : 0;
   p.weight_decay = 0.0f;
+  p.drop_thresh = 0;
   p.Bp_max = round_up(maxB, 64);
   p.tiles_b_max = (p.Bp_max + 255) / 256;      // 256-sample tiles of the matrix products
   p.ntiles = (int)((L + 127) / 128);
@@ -153,6 +156,9 @@ int elmo_head_create(int64_t L, int32_t d, int weight_dtype, int64_t chunk, cons
   if (rc) return rc;
   if (!(opts->weight_decay >= 0.0f) || opts->weight_decay > 1.0f) return fail(-1, "weight_decay must be in [0, 1] (got %g)", (double)opts->weight_decay);
   p.weight_decay = opts->weight_decay;
+  if (!(opts->dropout_p >= 0.0f) || opts->dropout_p > 255.0f / 256.0f)
+    return fail(-1, "dropout_p must be in [0, 255/256] (got %g)", (double)opts->dropout_p);
+  p.drop_thresh = (uint32_t)lrintf(opts->dropout_p * 256.0f);
   if (!opts->W || opts->W_bytes < p.W_bytes) return fail(-1, "W buffer missing or smaller than %zu bytes", p.W_bytes);
   if ((opts->flags & ELMO_KAHAN) && (!opts->comp || opts->comp_bytes < p.comp_bytes))
     return fail(-1, "ELMO_KAHAN needs a compensation buffer of %zu bytes", p.comp_bytes);
@@ -206,6 +212,15 @@ void elmo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t o
   out[0] = c.x; out[1] = c.y; out[2] = c.z; out[3] = c.w;
 }
 
+uint32_t elmo_dropout_keep16(uint64_t seed, uint64_t step, uint64_t block, uint32_t threshold) {
+  const elmo::U4 b = elmo::drop_block(block, seed, step);
+  const uint32_t tb = (threshold & 0xFFu) * 0x01010101u;
+  const uint32_t w[4] = {b.x, b.y, b.z, b.w};
+  uint32_t bits = 0;
+  for (int i = 0; i < 16; ++i) bits |= ((elmo::keep_bytes(w[i >> 2], tb) >> (8 * (i & 3))) & 1u) << i;
+  return bits;
+}
+
 int elmo_quantize(const float* src, int64_t n, int dtype, int mode, uint64_t seed, uint64_t step,
                   uint64_t first_elem, void* dst, void* hip_stream) {
   if (n < 0 || (n > 0 && (!src || !dst))) return fail(-1, "bad src/dst/n");
@@ -237,25 +252,37 @@ int poll_validation(elmo_head* h) {
   return 0;
 }
 
-template <bool FP8, bool LOSS, int TB>
+template <bool FP8, bool LOSS, int TB, bool DROP>
 void launch_logits_tb(hipStream_t st, int grid, const char* Xa, int a_rows, const char* Wc, int n, int d, int Bp, int B,
-                      uint16_t* Gt, const int* binptr, const int2* pos, int tile0, float* loss_slots) {
-  elmo::k_logits<FP8, LOSS, TB><<<grid, elmo::kGemmThreads, elmo::logits_smem<TB>(), st>>>(Xa, a_rows, Wc, n, d, Bp, B, Gt, binptr,
-                                                                                       pos, tile0, loss_slots);
+                      uint16_t* Gt, const int* binptr, const int2* pos, int tile0, float* loss_slots, uint64_t seed, uint64_t step,
+                      uint64_t elem0, elmo::DropArgs dr) {
+  elmo::k_logits<FP8, LOSS, TB, DROP><<<grid, elmo::kGemmThreads, elmo::logits_smem<TB>(), st>>>(
+      Xa, a_rows, Wc, n, d, Bp, B, Gt, binptr, pos, tile0, loss_slots, seed, step, elem0, dr);
 }
 // tb = rows of the batch tile (256, or 128 when the whole padded batch fits in 128 rows)
 template <bool FP8, bool LOSS>
 void launch_logits(hipStream_t st, int tb, int grid, const char* Xa, int a_rows, const char* Wc, int n, int d, int Bp, int B,
-                   uint16_t* Gt, const int* binptr, const int2* pos, int tile0, float* loss_slots) {
-  if (tb == 128) launch_logits_tb<FP8, LOSS, 128>(st, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, binptr, pos, tile0, loss_slots);
-  else launch_logits_tb<FP8, LOSS, 256>(st, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, binptr, pos, tile0, loss_slots);
+                   uint16_t* Gt, const int* binptr, const int2* pos, int tile0, float* loss_slots, uint64_t seed, uint64_t step,
+                   uint64_t elem0, elmo::DropArgs dr) {
+#define ELMO_LOGITS(TB_, DR_) \
+  launch_logits_tb<FP8, LOSS, TB_, DR_>(st, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, binptr, pos, tile0, loss_slots, seed, step, elem0, dr)
+  if (tb == 128) { if (dr.thresh) ELMO_LOGITS(128, true); else ELMO_LOGITS(128, false); }
+  else { if (dr.thresh) ELMO_LOGITS(256, true); else ELMO_LOGITS(256, false); }
+#undef ELMO_LOGITS
 }
 
 template <int FMT>
 void launch_update(hipStream_t st, int grid, bool sr, bool kahan, const char* Gt, const char* XT, char* Wc, uint16_t* Cc,
-                   int n, int d, int Bp, float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0) {
-#define ELMO_UPD(SR_, KA_) \
-  elmo::k_update<FMT, SR_, KA_><<<grid, elmo::kGemmThreads, elmo::kUpdateSmem, st>>>(Gt, XT, Wc, Cc, n, d, Bp, lr, wd, seed, step, elem0)
+                   int n, int d, int Bp, float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0, elmo::DropArgs dr) {
+#define ELMO_UPD(SR_, KA_)                                                                                                      \
+  do {                                                                                                                          \
+    if (dr.thresh)                                                                                                              \
+      elmo::k_update<FMT, SR_, KA_, true><<<grid, elmo::kGemmThreads, elmo::kUpdateSmem, st>>>(Gt, XT, Wc, Cc, n, d, Bp, lr, wd, \
+                                                                                               seed, step, elem0, dr);         \
+    else                                                                                                                        \
+      elmo::k_update<FMT, SR_, KA_, false><<<grid, elmo::kGemmThreads, elmo::kUpdateSmem, st>>>(Gt, XT, Wc, Cc, n, d, Bp, lr, wd, \
+                                                                                                seed, step, elem0, dr);        \
+  } while (0)
   if (sr && kahan) ELMO_UPD(true, true);
   else if (sr) ELMO_UPD(true, false);
   else if (kahan) ELMO_UPD(false, true);
@@ -300,24 +327,29 @@ int raise_lds_limits() {
   static bool done = false;
   if (done) return 0;
 #define ELMO_ATTR(k, bytes) ELMO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))
-  ELMO_ATTR((elmo::k_logits<true, true, 256>), elmo::logits_smem<256>());
-  ELMO_ATTR((elmo::k_logits<true, true, 128>), elmo::logits_smem<128>());
-  ELMO_ATTR((elmo::k_logits<true, false, 256>), elmo::logits_smem<256>());
-  ELMO_ATTR((elmo::k_logits<true, false, 128>), elmo::logits_smem<128>());
-  ELMO_ATTR((elmo::k_logits<false, true, 256>), elmo::logits_smem<256>());
-  ELMO_ATTR((elmo::k_logits<false, true, 128>), elmo::logits_smem<128>());
-  ELMO_ATTR((elmo::k_logits<false, false, 256>), elmo::logits_smem<256>());
-  ELMO_ATTR((elmo::k_logits<false, false, 128>), elmo::logits_smem<128>());
-  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, true, true>), elmo::kUpdateSmem);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, true, false>), elmo::kUpdateSmem);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, false, true>), elmo::kUpdateSmem);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_BF16, false, false>), elmo::kUpdateSmem);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, true, true>), elmo::kUpdateSmem);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, true, false>), elmo::kUpdateSmem);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, false, true>), elmo::kUpdateSmem);
-  ELMO_ATTR((elmo::k_update<elmo::FMT_E4M3, false, false>), elmo::kUpdateSmem);
-  ELMO_ATTR((elmo::k_dx<true>), elmo::dx_smem_bytes<true>());
-  ELMO_ATTR((elmo::k_dx<false>), elmo::dx_smem_bytes<false>());
+#define ELMO_ATTR_LOGITS(F, LO) \
+  ELMO_ATTR((elmo::k_logits<F, LO, 256, false>), elmo::logits_smem<256>()); ELMO_ATTR((elmo::k_logits<F, LO, 256, true>), elmo::logits_smem<256>()); \
+  ELMO_ATTR((elmo::k_logits<F, LO, 128, false>), elmo::logits_smem<128>()); ELMO_ATTR((elmo::k_logits<F, LO, 128, true>), elmo::logits_smem<128>())
+  ELMO_ATTR_LOGITS(true, true);
+  ELMO_ATTR_LOGITS(true, false);
+  ELMO_ATTR_LOGITS(false, true);
+  ELMO_ATTR_LOGITS(false, false);
+#undef ELMO_ATTR_LOGITS
+#define ELMO_ATTR_UPDATE(F, SR_, KA_) \
+  ELMO_ATTR((elmo::k_update<F, SR_, KA_, false>), elmo::kUpdateSmem); ELMO_ATTR((elmo::k_update<F, SR_, KA_, true>), elmo::kUpdateSmem)
+  ELMO_ATTR_UPDATE(elmo::FMT_BF16, true, true);
+  ELMO_ATTR_UPDATE(elmo::FMT_BF16, true, false);
+  ELMO_ATTR_UPDATE(elmo::FMT_BF16, false, true);
+  ELMO_ATTR_UPDATE(elmo::FMT_BF16, false, false);
+  ELMO_ATTR_UPDATE(elmo::FMT_E4M3, true, true);
+  ELMO_ATTR_UPDATE(elmo::FMT_E4M3, true, false);
+  ELMO_ATTR_UPDATE(elmo::FMT_E4M3, false, true);
+  ELMO_ATTR_UPDATE(elmo::FMT_E4M3, false, false);
+#undef ELMO_ATTR_UPDATE
+  ELMO_ATTR((elmo::k_dx<true, false>), elmo::dx_smem_bytes<true>());
+  ELMO_ATTR((elmo::k_dx<true, true>), elmo::dx_smem_bytes<true>());
+  ELMO_ATTR((elmo::k_dx<false, false>), elmo::dx_smem_bytes<false>());
+  ELMO_ATTR((elmo::k_dx<false, true>), elmo::dx_smem_bytes<false>());
   ELMO_ATTR((elmo::k_topk_filter<true, true>), elmo::logits_smem<256>());
   ELMO_ATTR((elmo::k_topk_filter<true, false>), elmo::logits_smem<256>());
   ELMO_ATTR((elmo::k_topk_filter<false, true>), elmo::logits_smem<256>());
@@ -340,10 +372,12 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
   if (B < 1 || B > p.maxB) return fail(-1, "B = %d outside [1, max_B = %d]", B, p.maxB);
   if (nnz < 0 || nnz > p.max_nnz) return fail(-1, "nnz = %lld outside [0, max_nnz = %lld]", (long long)nnz, (long long)p.max_nnz);
   if (nnz > 0 && !indices) return fail(-1, "indices must not be NULL when nnz > 0");
+  if (p.drop_thresh && (step >> 63)) return fail(-1, "with dropout the step counter must stay below 2^63");
   if (int rc = poll_validation(h)) return rc;
   if (int rc = raise_lds_limits()) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
   const bool fp8 = p.fmt == ELMO_FP8_E4M3;
+  const elmo::DropArgs dr{p.drop_thresh, 256.0f / (256.0f - (float)p.drop_thresh)};
   const int d = p.d, Bp = round_up(B, 64), Bp256 = round_up(Bp, 256);
   const int tiles_b = Bp256 / 256, tiles_j = (d + 255) / 256;   // 256 x 256 tiles of the matrix products
 
@@ -358,8 +392,10 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
   int2* pos = (int2*)(h->ws + p.off_pos);
   int* flag = (p.flags & ELMO_VALIDATE) ? (int*)(h->ws + p.off_flag) : nullptr;
 
-  // Small batches are bound by memory traffic: input gradient and update share one pass over W.
-  const bool small_batch = Bp <= 128 && d % 256 == 0;
+  // Small batches are bound by memory traffic: input gradient and update share one pass over W
+  // (not with dropout: the fused kernel updates the weights from the tile its product reads, and
+  // the product would need that tile masked).
+  const bool small_batch = Bp <= 128 && d % 256 == 0 && !p.drop_thresh;
   const int col_blocks = d / 256, label_groups = small_batch ? 256 / col_blocks : 0;
   // label slices of the input-gradient product: at most one 512-thread workgroup per CU, so the
   // whole grid is resident at once (256 CUs) and no second, nearly empty round of workgroups runs
@@ -410,12 +446,13 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
     {
       const int tb = Bp <= 128 ? 128 : 256;        // the logits kernel's tile is tb samples x tb labels
       const int grid = ((n + tb - 1) / tb) * ((Bp + tb - 1) / tb);
+      const uint64_t celem0 = (uint64_t)c0 * (uint64_t)d;
       if (fp8) {
-        if (loss_out) launch_logits<true, true>(st, tb, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots);
-        else launch_logits<true, false>(st, tb, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots);
+        if (loss_out) launch_logits<true, true>(st, tb, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots, seed, step, celem0, dr);
+        else launch_logits<true, false>(st, tb, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots, seed, step, celem0, dr);
       } else {
-        if (loss_out) launch_logits<false, true>(st, tb, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots);
-        else launch_logits<false, false>(st, tb, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots);
+        if (loss_out) launch_logits<false, true>(st, tb, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots, seed, step, celem0, dr);
+        else launch_logits<false, false>(st, tb, grid, Xa, a_rows, Wc, n, d, Bp, B, Gt, ptr, pos, tile0, loss_slots, seed, step, celem0, dr);
       }
       if (int rc = check_launch("k_logits")) return rc;
     }
@@ -446,8 +483,12 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
     if (dX_out) {
       prof.mark(st, CLS_DX);
       const int grid = tiles_b * tiles_j * S;
-      if (fp8) elmo::k_dx<true><<<grid, elmo::kGemmThreads, elmo::dx_smem_bytes<true>(), st>>>((const char*)Gt, Wc, dXacc, n, d, Bp, Bp256, S);
-      else elmo::k_dx<false><<<grid, elmo::kGemmThreads, elmo::dx_smem_bytes<false>(), st>>>((const char*)Gt, Wc, dXacc, n, d, Bp, Bp256, S);
+      const uint64_t celem0 = (uint64_t)c0 * (uint64_t)d;
+#define ELMO_DX(F, DR_) \
+  elmo::k_dx<F, DR_><<<grid, elmo::kGemmThreads, elmo::dx_smem_bytes<F>(), st>>>((const char*)Gt, Wc, dXacc, n, d, Bp, Bp256, S, seed, step, celem0, dr)
+      if (fp8) { if (dr.thresh) ELMO_DX(true, true); else ELMO_DX(true, false); }
+      else { if (dr.thresh) ELMO_DX(false, true); else ELMO_DX(false, false); }
+#undef ELMO_DX
       if (int rc = check_launch("k_dx")) return rc;
     }
     prof.mark(st, CLS_UPDATE);
@@ -460,8 +501,8 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
       const char* Gp = (const char*)(Gt + (size_t)l_off * Bp);
       char* Wp = Wc + (size_t)l_off * d * esz;
       uint16_t* Cp = kahan ? Cc + (size_t)l_off * d : nullptr;
-      if (fp8) launch_update<elmo::FMT_E4M3>(st, grid, sr, kahan, Gp, (const char*)XT, Wp, Cp, n_part, d, Bp, lr, p.weight_decay, seed, step, elem0);
-      else launch_update<elmo::FMT_BF16>(st, grid, sr, kahan, Gp, (const char*)XT, Wp, Cp, n_part, d, Bp, lr, p.weight_decay, seed, step, elem0);
+      if (fp8) launch_update<elmo::FMT_E4M3>(st, grid, sr, kahan, Gp, (const char*)XT, Wp, Cp, n_part, d, Bp, lr, p.weight_decay, seed, step, elem0, dr);
+      else launch_update<elmo::FMT_BF16>(st, grid, sr, kahan, Gp, (const char*)XT, Wp, Cp, n_part, d, Bp, lr, p.weight_decay, seed, step, elem0, dr);
       if (int rc = check_launch("k_update")) return rc;
     }
   }

@@ -139,6 +139,52 @@ template <int FN> __device__ inline void zero_acc(f32x16 (&acc)[2][FN]) {
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 }
 
+// Classifier dropout on a weight slab that has landed in LDS (appendix "Low-Memory Dropout for
+// Classifier": mask after the load, before the product).  The slab is ROWS weight rows of ROWB
+// bytes of consecutive columns in the tile_off<ROWB> layout; blk0 is the mask block of its first
+// 16 elements and blk_stride the mask blocks per weight row (d / 16).  Every thread draws whole
+// mask blocks and zeroes the dropped elements in place.
+template <int ROWS, int ROWB, bool FP8>
+__device__ __forceinline__ void drop_slab(char* tile, uint64_t blk0, uint32_t blk_stride, uint64_t seed, uint64_t step,
+                                          uint32_t thresh, int tid) {
+  constexpr int UPR = ROWB / (FP8 ? 16 : 32);                  // mask blocks per slab row
+  static_assert((ROWS * UPR) % kGemmThreads == 0, "slab size");
+  const uint32_t tb = thresh * 0x01010101u;
+#pragma unroll
+  for (int u0 = 0; u0 < ROWS * UPR; u0 += kGemmThreads) {
+    const int u = u0 + tid, r = u / UPR, k = u % UPR;
+    const U4 rb = drop_block(blk0 + (uint64_t)r * blk_stride + k, seed, step);
+    if (FP8) {
+      u32x4* p = reinterpret_cast<u32x4*>(tile + tile_off<ROWB>(r, k));
+      u32x4 w = *p;
+      w[0] &= keep_bytes(rb.x, tb);
+      w[1] &= keep_bytes(rb.y, tb);
+      w[2] &= keep_bytes(rb.z, tb);
+      w[3] &= keep_bytes(rb.w, tb);
+      *p = w;
+    } else {
+      // byte mask -> one 16-bit mask per element (v_perm_b32 doubles each byte)
+      u32x4* p0 = reinterpret_cast<u32x4*>(tile + tile_off<ROWB>(r, 2 * k));
+      u32x4* p1 = reinterpret_cast<u32x4*>(tile + tile_off<ROWB>(r, 2 * k + 1));
+      u32x4 a = *p0, b = *p1;
+      uint32_t m = keep_bytes(rb.x, tb);
+      a[0] &= __builtin_amdgcn_perm(m, m, 0x01010000u);
+      a[1] &= __builtin_amdgcn_perm(m, m, 0x03030202u);
+      m = keep_bytes(rb.y, tb);
+      a[2] &= __builtin_amdgcn_perm(m, m, 0x01010000u);
+      a[3] &= __builtin_amdgcn_perm(m, m, 0x03030202u);
+      m = keep_bytes(rb.z, tb);
+      b[0] &= __builtin_amdgcn_perm(m, m, 0x01010000u);
+      b[1] &= __builtin_amdgcn_perm(m, m, 0x03030202u);
+      m = keep_bytes(rb.w, tb);
+      b[2] &= __builtin_amdgcn_perm(m, m, 0x01010000u);
+      b[3] &= __builtin_amdgcn_perm(m, m, 0x03030202u);
+      *p0 = a;
+      *p1 = b;
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Logits + fused epilogue (Algorithm 1: matmul_fp8, sigmoid_, "-= 1" at the positives).
 // One workgroup computes a 256 (samples) x 256 (labels) tile of Z = Xq W_c^T with FP32
@@ -198,23 +244,27 @@ __device__ __forceinline__ void logits_slab_product(const char* sa, const char* 
 // Z tile = Xa[TB rows] . Wc[TB rows]^T over the full embedding width (rowb bytes per row), FP32
 // accumulators.  Waves as (8 / WGN) x WGN with WGN = 2 (TB = 256, 64 x 128 per wave) or 4
 // (TB = 128, 64 x 32 per wave).
-template <bool FP8, int TB, int FN>
+template <bool FP8, int TB, int FN, class Prep = NoPrep>
 __device__ __forceinline__ void logits_tile_product(const char* __restrict__ Xa, int a_valid, const char* __restrict__ Wc, int w_valid,
-                                                    size_t rowb, char* smem, int wave, int lane, f32x16 (&acc)[2][FN]) {
+                                                    size_t rowb, char* smem, int wave, int lane, f32x16 (&acc)[2][FN],
+                                                    Prep&& prep = Prep{}) {
   constexpr int WGN = TB / 32 / FN;
   static_assert(WGN == (TB == 256 ? 2 : 4), "wave layout");
   const int wm = wave / WGN, wn = wave % WGN;
   zero_acc(acc);
   ring_pipeline_pp<TB, 128, TB, 128, 2, kGemmWaves, true>(
       Xa, rowb, a_valid, 0, 128, 8, Wc, rowb, w_valid, 0, 128, 8, (int)(rowb >> 7), smem, wave, lane,
-      [&](const char* sa, const char* sb, int half) { logits_slab_product<FP8, FN>(sa, sb, half, wm, wn, lane, acc); });
+      [&](const char* sa, const char* sb, int half) { logits_slab_product<FP8, FN>(sa, sb, half, wm, wn, lane, acc); },
+      static_cast<Prep&&>(prep));
 }
 
-template <bool FP8, bool LOSS, int TB>
+// DROP: the W slabs are masked in LDS as they land (drop_slab) and Z is scaled by 1 / (1 - p);
+// elem0 = flat index of the chunk's first weight element.
+template <bool FP8, bool LOSS, int TB, bool DROP>
 __global__ void __launch_bounds__(kGemmThreads, TB == 256 ? 1 : 2)
 k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, int n, int d, int Bp, int B,
          uint16_t* __restrict__ Gt, const int* __restrict__ binptr, const int2* __restrict__ pos, int tile0,
-         float* __restrict__ loss_slots) {
+         float* __restrict__ loss_slots, uint64_t seed, uint64_t step, uint64_t elem0, DropArgs dr) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int WGN = TB == 256 ? 2 : 4, FN = TB / 32 / WGN;   // waves along the labels, 32-label blocks per wave
   constexpr int MW = TB / 32, SEGS = TB / 8;
@@ -226,7 +276,16 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
   const size_t rowb = (size_t)d * (FP8 ? 1 : 2);
 
   f32x16 acc[2][FN];
-  logits_tile_product<FP8, TB, FN>(Xa + (size_t)b0 * rowb, a_rows - b0, Wc + (size_t)l0 * rowb, n - l0, rowb, smem, wave, lane, acc);
+  if constexpr (DROP) {
+    const uint64_t blk_tile = (elem0 + (uint64_t)l0 * d) >> 4;     // mask block of the tile's first element
+    logits_tile_product<FP8, TB, FN>(Xa + (size_t)b0 * rowb, a_rows - b0, Wc + (size_t)l0 * rowb, n - l0, rowb, smem, wave, lane, acc,
+                                     [&](char* sb, int ks) {
+                                       drop_slab<TB, 128, FP8>(sb, blk_tile + (uint64_t)ks * (FP8 ? 8 : 4), (uint32_t)d >> 4, seed,
+                                                               step, dr.thresh, tid);
+                                     });
+  } else {
+    logits_tile_product<FP8, TB, FN>(Xa + (size_t)b0 * rowb, a_rows - b0, Wc + (size_t)l0 * rowb, n - l0, rowb, smem, wave, lane, acc);
+  }
 
   constexpr int GP = logits_gpitch<TB>();
   char* gts = smem;                                                      // G^T stage: TB rows of GP bytes
@@ -263,7 +322,7 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
         float g[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const float z = acc[i][j][4 * q + e];
+          const float z = DROP ? acc[i][j][4 * q + e] * dr.scale : acc[i][j][4 * q + e];
           const float y = (float)((ybits >> (8 * q + e)) & 1u);
           g[e] = row_ok ? sigmoidf_fast(z) - y : 0.0f;
           if (LOSS) loss += (row_ok && b0 + b + e < B) ? softplusf_fast(z) - y * z : 0.0f;
@@ -321,10 +380,10 @@ __device__ inline void add_acc_to_global(float* __restrict__ dst, int d, int lan
 template <bool FP8> constexpr int dx_stages() { return FP8 ? 3 : 2; }
 template <bool FP8> constexpr int dx_smem_bytes() { return dx_stages<FP8>() * (64 * 512 + 64 * (FP8 ? 256 : 512)); }
 
-template <bool FP8>
+template <bool FP8, bool DROP>
 __global__ void __launch_bounds__(kGemmThreads, 1)
 k_dx(const char* __restrict__ Gt, const char* __restrict__ Wc, float* __restrict__ dXacc, int n, int d, int Bp,
-     int Bp256, int S) {
+     int Bp256, int S, uint64_t seed, uint64_t step, uint64_t elem0, DropArgs dr) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int ESZ = FP8 ? 1 : 2, WROWB = 256 * ESZ;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
@@ -339,26 +398,46 @@ k_dx(const char* __restrict__ Gt, const char* __restrict__ Wc, float* __restrict
 
   f32x16 acc[2][4];
   zero_acc(acc);
-  ring_pipeline_pp<64, 512, 64, WROWB, dx_stages<FP8>(), kGemmWaves, true>(
-      Gt + (size_t)ks0 * 64 * strideA + (size_t)b0 * 2, strideA, (ksteps - ks0) * 64 /* zero rows past n are real */, 64, 64 * strideA, 32,
-      Wc + (size_t)ks0 * 64 * strideB + (size_t)j0 * ESZ, strideB, n - ks0 * 64, 64, 64 * strideB, min(256, d - j0) * ESZ / 16,
-      ks1 - ks0, smem, wave, lane, [&](const char* sa, const char* sb, int half) {
+  auto product = [&](const char* sa, const char* sb, int half) {
 #pragma unroll
-        for (int kk = 2 * half; kk < 2 * half + 2; ++kk) {
-          bf16x8 a[2], b[4];
+    for (int kk = 2 * half; kk < 2 * half + 2; ++kk) {
+      bf16x8 a[2], b[4];
 #pragma unroll
-          for (int i = 0; i < 2; ++i) a[i] = frag_tr_bf16<512>(sa, 16 * kk, wm * 64 + 32 * i, lane);
+      for (int i = 0; i < 2; ++i) a[i] = frag_tr_bf16<512>(sa, 16 * kk, wm * 64 + 32 * i, lane);
 #pragma unroll
-          for (int j = 0; j < 4; ++j)
-            b[j] = FP8 ? frag_tr_fp8<WROWB>(sb, 16 * kk, wn * 128 + 32 * j, lane)
-                       : frag_tr_bf16<WROWB>(sb, 16 * kk, wn * 128 + 32 * j, lane);
+      for (int j = 0; j < 4; ++j)
+        b[j] = FP8 ? frag_tr_fp8<WROWB>(sb, 16 * kk, wn * 128 + 32 * j, lane)
+                   : frag_tr_bf16<WROWB>(sb, 16 * kk, wn * 128 + 32 * j, lane);
 #pragma unroll
-          for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-        }
-      });
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+  };
+  const char* ga = Gt + (size_t)ks0 * 64 * strideA + (size_t)b0 * 2;
+  const char* gb = Wc + (size_t)ks0 * 64 * strideB + (size_t)j0 * ESZ;
+  const int va0 = (ksteps - ks0) * 64;                 // zero rows of G^T past n are real
+  const int chunks_b = min(256, d - j0) * ESZ / 16;
+  if constexpr (DROP) {
+    // the same masked weights as in the logits product (appendix "Low-Memory Dropout for Classifier")
+    const uint64_t blk_first = (elem0 + (uint64_t)ks0 * 64 * d + j0) >> 4;
+    ring_pipeline_pp<64, 512, 64, WROWB, dx_stages<FP8>(), kGemmWaves, true>(
+        ga, strideA, va0, 64, 64 * strideA, 32, gb, strideB, n - ks0 * 64, 64, 64 * strideB, chunks_b, ks1 - ks0, smem, wave, lane,
+        product, [&](char* sb, int ks) {
+          drop_slab<64, WROWB, FP8>(sb, blk_first + (uint64_t)ks * 4 * d, (uint32_t)d >> 4, seed, step, dr.thresh, tid);
+        });
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] *= dr.scale;
+  } else {
+    ring_pipeline_pp<64, 512, 64, WROWB, dx_stages<FP8>(), kGemmWaves, true>(
+        ga, strideA, va0, 64, 64 * strideA, 32, gb, strideB, n - ks0 * 64, 64, 64 * strideB, chunks_b, ks1 - ks0, smem, wave, lane,
+        product);
+  }
   float* out = dXacc + (size_t)s * Bp256 * d;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -453,10 +532,12 @@ __device__ inline void update16(uint32_t (&w)[8], uint32_t (&c)[8], const float 
   }
 }
 
-template <int FMT, bool SR, bool KAHAN>
+// DROP: the weight gradient is that of the masked model: zero where the step's mask drops the
+// element, scaled by 1 / (1 - p) elsewhere.
+template <int FMT, bool SR, bool KAHAN, bool DROP>
 __global__ void __launch_bounds__(kGemmThreads, 1)
 k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restrict__ Wc, uint16_t* __restrict__ Cc,
-         int n, int d, int Bp, float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0) {
+         int n, int d, int Bp, float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0, DropArgs dr) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int ESZ = FMT == FMT_E4M3 ? 1 : 2;
   constexpr int WQ = FMT == FMT_E4M3 ? 1 : 2;       // 16-byte loads per 16 weights
@@ -547,6 +628,13 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
       for (int q = 0; q < 4; ++q) {
         const f32x4 t = *reinterpret_cast<const f32x4*>(gs + row * kGPitch + useg * 16 + 4 * q);
         g[4 * q] = t[0]; g[4 * q + 1] = t[1]; g[4 * q + 2] = t[2]; g[4 * q + 3] = t[3];
+      }
+      if (DROP) {
+        const U4 mb = drop_block((elem0 + eoff) >> 4, seed, step);
+        const uint32_t tb = dr.thresh * 0x01010101u;
+        const uint32_t km[4] = {keep_bytes(mb.x, tb), keep_bytes(mb.y, tb), keep_bytes(mb.z, tb), keep_bytes(mb.w, tb)};
+#pragma unroll
+        for (int i = 0; i < 16; ++i) g[i] = ((km[i >> 2] >> (8 * (i & 3))) & 1u) ? g[i] * dr.scale : 0.0f;
       }
       U4 rb[2];
       if (SR) {

@@ -56,6 +56,36 @@ __host__ __device__ inline uint32_t sr_field(const U4& b, int f) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Classifier dropout (appendix "Low-Memory Dropout for Classifier"): the keep mask is a pure
+// function of (seed, step, element), so every kernel that touches a weight tile regenerates it
+// and no masked copy of W exists.  One Philox block per 16 consecutive elements, one byte each:
+// counter = (block, step | 2^63) -- the top bit separates this stream from the rounding fields,
+// whose steps stay below 2^63 -- and element e is kept iff byte e % 16 of the block is >= thresh
+// (byte b = bits [8 (b % 4), +8) of word b / 4), i.e. dropped with probability thresh / 256.
+// ---------------------------------------------------------------------------------------------
+struct DropArgs {
+  uint32_t thresh;      // 1..255 (kernels built without dropout ignore the struct)
+  float scale;          // 256 / (256 - thresh), applied to FP32 results, never to stored weights
+};
+
+__host__ __device__ inline U4 drop_block(uint64_t blk, uint64_t seed, uint64_t step) {
+  U4 c;
+  c.x = (uint32_t)blk;
+  c.y = (uint32_t)(blk >> 32);
+  c.z = (uint32_t)step;
+  c.w = (uint32_t)(step >> 32) | 0x80000000u;
+  return philox4x32_10(c, (uint32_t)seed, (uint32_t)(seed >> 32));
+}
+
+// 0xFF in every byte of r that is >= thresh (unsigned), 0x00 elsewhere.  tb = thresh * 0x01010101.
+// The low seven bits are compared by a borrow-free subtraction per byte, the top bits decide first.
+__host__ __device__ inline uint32_t keep_bytes(uint32_t r, uint32_t tb) {
+  const uint32_t s = ((r & 0x7F7F7F7Fu) | 0x80808080u) - (tb & 0x7F7F7F7Fu);   // bit 7: low bits of r >= low bits of thresh
+  const uint32_t ge = ((r & ~tb) | (~(r ^ tb) & s)) & 0x80808080u;
+  return ge | (ge - (ge >> 7));
+}
+
+// ---------------------------------------------------------------------------------------------
 // Bit casts and decoding
 // ---------------------------------------------------------------------------------------------
 __device__ inline uint32_t f2u(float f) { return __float_as_uint(f); }

@@ -13,6 +13,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace elmo {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -147,9 +149,14 @@ template <int ROWS, int ROWB> struct TileLoader {
 // restrict-qualified parameters on purpose: inlining then tags every LDS access inside with alias
 // information, without which the compiler puts a vmcnt(0) in front of LDS reads it cannot tell
 // from the asynchronous loads still in flight.
-template <int AROWS, int AROWB, int BROWS, int BROWB, int NST, int NW, bool UNEVEN, class Src, class Mma>
+// prep(stageB, ks), if given, is run by every wave on the landed B slab before the product (it may
+// rewrite the slab in LDS); a barrier follows it.
+struct NoPrep {};
+template <int AROWS, int AROWB, int BROWS, int BROWB, int NST, int NW, bool UNEVEN, class Src, class Mma, class Prep = NoPrep>
 __device__ inline void ring_stream_pp(const char* __restrict__ ga, size_t stride_a, int chunks_a, const char* __restrict__ gb,
-                                      size_t stride_b, int chunks_b, int nk, char* smem, int wave, int lane, Src&& src, Mma&& mma) {
+                                      size_t stride_b, int chunks_b, int nk, char* smem, int wave, int lane, Src&& src, Mma&& mma,
+                                      Prep&& prep = Prep{}) {
+  constexpr bool HAS_PREP = !std::is_same<std::remove_cv_t<std::remove_reference_t<Prep>>, NoPrep>::value;
   constexpr int ABYTES = AROWS * AROWB, SBYTES = ABYTES + BROWS * BROWB, NH = NW / 2, BH = BROWS / 2;
   constexpr int LPS_ALL = dma_loads_per_wave<AROWS, AROWB, NW>() + dma_loads_per_wave<BROWS, BROWB, NW>();
   constexpr int LPS_LATE = UNEVEN ? dma_loads_per_wave<BH, BROWB, NH>() : LPS_ALL;
@@ -182,7 +189,11 @@ __device__ inline void ring_stream_pp(const char* __restrict__ ga, size_t stride
     barrier_nofence();
     const bool more = ks + NST - 1 < nk;
     if (more && !late) issue(ks + NST - 1);
-    const char* st = smem + (ks % NST) * SBYTES;
+    char* st = smem + (ks % NST) * SBYTES;
+    if constexpr (HAS_PREP) {
+      prep(st + ABYTES, ks);
+      barrier_lds();
+    }
     __builtin_amdgcn_sched_barrier(0);
     mma(st, st + ABYTES, 0, ks);
     __builtin_amdgcn_sched_barrier(0);
@@ -194,17 +205,17 @@ __device__ inline void ring_stream_pp(const char* __restrict__ ga, size_t stride
 }
 
 // One output tile: slab ks of an operand starts at g + ks*adv and has v0 - ks*dv valid rows.
-template <int AROWS, int AROWB, int BROWS, int BROWB, int NST, int NW, bool UNEVEN, class Mma>
+template <int AROWS, int AROWB, int BROWS, int BROWB, int NST, int NW, bool UNEVEN, class Mma, class Prep = NoPrep>
 __device__ inline void ring_pipeline_pp(const char* __restrict__ ga, size_t stride_a, int va0, int dva, size_t adv_a, int chunks_a,
                                         const char* __restrict__ gb, size_t stride_b, int vb0, int dvb, size_t adv_b, int chunks_b,
-                                        int nk, char* smem, int wave, int lane, Mma&& mma) {
+                                        int nk, char* smem, int wave, int lane, Mma&& mma, Prep&& prep = Prep{}) {
   ring_stream_pp<AROWS, AROWB, BROWS, BROWB, NST, NW, UNEVEN>(
       ga, stride_a, chunks_a, gb, stride_b, chunks_b, nk, smem, wave, lane,
       [&](int ks, size_t& off_a, int& va, size_t& off_b, int& vb) {
         off_a = (size_t)ks * adv_a; va = va0 - ks * dva;
         off_b = (size_t)ks * adv_b; vb = vb0 - ks * dvb;
       },
-      [&](const char* sa, const char* sb, int half, int) { mma(sa, sb, half); });
+      [&](const char* sa, const char* sb, int half, int) { mma(sa, sb, half); }, static_cast<Prep&&>(prep));
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -35,6 +35,29 @@ def test_host_philox_matches_published_vectors_and_oracle(b):
     assert b.elmo_philox4x32_10(ctr, key) == [int(x) for x in o.philox4x32_10(ctr, key)]
 
 
+def test_host_dropout_mask_matches_the_oracle(b):
+    """The library's keep mask (same code as the kernels', run on the host) against the oracle's,
+    for thresholds around the byte's top bit and at both ends, on blocks beyond 2^32."""
+    import numpy as np
+    rng = np.random.default_rng(3)
+    seed, step = 0xA5A5A5A55A5A5A5A, (1 << 40) + 9
+    blocks = [0, 1, 12345, (1 << 32) + 7, (1 << 44) - 1] + [int(x) for x in rng.integers(0, 1 << 40, 40)]
+    for T in (0, 1, 2, 63, 127, 128, 129, 200, 254, 255):
+        for blk in blocks:
+            keep = o.dropout_keep(seed, step, np.arange(16 * blk, 16 * blk + 16, dtype=np.uint64), T)
+            want = sum(int(k) << i for i, k in enumerate(keep))
+            assert b.elmo_dropout_keep16(seed, step, blk, T) == want, (T, blk)
+    assert b.elmo_dropout_keep16(seed, step, 5, 0) == 0xFFFF
+
+
+def test_create_rejects_bad_dropout(b):
+    for p in (-0.1, 0.999, 1.0, float("nan")):
+        with pytest.raises(b.ElmoError) as e:
+            b.elmo_head_create(1000, 256, b.ELMO_BF16, 512, flags=0, max_B=8, max_nnz=64, W=None, comp=None, workspace=None,
+                               dropout_p=p)
+        assert e.value.code == -1 and "dropout_p" in str(e.value)
+
+
 def test_logit_buffer_closed_form_reproduces_the_papers_figures(b):
     """Section 4.4: 3M-label head (2,812,281 labels), batch 128, 16-bit logits: 687 MiB unchunked,
     86 MiB with 8 chunks."""

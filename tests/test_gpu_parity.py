@@ -135,14 +135,15 @@ class Case:
     """A head on the device initialised from host bits, plus the host copies the oracle needs."""
 
     def __init__(self, b, L, d, fmt, chunk, flags, B, max_nnz=None, seed=0, w_std=0.02, comp_std=0.0, kahan_rows=0,
-                 weight_decay=0.0):
+                 weight_decay=0.0, dropout_p=0.0):
         rng = np.random.default_rng([seed, L, d])
         self.b, self.L, self.d, self.fmt, self.flags = b, L, d, fmt, flags
         self.W0 = o.quantize(synth.make_w0_f32(rng, L, d, w_std), fmt)
         self.C0 = None
         if flags & o.FLAG_KAHAN:
             self.C0 = o.round_bf16((rng.standard_normal((kahan_rows or L, d)) * comp_std).astype(np.float32))
-        self.head = b.Head(L, d, fmt, chunk, flags, B, max_nnz or 64 * B, kahan_rows=kahan_rows, weight_decay=weight_decay)
+        self.head = b.Head(L, d, fmt, chunk, flags, B, max_nnz or 64 * B, kahan_rows=kahan_rows, weight_decay=weight_decay,
+                           dropout_p=dropout_p)
         self.load(self.W0, self.C0)
 
     def load(self, W, C):
@@ -304,6 +305,52 @@ def test_weight_decay(b, fmt, flags, B):
     assert np.mean(dist <= 1) >= 0.999
     assert_far_misses_are_tiny(Wn, ref["W_new"], dist, fmt, lr)
     assert rel_fro(dX, ref["dX_partial"]) <= 6e-2
+
+
+@pytest.mark.parametrize("fmt,flags,B,d,T", [
+    (o.E4M3, o.FLAG_SR | o.FLAG_KAHAN, 300, 384, 64),
+    (o.E4M3, o.FLAG_SR, 70, 256, 128),
+    (o.E4M3, 0, 600, 256, 230),
+    (o.BF16, o.FLAG_KAHAN, 300, 256, 26),
+    (o.BF16, o.FLAG_SR, 70, 128, 200),
+    (o.BF16, 0, 300, 384, 128),
+])
+def test_classifier_dropout(b, fmt, flags, B, d, T):
+    """Dropout on the weights inside the three products: the library regenerates the oracle's mask
+    from (seed, step, element) in the logits, the input-gradient and the update kernel, for both
+    logits tile sizes, a width with a half column tile, ragged label tails and several chunks.
+    A mask that differed in one kernel, or a missing scale, would miss every bar here: the logits
+    feed the loss and G, the input gradient sums masked weights, and the weight gradient of a
+    dropped element is zero, so without rounding noise and compensation it must not move at all."""
+    L, chunk, lr = 3 * 256 + 77, 512, 0.1
+    case = Case(b, L, d, fmt, chunk, flags, B, w_std=0.05, comp_std=2e-4, seed=23, dropout_p=T / 256)
+    rng = np.random.default_rng(41)
+    X = synth.make_x(rng, B, d)
+    indptr, indices = synth.ZipfLabels(L, 1.0).draw_csr(rng, B, "lognormal5")
+    say(f"[dropout] fmt={fmt} flags={flags} B={B} d={d} T={T}")
+    dX, loss = case.step(X, indptr, indices, lr, 77, 4)
+    ref = o.head_step(case.W0, case.C0, X, indptr, indices, lr, 77, 4, fmt, flags, dropout=T)
+    plain = o.head_step(case.W0, case.C0, X, indptr, indices, lr, 77, 4, fmt, flags)
+    Wn = case.W()
+    dist = np.abs(ordered(Wn, fmt) - ordered(ref["W_new"], fmt))
+    e_dx, e_loss = rel_fro(dX, ref["dX_partial"]), abs(loss - ref["loss"]) / abs(ref["loss"])
+    say(f"   W': exact {np.mean(dist == 0):.5f}, within 1 ulp {np.mean(dist <= 1):.6f};  dX rel-Fro {e_dx:.2e} "
+        f"(no-dropout oracle is {rel_fro(plain['dX_partial'], ref['dX_partial']):.2e} away);  loss rel {e_loss:.2e}")
+    assert rel_fro(plain["dX_partial"], ref["dX_partial"]) > 0.2        # the mask matters at this rate
+    assert np.mean(dist <= 1) >= 0.999
+    assert_far_misses_are_tiny(Wn, ref["W_new"], dist, fmt, lr)
+    assert e_dx <= (6e-2 if fmt == o.E4M3 else 2e-2)
+    assert e_loss <= 2e-3
+    if flags == 0:
+        keep = o.dropout_keep(77, 4, np.arange(L * d, dtype=np.int64).reshape(L, d), T)
+        assert np.array_equal(Wn[~keep], case.W0[~keep])
+        assert np.any(Wn[keep] != case.W0[keep])
+    # the mask is a function of the element, not of the chunking
+    other = Case(b, L, d, fmt, 256, flags, B, w_std=0.05, comp_std=2e-4, seed=23, dropout_p=T / 256)
+    other.step(X, indptr, indices, lr, 77, 4)
+    assert np.array_equal(other.W(), Wn)
+    with pytest.raises(b.ElmoError):
+        case.head.step(dev(X), dev(indptr), dev(indices), lr, 77, 1 << 63)
 
 
 def test_many_batch_tiles(b):
