@@ -25,6 +25,7 @@ What is computed follows the paper (ELMO, arxiv 2510.11168):
 * simulated (exponent, mantissa) formats                     -- Section 4.3 "8-Bit Training"
 * dropout on the classifier weights inside the products     -- Appendix "Low-Memory Dropout for
                                                                 Classifier"
+* AdamW with Kahan-compensated BF16 parameters (encoder)     -- Section 4.1
 
 Label chunking (Section 4.2) does not appear here: every label's logit, gradient row and weight
 update depend only on that label's own weight row, so the chunked and unchunked results are the
@@ -57,6 +58,9 @@ Readings taken where the paper is silent (each is repeated at the function that 
 * Weight decay (the table only gives a value): the L2 term of plain SGD, g + wd*w in FP32, each
   operation rounded; absent (not merely zero) when wd = 0.
 * Head labels are a prefix of the label ids (labels numbered by falling frequency).
+* Kahan-AdamW: the paper defers to a library; taken here is textbook AdamW (decoupled decay,
+  bias correction) in FP32 with every operation rounded once, the Kahan recurrence on the
+  parameter, moments in BF16 (round to nearest) or FP32 (kahan_adamw).
 * Classifier dropout: one keep bit per weight element and step (shared by the batch), from a
   second Philox stream; dropped with probability T/256, kept weights scaled by 256/(256-T); the
   masked weights serve logits and input gradient and mask the weight gradient (dropout_keep,
@@ -537,3 +541,63 @@ def kahan_sum_stream(s_bits, c_bits, addends, fmt):
         c_bits = round_bf16(((s_new - s).astype(f32) - y).astype(f32))
         s_bits = s_new_bits
     return s_bits, c_bits
+
+
+def kahan_adamw(p_bits, c_bits, m, v, g_bits, lr, beta1, beta2, eps, weight_decay, t, wide=False):
+    """One AdamW step with Kahan-compensated BF16 parameters -- what Section 4.1 uses for the
+    encoder ("Kahan summation for the encoder's parameters"; the experimental set-up names a fused
+    Kahan-AdamW).  AdamW is Loshchilov & Hutter's: decoupled weight decay, bias-corrected moments.
+
+    p_bits, c_bits, g_bits: uint16 BF16 patterns (parameter, compensation, gradient).  m, v: the
+    moments, uint16 BF16 patterns or float32 arrays (kept in the type they arrive in).  t >= 1 is
+    the step count of the bias correction.  Reading (the paper defers to a library): FP32
+    arithmetic, every operation rounded once, in this order
+        m' = fl(fl(b1 m) + fl(o1 g));              v' = fl(fl(b2 v) + fl(fl(o2 g) g))
+        mh = fl(m' / bc1);  vh = fl(v' / bc2)
+    with the scalars b_i = fl32(beta_i), o_i = fl32(1 - beta_i), bc_i = fl32(1 - beta_i^t) formed in
+    FP64 from the FP64 betas and rounded once,
+    then
+        r  = fl(mh / fl(fl(sqrt(vh)) + eps));      r = fl(r + fl(wd p)) if wd != 0
+        u  = fl(lr r)
+        y  = fl(-u - c);  s = fl(p + y);  p' = RNE_BF16(s);  c' = RNE_BF16(fl(fl(p' - p) - y))
+    (the last line is the Kahan recurrence of Section 3 with the update -u as the addend), and the
+    moments are stored round-to-nearest-even when they are BF16.
+
+    wide=True is the same recipe in FP64 with nothing rounded and p, c, m, v, g given as float64
+    values (c is then always 0): the textbook AdamW the tests compare with torch's.
+    Returns (p, c, m, v) in the types they came in.
+    """
+    if wide:
+        p, c, m, v, g = (np.asarray(a, dtype=np.float64) for a in (p_bits, c_bits, m, v, g_bits))
+        m1 = beta1 * m + (1.0 - beta1) * g
+        v1 = beta2 * v + (1.0 - beta2) * g * g
+        r = (m1 / (1.0 - beta1 ** t)) / (np.sqrt(v1 / (1.0 - beta2 ** t)) + eps)
+        r = r + weight_decay * p
+        return p - lr * r - c, np.zeros_like(p), m1, v1
+    f32 = np.float32
+    p = decode_bf16(p_bits).astype(f32)
+    c = decode_bf16(c_bits).astype(f32)
+    g = decode_bf16(g_bits).astype(f32)
+    m_is_bf16 = np.asarray(m).dtype == np.uint16
+    v_is_bf16 = np.asarray(v).dtype == np.uint16
+    m0 = decode_bf16(m).astype(f32) if m_is_bf16 else np.asarray(m, dtype=f32)
+    v0 = decode_bf16(v).astype(f32) if v_is_bf16 else np.asarray(v, dtype=f32)
+    b1, b2 = f32(beta1), f32(beta2)
+    ob1, ob2 = f32(1.0 - beta1), f32(1.0 - beta2)
+    bc1, bc2 = f32(1.0 - beta1 ** t), f32(1.0 - beta2 ** t)
+    m1 = ((b1 * m0).astype(f32) + (ob1 * g).astype(f32)).astype(f32)
+    v1 = ((b2 * v0).astype(f32) + ((ob2 * g).astype(f32) * g).astype(f32)).astype(f32)
+    mh = (m1 / bc1).astype(f32)
+    vh = (v1 / bc2).astype(f32)
+    r = (mh / (np.sqrt(vh).astype(f32) + f32(eps)).astype(f32)).astype(f32)
+    if weight_decay != 0.0:
+        r = (r + (f32(weight_decay) * p).astype(f32)).astype(f32)
+    u = (f32(lr) * r).astype(f32)
+    y = ((-u) - c).astype(f32)
+    s_ = (p + y).astype(f32)
+    p_new_bits = round_bf16(s_)
+    p_new = decode_bf16(p_new_bits).astype(f32)
+    c_new_bits = round_bf16(((p_new - p).astype(f32) - y).astype(f32))
+    m_out = round_bf16(m1) if m_is_bf16 else m1
+    v_out = round_bf16(v1) if v_is_bf16 else v1
+    return p_new_bits, c_new_bits, m_out, v_out
