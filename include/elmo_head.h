@@ -33,7 +33,7 @@ typedef struct elmo_head elmo_head_t; /* opaque, host-side */
 
 /* Storage format of the classifier weights (Section 4.1 pure 16-bit; Section 4.3 8-bit).
  * ELMO_FP8_E4M3 is the OCP "FN" flavour: bias 7, largest finite value 448, no infinities. */
-enum { ELMO_BF16 = 0, ELMO_FP8_E4M3 = 1 };
+enum { ELMO_BF16 = 0, ELMO_FP8_E4M3 = 1, ELMO_FP32 = 2 /* optimiser moments of elmo_kahan_adamw only */ };
 
 /* ELMO_SR: the update rounds with stochastic rounding (Eq. 1), otherwise to nearest even.
  * ELMO_KAHAN: a BF16 compensation buffer carries the rounding error of every update into the
@@ -156,6 +156,22 @@ int elmo_quantize(const float* src, int64_t n, int dtype, int mode, uint64_t see
  * src, dst: device FP32, n entries each (may be the same buffer). */
 int elmo_quantize_em(const float* src, int64_t n, int exp_bits, int man_bits, int mode, uint64_t seed,
                      uint64_t step, uint64_t first_elem, float* dst, void* hip_stream);
+
+/* AdamW with Kahan-compensated BF16 parameters, in place (Section 4.1: the encoder's parameters
+ * are kept in BF16 and their optimiser step uses Kahan summation so that updates below half a
+ * grid spacing are not cancelled).  Textbook AdamW (decoupled weight decay, bias-corrected
+ * moments) in FP32 arithmetic, every operation rounded once:
+ *   m' = b1 m + o1 g;   v' = b2 v + (o2 g) g;   r = (m'/bc1) / (sqrt(v'/bc2) + eps);
+ *   r += weight_decay * p (skipped when 0);   u = lr r;
+ *   y = -u - c;   s = p + y;   p' = RNE_BF16(s);   c' = RNE_BF16((p' - p) - y)
+ * with b_i = (float)beta_i, o_i = (float)(1 - beta_i), bc_i = (float)(1 - beta_i^t) formed in double.
+ * param, comp, grad: device BF16 [n] (comp starts at zero); m, v: device moments [n] in
+ * state_dtype = ELMO_BF16 (stored round-to-nearest-even) or ELMO_FP32, starting at zero.
+ * t >= 1 counts the steps.  All buffers 16-byte aligned, caller-owned, updated in place (grad is
+ * only read).  n = 0 is a no-op.  Errors: -1 bad argument, -2 unsupported state_dtype, -3 HIP. */
+int elmo_kahan_adamw(void* param, void* comp, void* m, void* v, const void* grad, int64_t n, int state_dtype,
+                     float lr, double beta1, double beta2, float eps, float weight_decay, int64_t t,
+                     void* hip_stream);
 
 /* Host-side view of the dropout mask of elmo_head_opts.dropout_p: bit i of the result is 1 iff
  * weight element 16 * block + i is kept at (seed, step) for the threshold T = threshold (0..255). */

@@ -15,6 +15,7 @@ from .build import LIB_PATH
 
 ELMO_BF16 = 0
 ELMO_FP8_E4M3 = 1
+ELMO_FP32 = 2
 ELMO_SR = 1
 ELMO_KAHAN = 2
 ELMO_VALIDATE = 4
@@ -75,13 +76,16 @@ _lib.elmo_quantize.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_uint
                                C.c_void_p, C.c_void_p]
 _lib.elmo_philox4x32_10.restype = None
 _lib.elmo_philox4x32_10.argtypes = [C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+_lib.elmo_kahan_adamw.restype = C.c_int
+_lib.elmo_kahan_adamw.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_float,
+                                  C.c_double, C.c_double, C.c_float, C.c_float, C.c_int64, C.c_void_p]
 _lib.elmo_dropout_keep16.restype = C.c_uint32
 _lib.elmo_dropout_keep16.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint32]
 
 EXPORTS = ("elmo_last_error", "elmo_logit_buffer_bytes", "elmo_head_sizes", "elmo_head_create",
            "elmo_head_step", "elmo_head_topk", "elmo_head_destroy", "elmo_quantize", "elmo_philox4x32_10",
            "elmo_head_profile", "elmo_head_profile_read", "elmo_precision_hits", "elmo_quantize_em",
-           "elmo_dropout_keep16")
+           "elmo_dropout_keep16", "elmo_kahan_adamw")
 
 
 def _check(rc: int) -> None:
@@ -169,6 +173,11 @@ def elmo_head_profile_read(h):
 
 def elmo_quantize(src, n, dtype, mode, seed, step, first_elem, dst, stream=None) -> None:
     _check(_lib.elmo_quantize(_ptr(src), n, dtype, mode, seed, step, first_elem, _ptr(dst), _stream(stream)))
+
+
+def elmo_kahan_adamw(param, comp, m, v, grad, n, state_dtype, lr, beta1, beta2, eps, weight_decay, t, stream=None) -> None:
+    _check(_lib.elmo_kahan_adamw(_ptr(param), _ptr(comp), _ptr(m), _ptr(v), _ptr(grad), n, state_dtype, lr, beta1, beta2, eps,
+                                 weight_decay, t, _stream(stream)))
 
 
 def elmo_dropout_keep16(seed, step, block, threshold) -> int:

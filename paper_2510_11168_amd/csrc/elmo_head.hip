@@ -576,3 +576,28 @@ extern "C" int elmo_quantize_em(const float* src, int64_t n, int exp_bits, int m
   else elmo::k_quantize_em<false><<<grid, elmo::kThreads, 0, st>>>(src, n, exp_bits, man_bits, seed, step, first_elem, dst);
   return check_launch("k_quantize_em");
 }
+
+extern "C" int elmo_kahan_adamw(void* param, void* comp, void* m, void* v, const void* grad, int64_t n, int state_dtype, float lr,
+                                double beta1, double beta2, float eps, float weight_decay, int64_t t, void* hip_stream) {
+  if (n < 0 || (n > 0 && (!param || !comp || !m || !v || !grad))) return fail(-1, "bad buffers / n");
+  if (state_dtype != ELMO_BF16 && state_dtype != ELMO_FP32) return fail(-2, "state_dtype must be ELMO_BF16 or ELMO_FP32 (got %d)", state_dtype);
+  if (!(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0)) return fail(-1, "betas must be in [0, 1)");
+  if (t < 1) return fail(-1, "the step count t starts at 1 (got %lld)", (long long)t);
+  if (!(eps >= 0.0f) || !(weight_decay >= 0.0f)) return fail(-1, "eps and weight_decay must be >= 0");
+  if (((uintptr_t)param | (uintptr_t)comp | (uintptr_t)m | (uintptr_t)v | (uintptr_t)grad) & 15)
+    return fail(-1, "all buffers must be 16-byte aligned");
+  if (n == 0) return 0;
+  elmo::AdamArgs a;
+  a.lr = lr;
+  a.b1 = (float)beta1; a.o1 = (float)(1.0 - beta1); a.bc1 = (float)(1.0 - std::pow(beta1, (double)t));
+  a.b2 = (float)beta2; a.o2 = (float)(1.0 - beta2); a.bc2 = (float)(1.0 - std::pow(beta2, (double)t));
+  a.eps = eps; a.wd = weight_decay;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int64_t work = std::max<int64_t>(n >> 3, 8);
+  const int grid = (int)std::min<int64_t>((work + elmo::kThreads - 1) / elmo::kThreads, 256 * 16);
+  if (state_dtype == ELMO_BF16)
+    elmo::k_kahan_adamw<true><<<grid, elmo::kThreads, 0, st>>>((uint16_t*)param, (uint16_t*)comp, m, v, (const uint16_t*)grad, n, a);
+  else
+    elmo::k_kahan_adamw<false><<<grid, elmo::kThreads, 0, st>>>((uint16_t*)param, (uint16_t*)comp, m, v, (const uint16_t*)grad, n, a);
+  return check_launch("k_kahan_adamw");
+}

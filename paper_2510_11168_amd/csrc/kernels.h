@@ -857,4 +857,98 @@ __global__ void __launch_bounds__(kThreads) k_quantize_em(const float* __restric
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// AdamW with Kahan-compensated BF16 parameters (Section 4.1: Kahan summation for the encoder's
+// parameters).  Elementwise, 8 elements per thread and pass; FP32 arithmetic, every operation
+// rounded once; the moments are BF16 (stored round-to-nearest-even) or FP32.
+//   m' = b1 m + o1 g;  v' = b2 v + (o2 g) g;  r = (m'/bc1) / (sqrt(v'/bc2) + eps) [+ wd p];  u = lr r
+//   y = -u - c;  s = p + y;  p' = RNE_BF16(s);  c' = RNE_BF16((p' - p) - y)
+// ---------------------------------------------------------------------------------------------
+struct AdamArgs { float lr, b1, o1, b2, o2, bc1, bc2, eps, wd; };
+
+__device__ inline void adamw_element(uint32_t& pb, uint32_t& cb, float& m, float& v, uint32_t gb, const AdamArgs& a) {
+  const float p = bf16_decode(pb), c = bf16_decode(cb), g = bf16_decode(gb);
+  m = __fadd_rn(__fmul_rn(a.b1, m), __fmul_rn(a.o1, g));
+  v = __fadd_rn(__fmul_rn(a.b2, v), __fmul_rn(__fmul_rn(a.o2, g), g));
+  const float mh = __fdiv_rn(m, a.bc1), vh = __fdiv_rn(v, a.bc2);
+  float r = __fdiv_rn(mh, __fadd_rn(sqrtf(vh), a.eps));      // sqrtf and '/' are correctly rounded (the __fsqrt_rn intrinsic is not)
+  if (a.wd != 0.0f) r = __fadd_rn(r, __fmul_rn(a.wd, p));
+  const float u = __fmul_rn(a.lr, r);
+  const float y = __fsub_rn(-u, c);
+  const uint32_t q = bf16_rne(__fadd_rn(p, y));
+  cb = bf16_rne(__fsub_rn(__fsub_rn(bf16_decode(q), p), y));
+  pb = q;
+}
+
+template <bool STATE_BF16>
+__global__ void __launch_bounds__(kThreads) k_kahan_adamw(uint16_t* __restrict__ P, uint16_t* __restrict__ C, void* __restrict__ Mv,
+                                                          void* __restrict__ Vv, const uint16_t* __restrict__ G, int64_t n,
+                                                          AdamArgs a) {
+  const int64_t groups = n >> 3;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < groups; i += (int64_t)gridDim.x * kThreads) {
+    u32x4 p4 = reinterpret_cast<const u32x4*>(P)[i], c4 = reinterpret_cast<const u32x4*>(C)[i];
+    const u32x4 g4 = reinterpret_cast<const u32x4*>(G)[i];
+    float m[8], v[8];
+    if (STATE_BF16) {
+      const u32x4 m4 = reinterpret_cast<const u32x4*>(Mv)[i], v4 = reinterpret_cast<const u32x4*>(Vv)[i];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        m[e] = bf16_decode((m4[e >> 1] >> (16 * (e & 1))) & 0xFFFFu);
+        v[e] = bf16_decode((v4[e >> 1] >> (16 * (e & 1))) & 0xFFFFu);
+      }
+    } else {
+      const f32x4 ma = reinterpret_cast<const f32x4*>(Mv)[2 * i], mb = reinterpret_cast<const f32x4*>(Mv)[2 * i + 1];
+      const f32x4 va = reinterpret_cast<const f32x4*>(Vv)[2 * i], vb = reinterpret_cast<const f32x4*>(Vv)[2 * i + 1];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { m[e] = ma[e]; m[4 + e] = mb[e]; v[e] = va[e]; v[4 + e] = vb[e]; }
+    }
+    uint32_t pn[8], cn[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      pn[e] = (p4[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+      cn[e] = (c4[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+      adamw_element(pn[e], cn[e], m[e], v[e], (g4[e >> 1] >> (16 * (e & 1))) & 0xFFFFu, a);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      p4[q] = pn[2 * q] | (pn[2 * q + 1] << 16);
+      c4[q] = cn[2 * q] | (cn[2 * q + 1] << 16);
+    }
+    reinterpret_cast<u32x4*>(P)[i] = p4;
+    reinterpret_cast<u32x4*>(C)[i] = c4;
+    if (STATE_BF16) {
+      u32x4 m4, v4;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        m4[q] = bf16_rne(m[2 * q]) | (bf16_rne(m[2 * q + 1]) << 16);
+        v4[q] = bf16_rne(v[2 * q]) | (bf16_rne(v[2 * q + 1]) << 16);
+      }
+      reinterpret_cast<u32x4*>(Mv)[i] = m4;
+      reinterpret_cast<u32x4*>(Vv)[i] = v4;
+    } else {
+      reinterpret_cast<f32x4*>(Mv)[2 * i] = f32x4{m[0], m[1], m[2], m[3]};
+      reinterpret_cast<f32x4*>(Mv)[2 * i + 1] = f32x4{m[4], m[5], m[6], m[7]};
+      reinterpret_cast<f32x4*>(Vv)[2 * i] = f32x4{v[0], v[1], v[2], v[3]};
+      reinterpret_cast<f32x4*>(Vv)[2 * i + 1] = f32x4{v[4], v[5], v[6], v[7]};
+    }
+  }
+  // the last n % 8 elements, one thread each
+  const int64_t tail = (groups << 3) + (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (tail < n) {
+    uint32_t pb = P[tail], cb = C[tail];
+    float m = STATE_BF16 ? bf16_decode(reinterpret_cast<uint16_t*>(Mv)[tail]) : reinterpret_cast<float*>(Mv)[tail];
+    float v = STATE_BF16 ? bf16_decode(reinterpret_cast<uint16_t*>(Vv)[tail]) : reinterpret_cast<float*>(Vv)[tail];
+    adamw_element(pb, cb, m, v, G[tail], a);
+    P[tail] = (uint16_t)pb;
+    C[tail] = (uint16_t)cb;
+    if (STATE_BF16) {
+      reinterpret_cast<uint16_t*>(Mv)[tail] = (uint16_t)bf16_rne(m);
+      reinterpret_cast<uint16_t*>(Vv)[tail] = (uint16_t)bf16_rne(v);
+    } else {
+      reinterpret_cast<float*>(Mv)[tail] = m;
+      reinterpret_cast<float*>(Vv)[tail] = v;
+    }
+  }
+}
+
 }  // namespace elmo

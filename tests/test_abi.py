@@ -50,6 +50,19 @@ def test_host_dropout_mask_matches_the_oracle(b):
     assert b.elmo_dropout_keep16(seed, step, 5, 0) == 0xFFFF
 
 
+def test_kahan_adamw_rejects_bad_arguments(b):
+    for kw in (dict(state_dtype=1), dict(beta1=1.0), dict(beta2=-0.1), dict(t=0), dict(eps=-1.0), dict(weight_decay=float("nan"))):
+        a = dict(state_dtype=b.ELMO_BF16, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, t=1)
+        a.update(kw)
+        with pytest.raises(b.ElmoError):
+            b._check(b._lib.elmo_kahan_adamw(16, 16, 16, 16, 16, 8, a["state_dtype"], a["lr"], a["beta1"], a["beta2"], a["eps"],
+                                             a["weight_decay"], a["t"], None))
+    with pytest.raises(b.ElmoError):      # NULL buffers with n > 0, misaligned buffers
+        b.elmo_kahan_adamw(None, None, None, None, None, 8, b.ELMO_BF16, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1)
+    with pytest.raises(b.ElmoError):
+        b._check(b._lib.elmo_kahan_adamw(16, 16, 24, 16, 16, 8, b.ELMO_BF16, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, None))
+
+
 def test_create_rejects_bad_dropout(b):
     for p in (-0.1, 0.999, 1.0, float("nan")):
         with pytest.raises(b.ElmoError) as e:

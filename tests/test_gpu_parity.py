@@ -130,6 +130,40 @@ def test_quantize_empty_is_a_no_op(b):
     b.elmo_quantize(None, 0, o.BF16, 0, 0, 0, 0, None)
 
 
+@pytest.mark.parametrize("state_bf16", [True, False])
+@pytest.mark.parametrize("wd", [0.0, 0.01])
+def test_kahan_adamw_bit_exact(b, state_bf16, wd):
+    """Three consecutive AdamW steps with Kahan-compensated BF16 parameters on 1 M + 5 elements
+    (the vector body and the scalar tail), values over many binades, BF16 and FP32 moments:
+    parameters, compensation and moments bit for bit against the oracle after every step."""
+    rng = np.random.default_rng(13)
+    n = (1 << 20) + 5
+    lr, b1, b2, eps = 2e-3, 0.9, 0.999, 1e-8
+    pb = o.round_bf16((rng.standard_normal(n) * np.exp(rng.uniform(-6, 2, n))).astype(np.float32))
+    cb = np.zeros(n, np.uint16)
+    m = np.zeros(n, np.uint16 if state_bf16 else np.float32)
+    v = np.zeros(n, np.uint16 if state_bf16 else np.float32)
+    P, C = dev(pb), dev(cb)
+    M, V = dev(m), dev(v)
+    sd = b.ELMO_BF16 if state_bf16 else b.ELMO_FP32
+    say(f"[kahan-adamw] state_bf16={state_bf16} wd={wd} n={n}")
+    for t in range(1, 4):
+        gb = o.round_bf16((rng.standard_normal(n) * np.exp(rng.uniform(-8, 1, n))).astype(np.float32))
+        if t == 2:
+            gb[:1000] = 0                      # zero gradients: the moments decay, sqrt(v) + eps stays positive
+        b.elmo_kahan_adamw(P, C, M, V, dev(gb), n, sd, lr, b1, b2, eps, wd, t)
+        torch.cuda.synchronize()
+        pb, cb, m, v = o.kahan_adamw(pb, cb, m, v, gb, lr, b1, b2, eps, wd, t)
+        got_m = host_u16(M) if state_bf16 else M.cpu().numpy()
+        got_v = host_u16(V) if state_bf16 else V.cpu().numpy()
+        for name, got, want in (("p", host_u16(P), pb), ("c", host_u16(C), cb), ("m", got_m, m), ("v", got_v, v)):
+            w32 = want.view(np.uint32) if want.dtype == np.float32 else want
+            g32 = got.view(np.uint32) if got.dtype == np.float32 else got
+            bad = np.nonzero(g32 != w32)[0]
+            assert bad.size == 0, f"step {t} {name}: {bad.size} mismatches, first at {bad[0]}: got {got[bad[0]]!r} want {want[bad[0]]!r}"
+    b.elmo_kahan_adamw(None, None, None, None, None, 0, sd, lr, b1, b2, eps, wd, 1)      # n = 0 is a no-op
+
+
 # --------------------------------------------------------------------------------- head step
 class Case:
     """A head on the device initialised from host bits, plus the host copies the oracle needs."""
