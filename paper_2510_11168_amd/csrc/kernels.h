@@ -268,7 +268,7 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int WGN = TB == 256 ? 2 : 4, FN = TB / 32 / WGN;   // waves along the labels, 32-label blocks per wave
   constexpr int MW = TB / 32, SEGS = TB / 8;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave / WGN, wn = wave % WGN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave / WGN, wn = wave % WGN;
   const int tiles_b = (Bp + TB - 1) / TB;
   const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
   const int lt = wg / tiles_b, bt = wg % tiles_b;
@@ -386,7 +386,7 @@ k_dx(const char* __restrict__ Gt, const char* __restrict__ Wc, float* __restrict
      int Bp256, int S, uint64_t seed, uint64_t step, uint64_t elem0, DropArgs dr) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int ESZ = FP8 ? 1 : 2, WROWB = 256 * ESZ;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave >> 1, wn = wave & 1;
   const int tiles_b = Bp256 >> 8, tiles_j = (d + 255) >> 8;
   const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
   const int jt = wg % tiles_j, bt = (wg / tiles_j) % tiles_b, s = wg / (tiles_j * tiles_b);
@@ -541,7 +541,7 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int ESZ = FMT == FMT_E4M3 ? 1 : 2;
   constexpr int WQ = FMT == FMT_E4M3 ? 1 : 2;       // 16-byte loads per 16 weights
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave >> 1, wn = wave & 1;
   const int tiles_j = (d + 255) >> 8;
   const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
   const int lt = wg / tiles_j, jt = wg % tiles_j;
@@ -686,7 +686,7 @@ __device__ __forceinline__ void dx_update_body(const char* __restrict__ Gt, cons
   constexpr int WROWB = 256 * ESZ;
   constexpr int WBYTES = 32 * WROWB, GBYTES = 32 * 256, SBYTES = dxu_stage_bytes<FMT, KAHAN>();
   constexpr int LPS = WROWB / 256 + 1 + (KAHAN ? 2 : 0);     // asynchronous loads per wave and tile
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int C = d >> 8;
   const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
   const int g = wg / C, c = wg % C;

@@ -76,8 +76,10 @@ __device__ inline void dma_tile(const char* __restrict__ g, size_t stride, int r
     const int r = rbase + lane / CPR;
     const int c = min((lane % CPR) ^ swz_key<ROWB>(r), chunks_valid - 1);   // chunks past a short row re-read its last one
     const int rc = min(r, rows_valid - 1);
-    __builtin_amdgcn_global_load_lds(ELMO_GLOBAL_PTR(g + (size_t)rc * stride + c * 16), ELMO_LDS_PTR(void, lds_tile + rbase * ROWB),
-                                     16, 0, 0);
+    // 32-bit lane offset on top of the (wave-uniform) slab pointer: the load then takes the
+    // scalar-base + vector-offset form and needs no 64-bit address arithmetic per lane
+    const uint32_t off = __umul24((uint32_t)rc, (uint32_t)stride) + (uint32_t)(c * 16);
+    __builtin_amdgcn_global_load_lds(ELMO_GLOBAL_PTR(g + off), ELMO_LDS_PTR(void, lds_tile + rbase * ROWB), 16, 0, 0);
   }
 }
 template <int ROWS, int ROWB, int NW> constexpr int dma_loads_per_wave() { return ROWS * ROWB / 1024 / NW; }

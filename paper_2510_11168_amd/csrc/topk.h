@@ -61,7 +61,7 @@ k_topk_chunk(const char* __restrict__ Xa, int a_rows, const char* __restrict__ W
   float* lsc = reinterpret_cast<float*>(smem + kTopkStage);
   int* lid = reinterpret_cast<int*>(smem + kTopkStage + kTopkRows * kTopkLP * 4);
   uint32_t* hit = reinterpret_cast<uint32_t*>(smem + kTopkStage + 2 * kTopkRows * kTopkLP * 4);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave >> 1, wn = wave & 1;
   const int seg = blockIdx.x % P, bt = blockIdx.x / P;
   const int b0 = bt * kTopkRows;
   const int tiles_l = (int)((L + 127) >> 7);
@@ -246,7 +246,7 @@ k_topk_filter(const char* __restrict__ Xa, int a_rows, const char* __restrict__ 
               const float* __restrict__ tau, int* __restrict__ cnt, int* __restrict__ ovf, float* __restrict__ cand_sc,
               int* __restrict__ cand_id) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave >> 1, wn = wave & 1;
   const int tiles_b = (Bp + 255) >> 8;
   const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
   const int lt = wg / tiles_b, bt = wg % tiles_b;
