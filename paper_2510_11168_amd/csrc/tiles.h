@@ -80,6 +80,10 @@ __device__ inline void dma_tile(const char* __restrict__ g, size_t stride, int r
     // scalar-base + vector-offset form and needs no 64-bit address arithmetic per lane
     const uint32_t off = __umul24((uint32_t)rc, (uint32_t)stride) + (uint32_t)(c * 16);
     __builtin_amdgcn_global_load_lds(ELMO_GLOBAL_PTR(g + off), ELMO_LDS_PTR(void, lds_tile + rbase * ROWB), 16, 0, 0);
+#if defined(ELMO_DMA_GAP)
+#pragma unroll
+    for (int w_ = 0; w_ < ELMO_DMA_GAP; ++w_) asm volatile("s_nop 15");
+#endif
   }
 }
 template <int ROWS, int ROWB, int NW> constexpr int dma_loads_per_wave() { return ROWS * ROWB / 1024 / NW; }
