@@ -274,43 +274,45 @@ void launch_logits(hipStream_t st, int tb, int grid, const char* Xa, int a_rows,
 template <int FMT>
 void launch_update(hipStream_t st, int grid, bool sr, bool kahan, const char* Gt, const char* XT, char* Wc, uint16_t* Cc,
                    int n, int d, int Bp, float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0, elmo::DropArgs dr) {
-#define ELMO_UPD(SR_, KA_)                                                                                                      \
-  do {                                                                                                                          \
-    if (dr.thresh)                                                                                                              \
-      elmo::k_update<FMT, SR_, KA_, true><<<grid, elmo::kGemmThreads, elmo::kUpdateSmem, st>>>(Gt, XT, Wc, Cc, n, d, Bp, lr, wd, \
-                                                                                               seed, step, elem0, dr);         \
-    else                                                                                                                        \
-      elmo::k_update<FMT, SR_, KA_, false><<<grid, elmo::kGemmThreads, elmo::kUpdateSmem, st>>>(Gt, XT, Wc, Cc, n, d, Bp, lr, wd, \
-                                                                                                seed, step, elem0, dr);        \
+#define ELMO_UPD2(SR_, KA_, DR_, WD_) \
+  elmo::k_update<FMT, SR_, KA_, DR_, WD_><<<grid, elmo::kGemmThreads, elmo::kUpdateSmem, st>>>(Gt, XT, Wc, Cc, n, d, Bp, lr, wd, seed, step, elem0, dr)
+#define ELMO_UPD(SR_, KA_)                                               \
+  do {                                                                   \
+    if (dr.thresh) { if (wd != 0.0f) ELMO_UPD2(SR_, KA_, true, true); else ELMO_UPD2(SR_, KA_, true, false); }   \
+    else { if (wd != 0.0f) ELMO_UPD2(SR_, KA_, false, true); else ELMO_UPD2(SR_, KA_, false, false); }           \
   } while (0)
   if (sr && kahan) ELMO_UPD(true, true);
   else if (sr) ELMO_UPD(true, false);
   else if (kahan) ELMO_UPD(false, true);
   else ELMO_UPD(false, false);
+#undef ELMO_UPD2
 #undef ELMO_UPD
 }
 
 // Small-batch fused input gradient + update.  Returns the launch's dynamic LDS size through the
 // template so that the attribute call and the launch agree.
-template <int FMT, bool SR, bool KAHAN, bool DX>
+template <int FMT, bool SR, bool KAHAN, bool DX, bool WD>
 int launch_dx_update_one(hipStream_t st, int grid, const char* Gt, const char* XT, char* Wc, uint16_t* Cc, float* dXacc, int n,
                          int d, int Bp, float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0, int tpg) {
   static bool attr_done = false;
   constexpr int smem = elmo::dxu_smem_bytes<FMT, KAHAN>();
   if (!attr_done) {
-    ELMO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&elmo::k_dx_update<FMT, SR, KAHAN, DX>),
+    ELMO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&elmo::k_dx_update<FMT, SR, KAHAN, DX, WD>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, smem));
     attr_done = true;
   }
-  elmo::k_dx_update<FMT, SR, KAHAN, DX><<<grid, elmo::kGemmThreads, smem, st>>>(Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, wd, seed,
+  elmo::k_dx_update<FMT, SR, KAHAN, DX, WD><<<grid, elmo::kGemmThreads, smem, st>>>(Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, wd, seed,
                                                                                step, elem0, tpg);
   return 0;
 }
 template <int FMT>
 int launch_dx_update(hipStream_t st, int grid, bool sr, bool kahan, bool dx, const char* Gt, const char* XT, char* Wc, uint16_t* Cc,
                      float* dXacc, int n, int d, int Bp, float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0, int tpg) {
-#define ELMO_DXU(SR_, KA_, DX_) \
-  return launch_dx_update_one<FMT, SR_, KA_, DX_>(st, grid, Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, wd, seed, step, elem0, tpg)
+#define ELMO_DXU(SR_, KA_, DX_)                                                                                                     \
+  do {                                                                                                                               \
+    if (wd != 0.0f) return launch_dx_update_one<FMT, SR_, KA_, DX_, true>(st, grid, Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, wd, seed, step, elem0, tpg); \
+    return launch_dx_update_one<FMT, SR_, KA_, DX_, false>(st, grid, Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, wd, seed, step, elem0, tpg);              \
+  } while (0)
   if (sr && kahan && dx) ELMO_DXU(true, true, true);
   if (sr && kahan) ELMO_DXU(true, true, false);
   if (sr && dx) ELMO_DXU(true, false, true);
@@ -335,8 +337,9 @@ int raise_lds_limits() {
   ELMO_ATTR_LOGITS(false, true);
   ELMO_ATTR_LOGITS(false, false);
 #undef ELMO_ATTR_LOGITS
-#define ELMO_ATTR_UPDATE(F, SR_, KA_) \
-  ELMO_ATTR((elmo::k_update<F, SR_, KA_, false>), elmo::kUpdateSmem); ELMO_ATTR((elmo::k_update<F, SR_, KA_, true>), elmo::kUpdateSmem)
+#define ELMO_ATTR_UPDATE(F, SR_, KA_)                                                                                                        \
+  ELMO_ATTR((elmo::k_update<F, SR_, KA_, false, false>), elmo::kUpdateSmem); ELMO_ATTR((elmo::k_update<F, SR_, KA_, true, false>), elmo::kUpdateSmem); \
+  ELMO_ATTR((elmo::k_update<F, SR_, KA_, false, true>), elmo::kUpdateSmem); ELMO_ATTR((elmo::k_update<F, SR_, KA_, true, true>), elmo::kUpdateSmem)
   ELMO_ATTR_UPDATE(elmo::FMT_BF16, true, true);
   ELMO_ATTR_UPDATE(elmo::FMT_BF16, true, false);
   ELMO_ATTR_UPDATE(elmo::FMT_BF16, false, true);

@@ -494,27 +494,33 @@ constexpr int kUpdateSmem = kUpdateEpiBytes > kWideRingBytes ? kUpdateEpiBytes :
 
 // Sixteen consecutive elements of one weight row: storage bits in, storage bits out.
 // E4M3: w[0..3] hold 4 codes each; BF16: w[0..7] hold 2 patterns each.  c[0..7]: BF16 compensation.
-template <int FMT, bool SR, bool KAHAN>
-__device__ inline void update16(uint32_t (&w)[8], uint32_t (&c)[8], const float (&g)[16], float lr, float wd, const U4 (&rb)[2]) {
+// WD = false ignores wd (the two extra operations of the decay are not even selected away).
+template <int FMT, bool SR, bool KAHAN, bool WD>
+__device__ inline void update16_wd(uint32_t (&w)[8], uint32_t (&c)[8], const float (&g)[16], float lr, float wd_, const U4 (&rb)[2]) {
+  const float wd = WD ? wd_ : 0.0f;
   const uint32_t rw[8] = {rb[0].x, rb[0].y, rb[0].z, rb[0].w, rb[1].x, rb[1].y, rb[1].z, rb[1].w};
   if (FMT == FMT_E4M3) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
+      // four codes at a time: the packed conversion decodes two E4M3 bytes per instruction (exact)
+      const f32x2 wlo = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(w[q], 1.0f, false);
+      const f32x2 whi = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(w[q], 1.0f, true);
+      const float wv[4] = {wlo[0], wlo[1], whi[0], whi[1]};
       uint32_t out = 0u;
-      float cn[4];
+      float y[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int i = 4 * q + e;
-        const float wv = e4m3_decode_byte(w[q], e);
-        const float gi = wd != 0.0f ? __fadd_rn(g[i], __fmul_rn(wd, wv)) : g[i];   // L2 weight decay as a gradient term
+        const float gi = wd != 0.0f ? __fadd_rn(g[i], __fmul_rn(wd, wv[e])) : g[i];   // L2 weight decay as a gradient term
         const float u = __fmul_rn(lr, gi);
-        float t, y = 0.0f;
+        float t;
+        y[e] = 0.0f;
         if (KAHAN) {
           const float cv = u2f((i & 1) ? (c[i >> 1] & 0xFFFF0000u) : (c[i >> 1] << 16));
-          y = __fsub_rn(-u, cv);
-          t = __fadd_rn(wv, y);
+          y[e] = __fsub_rn(-u, cv);
+          t = __fadd_rn(wv[e], y[e]);
         } else {
-          t = __fsub_rn(wv, u);
+          t = __fsub_rn(wv[e], u);
         }
         if (SR) {
           const uint32_t rnd = (i & 1) ? (rw[i >> 1] & 0xFFFF0000u) : (rw[i >> 1] << 16);
@@ -522,12 +528,13 @@ __device__ inline void update16(uint32_t (&w)[8], uint32_t (&c)[8], const float 
         } else {
           out |= e4m3_rne(t) << (8 * e);
         }
-        if (KAHAN) cn[e] = __fsub_rn(__fsub_rn(e4m3_decode_byte(out, e), wv), y);
       }
       w[q] = out;
       if (KAHAN) {
-        c[2 * q] = pack2_bf16(cn[0], cn[1]);       // hardware round-to-nearest-even
-        c[2 * q + 1] = pack2_bf16(cn[2], cn[3]);
+        const f32x2 nlo = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(out, 1.0f, false);
+        const f32x2 nhi = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(out, 1.0f, true);
+        c[2 * q] = pack2_bf16(__fsub_rn(__fsub_rn(nlo[0], wv[0]), y[0]), __fsub_rn(__fsub_rn(nlo[1], wv[1]), y[1]));   // hardware round-to-nearest-even
+        c[2 * q + 1] = pack2_bf16(__fsub_rn(__fsub_rn(nhi[0], wv[2]), y[2]), __fsub_rn(__fsub_rn(nhi[1], wv[3]), y[3]));
       }
     }
   } else {
@@ -545,7 +552,9 @@ __device__ inline void update16(uint32_t (&w)[8], uint32_t (&c)[8], const float 
 
 // DROP: the weight gradient is that of the masked model: zero where the step's mask drops the
 // element, scaled by 1 / (1 - p) elsewhere.
-template <int FMT, bool SR, bool KAHAN, bool DROP>
+// WD: the update includes the weight-decay term (a template parameter because this phase is bound
+// by the vector ALU: the common wd = 0 case should not compute the term and select it away).
+template <int FMT, bool SR, bool KAHAN, bool DROP, bool WD>
 __global__ void __launch_bounds__(kGemmThreads, 1)
 k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restrict__ Wc, uint16_t* __restrict__ Cc,
          int n, int d, int Bp, float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0, DropArgs dr) {
@@ -655,7 +664,7 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
         rb[0] = sr_block(blk, seed, step);
         rb[1] = sr_block(blk + 1, seed, step);
       }
-      update16<FMT, SR, KAHAN>(w, c, g, lr, wd, rb);
+      update16_wd<FMT, SR, KAHAN, WD>(w, c, g, lr, wd, rb);
       char* wp = Wc + eoff * ESZ;
       *reinterpret_cast<u32x4*>(wp) = u32x4{w[0], w[1], w[2], w[3]};
       if (WQ == 2) *reinterpret_cast<u32x4*>(wp + 16) = u32x4{w[4], w[5], w[6], w[7]};
@@ -690,7 +699,7 @@ template <int FMT, bool KAHAN> constexpr int dxu_smem_bytes() { return kStages *
 // vmcnt(0) wait in front of the transposing LDS reads (it cannot tell them from the asynchronous
 // loads still in flight for later stages) and the ring stops prefetching.  The waits that are
 // needed are the explicit ones below.
-template <int FMT, bool SR, bool KAHAN, bool DX>
+template <int FMT, bool SR, bool KAHAN, bool DX, bool WD>
 __device__ __forceinline__ void dx_update_body(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restrict__ Wc,
                                                uint16_t* __restrict__ Cc, float* __restrict__ dXacc, int n, int d, int Bp,
                                                float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0, int tiles_per_group,
@@ -808,7 +817,7 @@ __device__ __forceinline__ void dx_update_body(const char* __restrict__ Gt, cons
         rb[0] = sr_block(blk, seed, step);
         rb[1] = sr_block(blk + 1, seed, step);
       }
-      update16<FMT, SR, KAHAN>(w, cc, gr, lr, wd, rb);
+      update16_wd<FMT, SR, KAHAN, WD>(w, cc, gr, lr, wd, rb);
       char* wp = Wc + eoff * ESZ;
       *reinterpret_cast<u32x4*>(wp) = u32x4{w[0], w[1], w[2], w[3]};
       if (ESZ == 2) *reinterpret_cast<u32x4*>(wp + 16) = u32x4{w[4], w[5], w[6], w[7]};
@@ -826,13 +835,13 @@ __device__ __forceinline__ void dx_update_body(const char* __restrict__ Gt, cons
   }
 }
 
-template <int FMT, bool SR, bool KAHAN, bool DX>
+template <int FMT, bool SR, bool KAHAN, bool DX, bool WD>
 __global__ void __launch_bounds__(kGemmThreads, 1)
 k_dx_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restrict__ Wc, uint16_t* __restrict__ Cc,
             float* __restrict__ dXacc, int n, int d, int Bp, float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0,
             int tiles_per_group) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  dx_update_body<FMT, SR, KAHAN, DX>(Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, wd, seed, step, elem0, tiles_per_group, smem);
+  dx_update_body<FMT, SR, KAHAN, DX, WD>(Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, wd, seed, step, elem0, tiles_per_group, smem);
 }
 
 // ---------------------------------------------------------------------------------------------
