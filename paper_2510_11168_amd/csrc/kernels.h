@@ -125,6 +125,18 @@ __global__ void __launch_bounds__(kThreads) k_label_scatter(const int* __restric
 // a tile of this size halves the fill traffic per flop of a 256 x 128 tile, and the ping-pong
 // issue order of the ring hides most of what is left.
 // ---------------------------------------------------------------------------------------------
+#ifndef ELMO_UPD_UNEVEN
+#define ELMO_UPD_UNEVEN false
+#endif
+#ifndef ELMO_UPD_LA
+#define ELMO_UPD_LA 2
+#endif
+#ifndef ELMO_DX_UNEVEN
+#define ELMO_DX_UNEVEN true
+#endif
+#ifndef ELMO_DX_LA
+#define ELMO_DX_LA 2
+#endif
 constexpr int kGemmThreads = 512;
 constexpr int kGemmWaves = 8;
 constexpr int kStages = 3;                                       // ring depth of the small-batch kernel
@@ -254,7 +266,7 @@ __device__ __forceinline__ void logits_tile_product(const char* __restrict__ Xa,
   zero_acc(acc);
   ring_pipeline_pp<TB, 128, TB, 128, 2, kGemmWaves, true>(
       Xa, rowb, a_valid, 0, 128, 8, Wc, rowb, w_valid, 0, 128, 8, (int)(rowb >> 7), smem, wave, lane,
-      [&](const char* sa, const char* sb, int half) { logits_slab_product<FP8, FN>(sa, sb, half, wm, wn, lane, acc); },
+      [&](const char* sa, const char* sb, int q0, int) { logits_slab_product<FP8, FN>(sa, sb, q0 >> 1, wm, wn, lane, acc); },
       static_cast<Prep&&>(prep));
 }
 
@@ -409,9 +421,9 @@ k_dx(const char* __restrict__ Gt, const char* __restrict__ Wc, float* __restrict
 
   f32x16 acc[2][4];
   zero_acc(acc);
-  auto product = [&](const char* sa, const char* sb, int half) {
+  auto product = [&](const char* sa, const char* sb, int q0, int q1) {
 #pragma unroll
-    for (int kk = 2 * half; kk < 2 * half + 2; ++kk) {
+    for (int kk = q0; kk < q1; ++kk) {
       bf16x8 a[2], b[4];
 #pragma unroll
       for (int i = 0; i < 2; ++i) a[i] = frag_tr_bf16<512>(sa, 16 * kk, wm * 64 + 32 * i, lane);
@@ -433,7 +445,7 @@ k_dx(const char* __restrict__ Gt, const char* __restrict__ Wc, float* __restrict
   if constexpr (DROP) {
     // the same masked weights as in the logits product (appendix "Low-Memory Dropout for Classifier")
     const uint64_t blk_first = (elem0 + (uint64_t)ks0 * 64 * d + j0) >> 4;
-    ring_pipeline_pp<64, 512, 64, WROWB, dx_stages<FP8>(), kGemmWaves, true>(
+    ring_pipeline_pp<64, 512, 64, WROWB, dx_stages<FP8>(), kGemmWaves, ELMO_DX_UNEVEN, ELMO_DX_LA>(
         ga, strideA, va0, 64, 64 * strideA, 32, gb, strideB, n - ks0 * 64, 64, 64 * strideB, chunks_b, ks1 - ks0, smem, wave, lane,
         product, [&](char* sb, int ks) {
           drop_slab<64, WROWB, FP8>(sb, blk_first + (uint64_t)ks * 4 * d, (uint32_t)d >> 4, seed, step, dr.thresh, tid);
@@ -445,7 +457,7 @@ k_dx(const char* __restrict__ Gt, const char* __restrict__ Wc, float* __restrict
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] *= dr.scale;
   } else {
-    ring_pipeline_pp<64, 512, 64, WROWB, dx_stages<FP8>(), kGemmWaves, true>(
+    ring_pipeline_pp<64, 512, 64, WROWB, dx_stages<FP8>(), kGemmWaves, ELMO_DX_UNEVEN, ELMO_DX_LA>(
         ga, strideA, va0, 64, 64 * strideA, 32, gb, strideB, n - ks0 * 64, 64, 64 * strideB, chunks_b, ks1 - ks0, smem, wave, lane,
         product);
   }
@@ -594,11 +606,11 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
   f32x16 acc[2][4];
   zero_acc(acc);
   // K loop over the batch in slabs of 64 samples
-  ring_pipeline_pp<256, 128, 256, 128, 2, kGemmWaves, false>(
+  ring_pipeline_pp<256, 128, 256, 128, 2, kGemmWaves, ELMO_UPD_UNEVEN, ELMO_UPD_LA>(
       Gt + (size_t)l0 * stride, stride, n - l0, 0, 128, 8, XT + (size_t)j0 * stride, stride, d - j0, 0, 128, 8, Bp >> 6, smem, wave,
-      lane, [&](const char* sa, const char* sb, int half) {
+      lane, [&](const char* sa, const char* sb, int q0, int q1) {
 #pragma unroll
-        for (int kk = 2 * half; kk < 2 * half + 2; ++kk) {
+        for (int kk = q0; kk < q1; ++kk) {
           bf16x8 a[2], b[4];
 #pragma unroll
           for (int i = 0; i < 2; ++i) a[i] = frag_bf16(sa, wm * 64 + 32 * i, kk, lane);

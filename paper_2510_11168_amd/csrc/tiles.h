@@ -71,6 +71,14 @@ __device__ inline void dma_tile(const char* __restrict__ g, size_t stride, int r
                                 int chunks_valid = 1 << 20) {
   constexpr int RPI = 1024 / ROWB, CPR = ROWB / 16, NI = ROWS / RPI / NW;
   static_assert(ROWS % (RPI * NW) == 0 && NI >= 1, "tile must split evenly over the waves");
+  // The slab pointer is wave-uniform.  Passing it through an empty asm statement as a scalar
+  // register pair keeps the compiler from folding it into per-lane 64-bit addresses that it then
+  // hoists out of the K loop (two registers per load, kept alive for the whole kernel).
+  {
+    uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)g), hi = __builtin_amdgcn_readfirstlane((uint32_t)((uintptr_t)g >> 32));
+    asm volatile("" : "+s"(lo), "+s"(hi));
+    g = reinterpret_cast<const char*>(((uintptr_t)hi << 32) | lo);
+  }
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
     const int rbase = (wave * NI + i) * RPI;
@@ -79,7 +87,8 @@ __device__ inline void dma_tile(const char* __restrict__ g, size_t stride, int r
     const int rc = min(r, rows_valid - 1);
     // 32-bit lane offset on top of the (wave-uniform) slab pointer: the load then takes the
     // scalar-base + vector-offset form and needs no 64-bit address arithmetic per lane
-    const uint32_t off = __umul24((uint32_t)rc, (uint32_t)stride) + (uint32_t)(c * 16);
+    uint32_t off = __umul24((uint32_t)rc, (uint32_t)stride) + (uint32_t)(c * 16);
+    asm volatile("" : "+v"(off));   // stays a 32-bit register (its 64-bit extension would be hoisted as a pair)
     __builtin_amdgcn_global_load_lds(ELMO_GLOBAL_PTR(g + off), ELMO_LDS_PTR(void, lds_tile + rbase * ROWB), 16, 0, 0);
 #if defined(ELMO_DMA_GAP)
 #pragma unroll
@@ -152,14 +161,17 @@ template <int ROWS, int ROWB> struct TileLoader {
 //
 // ring_stream_pp is the general form: src(ks, off_a, va, off_b, vb) names slab ks of each operand
 // (byte offset from ga / gb and number of valid rows), so a workgroup can run the ring across the
-// output tiles it owns without draining it; mma(stageA, stageB, half, ks).  The base pointers are
+// output tiles it owns without draining it; mma(stageA, stageB, q0, q1, ks).  The base pointers are
 // restrict-qualified parameters on purpose: inlining then tags every LDS access inside with alias
 // information, without which the compiler puts a vmcnt(0) in front of LDS reads it cannot tell
 // from the asynchronous loads still in flight.
 // prep(stageB, ks), if given, is run by every wave on the landed B slab before the product (it may
 // rewrite the slab in LDS); a barrier follows it.
 struct NoPrep {};
-template <int AROWS, int AROWB, int BROWS, int BROWB, int NST, int NW, bool UNEVEN, class Src, class Mma, class Prep = NoPrep>
+// LATE_AFTER (1..3): the product of a slab is four quarters, mma(stageA, stageB, q0, q1, ks) runs
+// quarters [q0, q1); the late waves issue after LATE_AFTER of them (2 = between the two halves).
+template <int AROWS, int AROWB, int BROWS, int BROWB, int NST, int NW, bool UNEVEN, int LATE_AFTER = 2, class Src, class Mma,
+          class Prep = NoPrep>
 __device__ inline void ring_stream_pp(const char* __restrict__ ga, size_t stride_a, int chunks_a, const char* __restrict__ gb,
                                       size_t stride_b, int chunks_b, int nk, char* smem, int wave, int lane, Src&& src, Mma&& mma,
                                       Prep&& prep = Prep{}) {
@@ -202,27 +214,27 @@ __device__ inline void ring_stream_pp(const char* __restrict__ ga, size_t stride
       barrier_lds();
     }
     __builtin_amdgcn_sched_barrier(0);
-    mma(st, st + ABYTES, 0, ks);
+    mma(st, st + ABYTES, 0, LATE_AFTER, ks);
     __builtin_amdgcn_sched_barrier(0);
     if (more && late) issue(ks + NST - 1);
     __builtin_amdgcn_sched_barrier(0);
-    mma(st, st + ABYTES, 1, ks);
+    mma(st, st + ABYTES, LATE_AFTER, 4, ks);
   }
   barrier_nofence();   // every wave is done with the ring: the caller may reuse the memory
 }
 
 // One output tile: slab ks of an operand starts at g + ks*adv and has v0 - ks*dv valid rows.
-template <int AROWS, int AROWB, int BROWS, int BROWB, int NST, int NW, bool UNEVEN, class Mma, class Prep = NoPrep>
+template <int AROWS, int AROWB, int BROWS, int BROWB, int NST, int NW, bool UNEVEN, int LATE_AFTER = 2, class Mma, class Prep = NoPrep>
 __device__ inline void ring_pipeline_pp(const char* __restrict__ ga, size_t stride_a, int va0, int dva, size_t adv_a, int chunks_a,
                                         const char* __restrict__ gb, size_t stride_b, int vb0, int dvb, size_t adv_b, int chunks_b,
                                         int nk, char* smem, int wave, int lane, Mma&& mma, Prep&& prep = Prep{}) {
-  ring_stream_pp<AROWS, AROWB, BROWS, BROWB, NST, NW, UNEVEN>(
+  ring_stream_pp<AROWS, AROWB, BROWS, BROWB, NST, NW, UNEVEN, LATE_AFTER>(
       ga, stride_a, chunks_a, gb, stride_b, chunks_b, nk, smem, wave, lane,
       [&](int ks, size_t& off_a, int& va, size_t& off_b, int& vb) {
         off_a = (size_t)ks * adv_a; va = va0 - ks * dva;
         off_b = (size_t)ks * adv_b; vb = vb0 - ks * dvb;
       },
-      [&](const char* sa, const char* sb, int half, int) { mma(sa, sb, half); }, static_cast<Prep&&>(prep));
+      [&](const char* sa, const char* sb, int q0, int q1, int) { mma(sa, sb, q0, q1); }, static_cast<Prep&&>(prep));
 }
 
 // ---------------------------------------------------------------------------------------------
