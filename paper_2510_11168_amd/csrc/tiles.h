@@ -33,7 +33,14 @@ constexpr int kThreads = 256;
 #define ELMO_LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
 template <int ROWB> __device__ inline int swz_key(int r) {
-  return ROWB == 64 ? (r >> 2) & 3 : ROWB == 128 ? (r >> 1) & 7 : (r & 7) << 1;   // 256- and 512-byte rows: pairs of chunks move together
+  // 256- and 512-byte rows (the K-major tiles read by the transposing loads): pairs of chunks move
+  // together.  512-byte rows: four consecutive rows go to four different 64-byte quarters of the
+  // 256-byte bank period, which is what one pass of ds_read_b64_tr_b16 (4 rows x 64 B) touches;
+  // with the (r & 7) << 1 key of the 256-byte rows that read ran into two-way conflicts (a third
+  // of the LDS cycles of the input-gradient kernel by the SQ_LDS_BANK_CONFLICT counter).  The
+  // 256-byte rows keep their key: ds_read_b64_tr_b8 (8 rows x 32 B) is conflict-free with it, and
+  // the single-pass small-batch kernel measured 4 % slower with the other one.
+  return ROWB == 64 ? (r >> 2) & 3 : ROWB == 128 ? (r >> 1) & 7 : ROWB == 256 ? (r & 7) << 1 : ((r & 3) << 2) | (((r >> 2) & 1) << 1);
 }
 template <int ROWB> __device__ inline int tile_off(int r, int c) {
   return r * ROWB + ((c ^ swz_key<ROWB>(r)) << 4);
