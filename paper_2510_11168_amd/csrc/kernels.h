@@ -59,62 +59,129 @@ __global__ void __launch_bounds__(kThreads) k_prep_x(const uint16_t* __restrict_
 // COO pairs of each chunk; here the filter is a counting sort done once per step).
 // ---------------------------------------------------------------------------------------------
 // Eight lanes share a sample row (its positives are few, and one lane per row would walk them as a
-// chain of dependent loads).
+// chain of dependent loads).  Label ids sorted by falling frequency put most positives of a batch
+// into the first few bins; atomics on one address serialise in L2, so every workgroup first counts
+// the bins below kHotBins in LDS and touches each of those global counters once.
 constexpr int kRowLanes = 8;
+constexpr int kHotBins = 2048;                                   // labels 0 .. 262143
 __global__ void __launch_bounds__(kThreads) k_label_hist(const int* __restrict__ indptr, const int* __restrict__ indices,
                                                          int B, int64_t L, int64_t nnz, int* __restrict__ cnt,
                                                          int* __restrict__ bad) {
+  __shared__ int hot[kHotBins];
+  for (int i = threadIdx.x; i < kHotBins; i += kThreads) hot[i] = 0;
+  __syncthreads();
   const int t = blockIdx.x * kThreads + threadIdx.x;
   const int b = t / kRowLanes, sub = t % kRowLanes;
-  if (b >= B) return;
-  const int p0 = indptr[b], p1 = indptr[b + 1];
-  if (p0 < 0 || p1 < p0 || p1 > nnz) { if (bad && sub == 0) atomicOr(bad, 1); return; }
-  for (int p = p0 + sub; p < p1; p += kRowLanes) {
-    const int l = indices[p];
-    const bool in_range = l >= 0 && l < L;
-    if (bad && (!in_range || (p > p0 && l <= indices[p - 1]))) atomicOr(bad, 2);   // out of range, or not strictly ascending
-    if (in_range) atomicAdd(&cnt[l >> 7], 1);
+  if (b < B) {
+    const int p0 = indptr[b], p1 = indptr[b + 1];
+    if (p0 < 0 || p1 < p0 || p1 > nnz) {
+      if (bad && sub == 0) atomicOr(bad, 1);
+    } else {
+      for (int p = p0 + sub; p < p1; p += kRowLanes) {
+        const int l = indices[p];
+        const bool in_range = l >= 0 && l < L;
+        if (bad && (!in_range || (p > p0 && l <= indices[p - 1]))) atomicOr(bad, 2);   // out of range, or not strictly ascending
+        if (in_range) {
+          const int bin = l >> 7;
+          if (bin < kHotBins) atomicAdd(&hot[bin], 1);
+          else atomicAdd(&cnt[bin], 1);
+        }
+      }
+    }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < kHotBins; i += kThreads) {
+    const int c = hot[i];
+    if (c) atomicAdd(&cnt[i], c);
   }
 }
-// Exclusive scan of cnt[0..nb) into ptr[0..nb] (ptr[nb] = total) and cur[0..nb) = ptr. One workgroup:
-// every thread sums a contiguous run of bins, the 1024 run totals are scanned in LDS.
+// Exclusive scan of cnt[0..nb) into ptr[0..nb] (ptr[nb] = total) and cur[0..nb) = ptr.  One
+// workgroup; the bins pass through LDS in segments so that global memory is read and written in
+// whole lines (a thread's run of consecutive bins would otherwise touch 64 lines per load), every
+// thread sums a run of a segment, the 1024 run totals are scanned in LDS.
+constexpr int kScanRun = 15, kScanSeg = kScanRun * 1024;
 __global__ void __launch_bounds__(1024) k_label_scan(const int* __restrict__ cnt, int nb, int* __restrict__ ptr, int* __restrict__ cur) {
+  __shared__ int seg[kScanSeg];
   __shared__ int part[1024];
   const int tid = threadIdx.x;
-  const int per = (nb + 1023) / 1024;
-  const int i0 = min(tid * per, nb), i1 = min(i0 + per, nb);
-  int sum = 0;
-  for (int i = i0; i < i1; ++i) sum += cnt[i];
-  part[tid] = sum;
-  __syncthreads();
-  for (int o = 1; o < 1024; o <<= 1) {
-    const int t = tid >= o ? part[tid - o] : 0;
+  int carry = 0;
+  for (int base = 0; base < nb; base += kScanSeg) {
+    const int m = min(kScanSeg, nb - base);
+    for (int i = tid; i < m; i += 1024) seg[i] = cnt[base + i];
     __syncthreads();
-    part[tid] += t;
+    const int i0 = min(tid * kScanRun, m), i1 = min(i0 + kScanRun, m);
+    int sum = 0;
+    for (int i = i0; i < i1; ++i) sum += seg[i];
+    part[tid] = sum;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+      const int t = tid >= o ? part[tid - o] : 0;
+      __syncthreads();
+      part[tid] += t;
+      __syncthreads();
+    }
+    int run = carry + part[tid] - sum;               // exclusive prefix of this thread's run
+    for (int i = i0; i < i1; ++i) {
+      const int v = seg[i];
+      seg[i] = run;
+      run += v;
+    }
+    carry += part[1023];
+    __syncthreads();
+    for (int i = tid; i < m; i += 1024) {
+      const int v = seg[i];
+      ptr[base + i] = v;
+      cur[base + i] = v;
+    }
     __syncthreads();
   }
-  int run = part[tid] - sum;                       // exclusive prefix of this thread's run
-  for (int i = i0; i < i1; ++i) {
-    ptr[i] = run;
-    cur[i] = run;
-    run += cnt[i];
-  }
-  if (tid == 1023) ptr[nb] = part[1023];
+  if (tid == 0) ptr[nb] = carry;
 }
+// Positives into their bins.  For the bins below kHotBins a workgroup ranks its positives in LDS,
+// reserves one range per bin with a single global atomic and then writes; a thread keeps up to
+// four such positives in registers between the two phases, anything beyond goes the direct way.
 __global__ void __launch_bounds__(kThreads) k_label_scatter(const int* __restrict__ indptr, const int* __restrict__ indices,
                                                             int B, int64_t L, int64_t nnz, int* __restrict__ cur,
                                                             int2* __restrict__ pos) {
+  __shared__ int hot[kHotBins];
+  for (int i = threadIdx.x; i < kHotBins; i += kThreads) hot[i] = 0;
+  __syncthreads();
   const int t = blockIdx.x * kThreads + threadIdx.x;
   const int b = t / kRowLanes, sub = t % kRowLanes;
-  if (b >= B) return;
-  const int p0 = indptr[b], p1 = indptr[b + 1];
-  if (p0 < 0 || p1 < p0 || p1 > nnz) return;
-  for (int p = p0 + sub; p < p1; p += kRowLanes) {
-    const int l = indices[p];
-    if (l < 0 || l >= L) continue;
-    const int slot = atomicAdd(&cur[l >> 7], 1);
-    if (slot < nnz) pos[slot] = make_int2(l, b);
+  int lab[4] = {-1, -1, -1, -1}, rank[4] = {0, 0, 0, 0};
+  if (b < B) {
+    const int p0 = indptr[b], p1 = indptr[b + 1];
+    if (!(p0 < 0 || p1 < p0 || p1 > nnz)) {
+      int kept = 0;
+      for (int p = p0 + sub; p < p1; p += kRowLanes) {
+        const int l = indices[p];
+        if (l < 0 || l >= L) continue;
+        const int bin = l >> 7;
+        if (bin < kHotBins && kept < 4) {
+          const int r = atomicAdd(&hot[bin], 1);
+#pragma unroll
+          for (int k = 0; k < 4; ++k)
+            if (k == kept) { lab[k] = l; rank[k] = r; }
+          ++kept;
+        } else {
+          const int slot = atomicAdd(&cur[bin], 1);
+          if (slot < nnz) pos[slot] = make_int2(l, b);
+        }
+      }
+    }
   }
+  __syncthreads();
+  for (int i = threadIdx.x; i < kHotBins; i += kThreads) {
+    const int c = hot[i];
+    hot[i] = c ? atomicAdd(&cur[i], c) : 0;          // first slot of this workgroup's range in bin i
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+    if (lab[k] >= 0) {
+      const int slot = hot[lab[k] >> 7] + rank[k];
+      if (slot < nnz) pos[slot] = make_int2(lab[k], b);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
