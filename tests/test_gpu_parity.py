@@ -473,6 +473,45 @@ def test_degenerate_inputs(b):
     assert abs(loss - 3 * L * np.log(2.0)) < 1e-3 * 3 * L
 
 
+def test_label_index_with_long_rows_crowded_bins_and_far_labels(b):
+    """The per-step label index (positives regrouped by 128-label bin): a row with 300 positives (more
+    than a thread keeps in registers between the index's two phases), 40 rows that all name the
+    same few head labels (one crowded bin), and labels beyond the range that is counted in LDS
+    first (ids >= 262144).  Every positive must arrive as exactly one "-1" in G: checked through
+    the weight rows of the touched labels, the input gradient and the loss."""
+    L, d, B, chunk, lr = 270000, 128, 70, 65536, 0.1
+    fmt, flags = o.BF16, 0
+    case = Case(b, L, d, fmt, chunk, flags, B, max_nnz=4096, w_std=0.05, seed=31)
+    rng = np.random.default_rng(77)
+    X = synth.make_x(rng, B, d)
+    rows = []
+    rows.append(np.unique(np.concatenate([rng.choice(400, 200, replace=False), rng.choice(np.arange(262144, L), 100, replace=False)])))
+    for i in range(1, 41):
+        rows.append(np.array([0, 1, 2, 3, 127, 128, 262144 + i, L - 1]))
+    for i in range(41, B):
+        rows.append(np.unique(rng.integers(0, L, size=rng.integers(0, 9))))
+    indptr = np.zeros(B + 1, np.int32)
+    indptr[1:] = np.cumsum([len(r) for r in rows])
+    indices = np.concatenate(rows).astype(np.int32)
+    say(f"[label index] L={L} B={B} nnz={len(indices)} longest row {max(len(r) for r in rows)}")
+    dX, loss = case.step(X, indptr, indices, lr, 5, 1)
+    touched = np.unique(indices)
+    sample = np.unique(np.concatenate([touched, rng.integers(0, L, 4000)]))
+    ref = o.head_step(case.W0[sample], None, X, indptr, indices, lr, 5, 1, fmt, flags, label_ids=sample)
+    Wn = case.W()[sample]
+    dist = np.abs(ordered(Wn, fmt) - ordered(ref["W_new"], fmt))
+    say(f"   W' on {len(sample)} label rows ({len(touched)} with positives): within 1 ulp {np.mean(dist <= 1):.6f}")
+    assert np.mean(dist <= 1) >= 0.999
+    assert_far_misses_are_tiny(Wn, ref["W_new"], dist, fmt, lr)
+    # rows with positives move against X; a lost or doubled "-1" would change them by lr * |x| ~ 1e-2
+    hot = np.isin(sample, touched)
+    assert np.max(np.abs(o.decode(Wn[hot], fmt) - o.decode(ref["W_new"][hot], fmt))) < 1e-3
+    dX_ref, Z = o.input_gradient_rows(case.W0, X, indptr, indices, fmt, np.arange(B))
+    assert rel_fro(dX, dX_ref) <= 2e-2
+    Y = o.csr_to_dense(indptr, indices, L)
+    assert abs(loss - o.bce_loss(Z, Y)) / o.bce_loss(Z, Y) < 2e-3
+
+
 def test_validation_flag_reports_bad_labels_on_the_next_call(b):
     """Bad label ids are caught by the kernels' own bounds checks (nothing faults) and surface
     as error -4 on the following call."""
