@@ -192,18 +192,12 @@ __global__ void __launch_bounds__(kThreads) k_label_scatter(const int* __restric
 // a tile of this size halves the fill traffic per flop of a 256 x 128 tile, and the ping-pong
 // issue order of the ring hides most of what is left.
 // ---------------------------------------------------------------------------------------------
-#ifndef ELMO_UPD_UNEVEN
-#define ELMO_UPD_UNEVEN false
-#endif
-#ifndef ELMO_UPD_LA
-#define ELMO_UPD_LA 2
-#endif
-#ifndef ELMO_DX_UNEVEN
-#define ELMO_DX_UNEVEN true
-#endif
-#ifndef ELMO_DX_LA
-#define ELMO_DX_LA 2
-#endif
+// How each product splits a slab's loads between the early and the late waves (tiles.h): uneven =
+// three quarters early; late issue after this many quarters of the slab's MFMAs.  Measured per
+// kernel: the update kernel's K loop is 2 % faster uneven but then spills; issuing after one or
+// three quarters was never better than after two.
+constexpr bool kUpdUneven = false, kDxUneven = true;
+constexpr int kUpdLateAfter = 2, kDxLateAfter = 2;
 constexpr int kGemmThreads = 512;
 constexpr int kGemmWaves = 8;
 constexpr int kStages = 3;                                       // ring depth of the small-batch kernel
@@ -512,7 +506,7 @@ k_dx(const char* __restrict__ Gt, const char* __restrict__ Wc, float* __restrict
   if constexpr (DROP) {
     // the same masked weights as in the logits product (appendix "Low-Memory Dropout for Classifier")
     const uint64_t blk_first = (elem0 + (uint64_t)ks0 * 64 * d + j0) >> 4;
-    ring_pipeline_pp<64, 512, 64, WROWB, dx_stages<FP8>(), kGemmWaves, ELMO_DX_UNEVEN, ELMO_DX_LA>(
+    ring_pipeline_pp<64, 512, 64, WROWB, dx_stages<FP8>(), kGemmWaves, kDxUneven, kDxLateAfter>(
         ga, strideA, va0, 64, 64 * strideA, 32, gb, strideB, n - ks0 * 64, 64, 64 * strideB, chunks_b, ks1 - ks0, smem, wave, lane,
         product, [&](char* sb, int ks) {
           drop_slab<64, WROWB, FP8>(sb, blk_first + (uint64_t)ks * 4 * d, (uint32_t)d >> 4, seed, step, dr.thresh, tid);
@@ -524,7 +518,7 @@ k_dx(const char* __restrict__ Gt, const char* __restrict__ Wc, float* __restrict
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] *= dr.scale;
   } else {
-    ring_pipeline_pp<64, 512, 64, WROWB, dx_stages<FP8>(), kGemmWaves, ELMO_DX_UNEVEN, ELMO_DX_LA>(
+    ring_pipeline_pp<64, 512, 64, WROWB, dx_stages<FP8>(), kGemmWaves, kDxUneven, kDxLateAfter>(
         ga, strideA, va0, 64, 64 * strideA, 32, gb, strideB, n - ks0 * 64, 64, 64 * strideB, chunks_b, ks1 - ks0, smem, wave, lane,
         product);
   }
@@ -673,7 +667,7 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
   f32x16 acc[2][4];
   zero_acc(acc);
   // K loop over the batch in slabs of 64 samples
-  ring_pipeline_pp<256, 128, 256, 128, 2, kGemmWaves, ELMO_UPD_UNEVEN, ELMO_UPD_LA>(
+  ring_pipeline_pp<256, 128, 256, 128, 2, kGemmWaves, kUpdUneven, kUpdLateAfter>(
       Gt + (size_t)l0 * stride, stride, n - l0, 0, 128, 8, XT + (size_t)j0 * stride, stride, d - j0, 0, 128, 8, Bp >> 6, smem, wave,
       lane, [&](const char* sa, const char* sb, int q0, int q1) {
 #pragma unroll

@@ -97,10 +97,6 @@ __device__ inline void dma_tile(const char* __restrict__ g, size_t stride, int r
     uint32_t off = __umul24((uint32_t)rc, (uint32_t)stride) + (uint32_t)(c * 16);
     asm volatile("" : "+v"(off));   // stays a 32-bit register (its 64-bit extension would be hoisted as a pair)
     __builtin_amdgcn_global_load_lds(ELMO_GLOBAL_PTR(g + off), ELMO_LDS_PTR(void, lds_tile + rbase * ROWB), 16, 0, 0);
-#if defined(ELMO_DMA_GAP)
-#pragma unroll
-    for (int w_ = 0; w_ < ELMO_DMA_GAP; ++w_) asm volatile("s_nop 15");
-#endif
   }
 }
 template <int ROWS, int ROWB, int NW> constexpr int dma_loads_per_wave() { return ROWS * ROWB / 1024 / NW; }
@@ -154,12 +150,13 @@ template <int ROWS, int ROWB> struct TileLoader {
 // wait until at most the younger slabs' loads are outstanding (vmcnt counts in issue order), one
 // barrier, refill the stage that was consumed one step earlier, then the slab's products.
 //
-// Ping-pong issue order.  The product of one slab is split in two
-// halves, mma(stageA, stageB, 0) and mma(stageA, stageB, 1).  A wave that issues an asynchronous
+// Ping-pong issue order.  The product of one slab is split in two parts (by default its two
+// halves), mma(stageA, stageB, 0, LATE_AFTER) and mma(stageA, stageB, LATE_AFTER, 4), in units of
+// quarters of the slab.  A wave that issues an asynchronous
 // load is held until the memory pipeline accepts it, i.e. roughly for as long as the data takes
 // to move; with every wave issuing at the same point the load and MFMA phases add up instead of
 // overlapping.  Here waves 0..NW/2-1 issue right after the barrier (the whole A slab and the first
-// half of the B slab), waves NW/2..NW-1 between the two halves (the second half of the B slab);
+// half of the B slab), waves NW/2..NW-1 between the two parts (the second half of the B slab);
 // with UNEVEN = false both groups issue an equal share of both slabs.
 // Waves w and w + 4 share a SIMD, so one wave of each SIMD computes while its partner is held.
 // Measured on the BF16 main loop alone: all waves issuing together 1.33 PFLOP/s, equal shares
