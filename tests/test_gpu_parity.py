@@ -561,14 +561,26 @@ def test_full_size_configs_on_samples(b, name, dx_rows):
     """BASELINE configs 2-4 at full size in the launch configuration the benchmark times.
     Labels are independent given X, so the oracle evaluates a label sample exactly (all in-batch
     positives, chunk-boundary rows, the ragged tail, random rows) and a few full rows of dX."""
-    cfg = synth.CONFIGS[name]
+    _full_size_check(b, synth.CONFIGS[name], name, dx_rows, 2)
+
+
+@pytest.mark.parametrize("B,chunk,kahan,dx_rows", [(128, 262144, True, 2), (32, 65536, True, 2), (4096, 65536, False, 2)])
+def test_xl_sweep_points_on_samples(b, B, chunk, kahan, dx_rows):
+    """BASELINE config 5 (the bandwidth-regime sweep at 3M labels) at full size, in the launch
+    configurations the benchmark times: the single-pass small-batch kernel at B = 128 and B = 32,
+    the 256 x 256-tile kernels with 16 batch tiles at B = 4096."""
+    cfg = synth.xl_sweep(B, chunk, kahan)
+    _full_size_check(b, cfg, cfg.name, dx_rows, 1)
+
+
+def _full_size_check(b, cfg, name, dx_rows, steps):
     tol = 6e-2 if cfg.fmt == o.E4M3 else 2e-2
     say(f"[{name}] L={cfg.L} d={cfg.d} B={cfg.B} chunk={cfg.chunk} fmt={cfg.fmt} flags={cfg.flags}: init")
     head = b.Head(cfg.L, cfg.d, cfg.fmt, cfg.chunk, cfg.flags, cfg.B, 64 * cfg.B)
     _init_on_device(b, head, cfg)
     zipf = synth.ZipfLabels(cfg.L, cfg.zipf_s)
     rng = np.random.default_rng(1)
-    for step in range(2):                     # second step starts from non-zero compensation
+    for step in range(steps):                 # a second step starts from non-zero compensation
         X, indptr, indices = synth.make_batch(cfg, step, zipf)
         ids = _sample_labels(cfg.L, cfg.chunk, indices, rng, 2048)
         idt = torch.from_numpy(ids).to(DEV)
@@ -710,3 +722,35 @@ def test_topk_mid_size(b):
     X = synth.make_x(np.random.default_rng(3), 64, cfg.d)
     say("[topk-mid] L=131072 B=64 k=100")
     _check_topk(b, head, W, X, 100, cfg.fmt, 2e-3)
+
+
+def test_topk_xl_k100_on_sampled_queries(b):
+    """BASELINE config 5, inference part: elmo_head_topk with k = 100 over all 3M logits for 1024
+    queries.  Every row is checked for shape properties (distinct ids in range, scores sorted);
+    six sampled rows are checked against the oracle's logits over all labels."""
+    cfg = synth.CONFIGS["xl"]
+    B, k = 1024, 100
+    head = b.Head(cfg.L, cfg.d, cfg.fmt, cfg.chunk, 0, B, 64)
+    _init_on_device(b, head, cfg)
+    X = synth.make_x(np.random.default_rng(9), B, cfg.d)
+    idx = torch.zeros((B, k), dtype=torch.int32, device=DEV)
+    sc = torch.zeros((B, k), dtype=torch.float32, device=DEV)
+    say("[topk-xl] L=3000000 B=1024 k=100")
+    head.topk(dev(X), k, idx, sc)
+    torch.cuda.synchronize()
+    idx, sc = idx.cpu().numpy(), sc.cpu().numpy().astype(np.float64)
+    assert idx.min() >= 0 and idx.max() < cfg.L
+    assert np.all(np.diff(sc, axis=1) <= 0)
+    assert all(len(set(r.tolist())) == k for r in idx)
+    rows = np.sort(np.random.default_rng(10).choice(B, size=6, replace=False))
+    W = head.weights().cpu().numpy()
+    Z = np.empty((len(rows), cfg.L))
+    for l0 in range(0, cfg.L, 262144):
+        Z[:, l0:l0 + 262144] = o.logits(W[l0:l0 + 262144], X[rows], cfg.fmt)
+    ref_idx, ref_sc = o.topk(Z, k)
+    eps = 2e-3 * np.abs(ref_sc).max()
+    for j, i in enumerate(rows):
+        assert np.all(Z[j, idx[i]] >= ref_sc[j, -1] - eps)
+        assert np.all(np.abs(sc[i] - Z[j, idx[i]]) <= eps)
+    say(f"   ids identical to the FP64 order in {np.mean(idx[rows] == ref_idx):.4f} of the sampled slots")
+    head.close()
