@@ -87,7 +87,7 @@ int elmo_head_sizes(int64_t L, int32_t d, int weight_dtype, int64_t chunk, int32
  * 16 bits, batch * labels * 2 -- the quantity Section 4.4 divides by the number of chunks. */
 size_t elmo_logit_buffer_bytes(int64_t batch, int64_t labels);
 
-/* Create a head over caller-owned buffers.  Requirements: L >= 1; d a positive multiple of 128;
+/* Create a head over caller-owned buffers.  Requirements: L >= 1; d a positive multiple of 128, at most 2^20;
  * chunk a positive multiple of 128 (the labels processed per pass, Section 4.2 "chunking"; it need
  * not divide L, the last chunk is short); buffers at least as large as elmo_head_sizes says and
  * 256-byte aligned.  Launches nothing.  *out receives the handle. */

@@ -52,6 +52,7 @@ int make_plan(int64_t L, int d, int fmt, int64_t chunk, int maxB, int64_t max_nn
   if (L < 1) return fail(-1, "L must be >= 1 (got %lld)", (long long)L);
   if (L > (int64_t)1 << 31) return fail(-1, "L must fit 31 bits (got %lld)", (long long)L);
   if (d < 128 || d % 128 != 0) return fail(-1, "d must be a positive multiple of 128 (got %d)", d);
+  if (d > (1 << 20)) return fail(-1, "d must be at most 2^20 (got %d)", d);   // tile loads use 24-bit x 24-bit row offsets
   if (chunk < 128 || chunk % 128 != 0) return fail(-1, "chunk must be a positive multiple of 128 (got %lld)", (long long)chunk);
   if (chunk > ((int64_t)1 << 30)) return fail(-1, "chunk too large (got %lld)", (long long)chunk);
   if (maxB < 1 || maxB > 65536) return fail(-1, "max_B must be in [1, 65536] (got %d)", maxB);

@@ -118,6 +118,7 @@ def test_workspace_is_one_chunks_buffer_plus_small_terms(b):
 @pytest.mark.parametrize("args,code", [
     ((0, 768, 0, 1024, 8, 8, 0), -1),            # L
     ((100, 100, 0, 1024, 8, 8, 0), -1),          # d not a multiple of 128
+    ((100, (1 << 20) + 128, 0, 1024, 8, 8, 0), -1),   # d beyond the supported width
     ((100, 768, 0, 100, 8, 8, 0), -1),           # chunk not a multiple of 128
     ((100, 768, 0, 1024, 0, 8, 0), -1),          # max_B
     ((100, 768, 0, 1024, 8, 0, 0), -1),          # max_nnz
