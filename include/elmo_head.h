@@ -106,7 +106,10 @@ int elmo_head_create(int64_t L, int32_t d, int weight_dtype, int64_t chunk,
  *        (flat element index / 8, step); element l*d+j uses 16-bit field (l*d+j) % 8).  The
  *        updated weights depend on (seed, step) only -- not on chunk or launch geometry.
  * dX_out [B, d] BF16 input gradient, or NULL.  loss_out: one float, the summed BCE loss
- *        sum(softplus(z) - y z) over the batch and all labels, or NULL. */
+ *        sum(softplus(z) - y z) over the batch and all labels, or NULL.
+ * The call only enqueues kernels on hip_stream (no allocation, no memset node, no host
+ * synchronisation unless ELMO_VALIDATE is set), so after one ordinary call it can be captured
+ * into a HIP graph; lr, seed and step are then part of the captured launches. */
 int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const int32_t* indptr,
                    const int32_t* indices, int64_t nnz, float lr, uint64_t seed, uint64_t step,
                    void* dX_out, float* loss_out, void* hip_stream);

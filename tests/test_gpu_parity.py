@@ -441,6 +441,52 @@ def test_weights_do_not_depend_on_chunk_and_steps_repeat(b):
     assert not np.array_equal(case.W(), outs[0][0])
 
 
+def test_step_replays_bit_identically_from_a_hip_graph(b):
+    """A training step only enqueues kernels on the caller's stream (no allocation, no memset node,
+    no host synchronisation without ELMO_VALIDATE), so it can be captured: three replays of a
+    captured step, with eager work and synchronisations between them, leave the same weights,
+    compensation, input gradient and loss as three eager calls with the same arguments."""
+    L, d, B, chunk = 3 * 256 + 77, 256, 300, 512
+    fmt, flags = o.E4M3, o.FLAG_SR | o.FLAG_KAHAN
+    rng = np.random.default_rng(51)
+    X = synth.make_x(rng, B, d)
+    indptr, indices = synth.ZipfLabels(L, 1.0).draw_csr(rng, B, "lognormal5")
+    Xd, ip, ix = dev(X), dev(indptr), dev(indices)
+    results = []
+    for mode in ("eager", "graph"):
+        case = Case(b, L, d, fmt, chunk, flags, B, w_std=0.05, comp_std=2e-4, seed=33)
+        dX = torch.zeros(X.shape, dtype=torch.int16, device=DEV)
+        loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+        case.head.step(Xd, ip, ix, 0.1, 9, 0, dX, loss)            # warm-up: one-time kernel attributes
+        torch.cuda.synchronize()
+        case.load(case.W0, case.C0)
+        side = torch.cuda.Stream()
+        graph = None
+        if mode == "graph":
+            graph = torch.cuda.CUDAGraph()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.graph(graph, stream=side):
+                case.head.step(Xd, ip, ix, 0.1, 9, 4, dX, loss, torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            case.load(case.W0, case.C0)                            # capture does not run the step
+        snaps = []
+        for rep in range(3):
+            if graph is not None:
+                graph.replay()
+            else:
+                case.head.step(Xd, ip, ix, 0.1, 9, 4, dX, loss)
+            torch.cuda.synchronize()
+            scratch = torch.randn(1 << 20, device=DEV).sum().item()   # unrelated eager work between replays
+            snaps.append((case.W().copy(), case.C().copy(), host_u16(dX).copy(), float(loss.item())))
+        results.append(snaps)
+    say("[graph] three replays against three eager steps")
+    for rep in range(3):
+        for a, g_ in zip(results[0][rep][:3], results[1][rep][:3]):
+            assert np.array_equal(a, g_), f"replay {rep} differs from the eager step"
+        assert results[0][rep][3] == results[1][rep][3]
+    assert not np.array_equal(results[0][0][0], results[0][2][0])     # the weights do move from replay to replay
+
+
 def test_rne_cancels_tiny_updates_bit_identically(b):
     """Section 4.1: with nearest rounding an update below half a spacing leaves W untouched."""
     L, d, B = 512, 128, 32
