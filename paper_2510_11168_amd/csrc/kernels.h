@@ -264,19 +264,21 @@ __device__ __forceinline__ void drop_slab(char* tile, uint64_t blk0, uint32_t bl
 // accumulation over the full embedding width, then G = sigmoid(Z) - Y, and stores G^T[l][b] as
 // BF16 (labels x batch, the layout the paper's logits buffer has).  Z never reaches memory.
 // FP8: both operands E4M3, v_mfma_f32_32x32x64_f8f6f4.  BF16: v_mfma_f32_32x32x16_bf16.
-// Epilogue: the positives of the tile's two 128-label bins are turned into a bit mask in LDS, then
-// every thread finishes its accumulators in registers (sigmoid, minus the mask bit, BF16) and
-// writes them transposed into an LDS stage of G^T, from which whole rows are stored coalesced.
+// The positives of the tile's two 128-label bins are turned into a bit mask in LDS before the K
+// loop; afterwards every wave finishes its accumulators in registers (sigmoid, minus the mask
+// bit, BF16), transposes its block through a private LDS area and stores 128-byte segments of
+// G^T rows, without a workgroup barrier.
 // Rows of G^T between n and the next multiple of 128 are written as zeros (the input-gradient
 // product reads whole 64-label slabs).
 // ---------------------------------------------------------------------------------------------
 // TB x TB output tiles: TB = 256, or 128 for padded batches of at most 128 rows, where half of a
 // 256-row tile would be padding and the kernel is bound by the stream of W: 128 x 128 tiles need
 // 66 KiB of LDS, so two workgroups share a CU and one's epilogue overlaps the other's loads.
-template <int TB> constexpr int logits_gpitch() { return (TB + 4) * 2; }            // bytes per staged G^T row (odd multiple of 8)
+constexpr int kGtPitch = 136;                                                        // bytes per staged G^T row segment of 64 samples (odd multiple of 8)
 template <int TB> constexpr int logits_ring_bytes() { return 2 * (TB + TB) * 128; }
-template <int TB> constexpr int logits_mask_offset() {                              // positives mask: behind ring and G^T stage
-  return TB * logits_gpitch<TB>() > logits_ring_bytes<TB>() ? TB * logits_gpitch<TB>() : logits_ring_bytes<TB>();
+template <int TB> constexpr int logits_stage_bytes() { return TB * (TB / 64) * kGtPitch; }   // 8 waves x (their label rows) x pitch
+template <int TB> constexpr int logits_mask_offset() {                              // positives mask: behind ring and G^T stages
+  return logits_stage_bytes<TB>() > logits_ring_bytes<TB>() ? logits_stage_bytes<TB>() : logits_ring_bytes<TB>();
 }
 template <int TB> constexpr int logits_smem() { return logits_mask_offset<TB>() + TB * (TB / 32) * 4 + 32; }
 
@@ -340,13 +342,33 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
          float* __restrict__ loss_slots, uint64_t seed, uint64_t step, uint64_t elem0, DropArgs dr) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int WGN = TB == 256 ? 2 : 4, FN = TB / 32 / WGN;   // waves along the labels, 32-label blocks per wave
-  constexpr int MW = TB / 32, SEGS = TB / 8;
+  constexpr int MW = TB / 32;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave / WGN, wn = wave % WGN;
   const int tiles_b = (Bp + TB - 1) / TB;
   const int wg = xcd_logical_id(blockIdx.x, gridDim.x);
   const int lt = wg / tiles_b, bt = wg % tiles_b;
   const int b0 = bt * TB, l0 = lt * TB;
   const size_t rowb = (size_t)d * (FP8 ? 1 : 2);
+
+  uint32_t* ym = reinterpret_cast<uint32_t*>(smem + logits_mask_offset<TB>());   // [TB labels][MW] bits over the samples
+  float* red = reinterpret_cast<float*>(smem + logits_mask_offset<TB>() + TB * MW * 4);
+  const int rows_out = min(TB, ((n - l0 + 127) >> 7) << 7);              // rows of G^T this tile writes
+  const int gt0 = tile0 + lt * (TB / 128);                               // first of the tile's one or two bins
+
+  // ---- positives of this tile's bins that fall into this batch tile -> bit mask.  The mask lives
+  // behind the ring, so it is built first: its loads overlap the first slabs' way in, and the K
+  // loop's barriers publish it.
+  for (int i = tid; i < TB * MW; i += kGemmThreads) ym[i] = 0u;
+  barrier_lds();
+  {
+    const int p0 = binptr[gt0], p1 = binptr[gt0 + (rows_out >> 7)];
+    for (int p = p0 + tid; p < p1; p += kGemmThreads) {
+      const int2 e = pos[p];
+      const int lr_ = e.x - (gt0 << 7), br = e.y - b0;
+      if (br >= 0 && br < TB && lr_ >= 0 && lr_ < TB) atomicOr(&ym[lr_ * MW + (br >> 5)], 1u << (br & 31));
+    }
+  }
+  barrier_lds();
 
   f32x16 acc[2][FN];
   if constexpr (DROP) {
@@ -360,44 +382,31 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
     logits_tile_product<FP8, TB, FN>(Xa + (size_t)b0 * rowb, a_rows - b0, Wc + (size_t)l0 * rowb, n - l0, rowb, smem, wave, lane, acc);
   }
 
-  constexpr int GP = logits_gpitch<TB>();
-  char* gts = smem;                                                      // G^T stage: TB rows of GP bytes
-  uint32_t* ym = reinterpret_cast<uint32_t*>(smem + logits_mask_offset<TB>());   // [TB labels][MW] bits over the samples
-  float* red = reinterpret_cast<float*>(smem + logits_mask_offset<TB>() + TB * MW * 4);
-  const int rows_out = min(TB, ((n - l0 + 127) >> 7) << 7);              // rows of G^T this tile writes
-  const int gt0 = tile0 + lt * (TB / 128);                               // first of the tile's one or two bins
 
-  // ---- positives of this tile's bins that fall into this batch tile -> bit mask
-  for (int i = tid; i < TB * MW; i += kGemmThreads) ym[i] = 0u;
-  barrier_lds();
-  {
-    const int p0 = binptr[gt0], p1 = binptr[gt0 + (rows_out >> 7)];
-    for (int p = p0 + tid; p < p1; p += kGemmThreads) {
-      const int2 e = pos[p];
-      const int lr_ = e.x - (gt0 << 7), br = e.y - b0;
-      if (br >= 0 && br < TB && lr_ >= 0 && lr_ < TB) atomicOr(&ym[lr_ * MW + (br >> 5)], 1u << (br & 31));
-    }
-  }
-  barrier_lds();
-
-  // ---- G = sigmoid(Z) - Y in registers, BF16, transposed into the stage (4 samples = 8 bytes per write)
+  // ---- G = sigmoid(Z) - Y in registers, BF16, transposed through LDS, stored as row segments.
+  // Each wave finishes its own 64-sample x (32 FN)-label block on its own: it stages the block in
+  // a private LDS area ((32 FN) rows of 128 bytes, 4 samples = 8 bytes per write) and stores
+  // 128-byte segments of G^T rows (8 lanes each).  No workgroup barrier: one wave's stores overlap
+  // another's arithmetic, and this phase is bound by the vector ALU (two transcendental
+  // instructions per value).
   // Positives are a handful per sample among millions of labels: a 32 x 32 block whose mask words
   // are all zero, in a tile without ragged rows, takes the short form (sigmoid only); the wave
-  // votes, so the choice is uniform.  This phase is bound by the vector ALU (two transcendental
-  // instructions per value), so the instructions saved per value count.
+  // votes, so the choice is uniform.
+  constexpr int WROWS = 32 * FN;
+  char* gts = smem + wave * (WROWS * kGtPitch);
   float loss = 0.0f;
   const bool tile_full = n - l0 >= TB;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
-      const int l = wn * 32 * FN + 32 * j + (lane & 31);
+      const int lw = 32 * j + (lane & 31), l = wn * WROWS + lw;
       const bool row_ok = l0 + l < n;
       const uint32_t ybits = (ym[l * MW + 2 * wm + i] >> (4 * (lane >> 5))) & 0x0F0F0F0Fu;
       const bool plain = !LOSS && tile_full && __builtin_amdgcn_ballot_w64(ybits != 0u) == 0ull;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int b = wm * 64 + 32 * i + 8 * q + 4 * (lane >> 5);
+        const int bw = 32 * i + 8 * q + 4 * (lane >> 5), b = wm * 64 + bw;
         float g[4];
         if (plain) {
 #pragma unroll
@@ -414,20 +423,21 @@ k_logits(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wc, i
         uint2 o;
         o.x = pack2_bf16(g[0], g[1]);
         o.y = pack2_bf16(g[2], g[3]);
-        *reinterpret_cast<uint2*>(gts + l * GP + b * 2) = o;
+        *reinterpret_cast<uint2*>(gts + lw * kGtPitch + bw * 2) = o;
       }
     }
-  barrier_lds();
-
-  // ---- coalesced rows of G^T
+  __builtin_amdgcn_s_waitcnt(0xC07F);              // this wave's LDS writes have completed (its lanes read each other's)
+  asm volatile("" ::: "memory");
+  if (b0 + wm * 64 < Bp) {
 #pragma unroll
-  for (int it = 0; it < TB * SEGS / kGemmThreads; ++it) {
-    const int id = it * kGemmThreads + tid;
-    const int row = id / SEGS, seg = id % SEGS;
-    if (row < rows_out && b0 + seg * 8 < Bp) {
-      const uint2 lo = *reinterpret_cast<const uint2*>(gts + row * GP + seg * 16);
-      const uint2 hi = *reinterpret_cast<const uint2*>(gts + row * GP + seg * 16 + 8);
-      *reinterpret_cast<u32x4*>(Gt + (size_t)(l0 + row) * Bp + b0 + seg * 8) = u32x4{lo.x, lo.y, hi.x, hi.y};
+    for (int it = 0; it < WROWS * 8 / 64; ++it) {
+      const int id = it * 64 + lane, r = id >> 3, sgm = id & 7;
+      const int row = wn * WROWS + r;
+      if (row < rows_out) {
+        const uint2 lo = *reinterpret_cast<const uint2*>(gts + r * kGtPitch + sgm * 16);
+        const uint2 hi = *reinterpret_cast<const uint2*>(gts + r * kGtPitch + sgm * 16 + 8);
+        *reinterpret_cast<u32x4*>(Gt + (size_t)(l0 + row) * Bp + b0 + wm * 64 + sgm * 8) = u32x4{lo.x, lo.y, hi.x, hi.y};
+      }
     }
   }
   if (LOSS) {
