@@ -571,8 +571,8 @@ __global__ void __launch_bounds__(kThreads) k_finalize(const float* __restrict__
 // The weight gradient only ever exists as MFMA accumulators and one LDS tile (staged in two
 // halves of 128 columns).
 // ---------------------------------------------------------------------------------------------
-constexpr int kGPitch = 132;
-constexpr int kUpdateEpiBytes = 256 * kGPitch * 4;
+constexpr int kGPitch = 132;                                     // floats per staged gradient row of 128 columns
+constexpr int kUpdateEpiBytes = kGemmWaves * 32 * kGPitch * 4;   // one 32 x 128 FP32 half-block per wave
 constexpr int kUpdateSmem = kUpdateEpiBytes > kWideRingBytes ? kUpdateEpiBytes : kWideRingBytes;
 
 // Sixteen consecutive elements of one weight row: storage bits in, storage bits out.
@@ -652,18 +652,22 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
   const int lt = wg / tiles_j, jt = wg % tiles_j;
   const int l0 = lt << 8, j0 = jt << 8;
   const size_t stride = (size_t)Bp * 2;
-  const bool two_halves = j0 + 128 < d;             // the last column tile of a d = 128 (mod 256) head has one
-
-  // This thread's share of a 256 x 128 half of the weight (and compensation) tile: 4 passes x 16
-  // consecutive columns of one row.  The first half is fetched before the product, the second
-  // one pass at a time while the first half is being updated, so the read-modify-write does not
-  // wait on memory.
-  const int urow = tid >> 3, useg = tid & 7;
+  // Every wave finishes its own 64 (labels) x 128 (columns) block of the tile on its own, in two
+  // halves of 32 labels: per half the lane handles 4 passes x 16 consecutive columns of one row
+  // (row = 8 pass + lane / 8; eight lanes cover the 128 columns of a row, i.e. whole 128-byte
+  // lines of E4M3 weights -- halves of 64 columns measured 3.5 % slower for E4M3 with
+  // compensation and 7 % faster for BF16).  The first half's weights (and compensation) are fetched before
+  // the product, the second half's pass by pass while the first is being updated, so the
+  // read-modify-write does not wait on memory.  A wave whose columns lie beyond d (the last
+  // column tile of a d = 128 (mod 256) head) has nothing to update.
+  const int wl0 = l0 + wm * 64, wj0 = j0 + wn * 128;
+  const bool has_cols = wj0 < d;
+  const int urow = lane >> 3, useg = lane & 7;
   u32x4 wreg[4][WQ];
   u32x4 creg[4][2];
-  auto fetch = [&](int it, int jh) {
-    const int l = min(l0 + it * 64 + urow, n - 1);
-    const size_t eoff = (size_t)l * d + jh + useg * 16;
+  auto fetch = [&](int it, int half) {
+    const int l = min(wl0 + 32 * half + it * 8 + urow, n - 1);
+    const size_t eoff = (size_t)l * d + wj0 + useg * 16;
 #pragma unroll
     for (int q = 0; q < WQ; ++q) wreg[it][q] = *reinterpret_cast<const u32x4*>(Wc + eoff * ESZ + 16 * q);
     if (KAHAN) {
@@ -671,8 +675,10 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
       creg[it][1] = *reinterpret_cast<const u32x4*>(Cc + eoff + 8);
     }
   };
+  if (has_cols) {
 #pragma unroll
-  for (int it = 0; it < 4; ++it) fetch(it, j0);
+    for (int it = 0; it < 4; ++it) fetch(it, 0);
+  }
 
   f32x16 acc[2][4];
   zero_acc(acc);
@@ -694,30 +700,26 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
               acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
         }
       });
+  if (!has_cols) return;                             // after the ring's last barrier: no barrier follows
 
-  float* gs = reinterpret_cast<float*>(smem);
+  // This wave's LDS area: a 32 x 128 FP32 half-block, [label][column], turns the MFMA layout into
+  // 16 consecutive columns per lane.  Nothing below synchronises the workgroup.
+  float* gs = reinterpret_cast<float*>(smem) + wave * (32 * kGPitch);
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
-    if (h && !two_halves) break;                   // the same for the whole workgroup
-    const int jh = j0 + 128 * h;
-    if (h) barrier_lds();                          // the first half has been read out of the stage (no wait for its stores)
-    // ---- stage this half of the gradient tile [label][column] in LDS: the waves that own it write
-    if (wn == h) {
+    asm volatile("" ::: "memory");
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-          for (int v = 0; v < 16; ++v)
-            gs[(wm * 64 + 32 * i + acc_row(v, lane)) * kGPitch + 32 * j + (lane & 31)] = acc[i][j][v];
-    }
-    barrier_lds();
+      for (int v = 0; v < 16; ++v) gs[acc_row(v, lane) * kGPitch + 32 * j + (lane & 31)] = acc[h][j][v];
+    __builtin_amdgcn_s_waitcnt(0xC07F);              // the wave's own LDS writes (its lanes read each other's)
+    asm volatile("" ::: "memory");
 
     // ---- per-element update
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-      const int row = it * 64 + urow;
-      const int l = l0 + row;
+      const int row = it * 8 + urow;
+      const int l = wl0 + 32 * h + row;
       uint32_t w[8], c[8];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
@@ -725,15 +727,15 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
         if (WQ == 2) w[4 + q] = wreg[it][WQ - 1][q];
         if (KAHAN) { c[q] = creg[it][0][q]; c[4 + q] = creg[it][1][q]; }
       }
-      if (h == 0 && two_halves) fetch(it, j0 + 128);
-      if (l >= n) continue;
-      const size_t eoff = (size_t)l * d + jh + useg * 16;
       float g[16];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const f32x4 t = *reinterpret_cast<const f32x4*>(gs + row * kGPitch + useg * 16 + 4 * q);
         g[4 * q] = t[0]; g[4 * q + 1] = t[1]; g[4 * q + 2] = t[2]; g[4 * q + 3] = t[3];
       }
+      if (h == 0) fetch(it, 1);
+      if (l >= n) continue;
+      const size_t eoff = (size_t)l * d + wj0 + useg * 16;
       if (DROP) {
         const U4 mb = drop_block((elem0 + eoff) >> 4, seed, step);
         const uint32_t tb = dr.thresh * 0x01010101u;
