@@ -414,19 +414,11 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
   // ---- step set-up: inputs, zeroed partial sums, label index
   {
     const size_t n = (size_t)Bp * d;
-    elmo::k_prep_x<<<(int)std::min<size_t>((n + 255) / 256, 4096), elmo::kThreads, 0, st>>>((const uint16_t*)X, B, Bp, d, Xq, XT);
-    if (int rc = check_launch("k_prep_x")) return rc;
-    if (dX_out) {
-      const size_t w = (size_t)dx_slices * dx_plane_rows * d;
-      elmo::k_fill_u32<<<(int)std::min<size_t>((w + 255) / 256, 4096), elmo::kThreads, 0, st>>>((uint32_t*)dXacc, w, 0u);
-      if (int rc = check_launch("k_fill_u32")) return rc;
-    }
-    elmo::k_fill_u32<<<(p.ntiles + 1 + 255) / 256, elmo::kThreads, 0, st>>>((uint32_t*)cnt, (size_t)p.ntiles + 1, 0u);
-    if (int rc = check_launch("k_fill_u32")) return rc;
-    if (flag) {
-      elmo::k_fill_u32<<<1, elmo::kThreads, 0, st>>>((uint32_t*)flag, 1, 0u);
-      if (int rc = check_launch("k_fill_u32")) return rc;
-    }
+    const size_t n_dx = dX_out ? (size_t)dx_slices * dx_plane_rows * d : 0;
+    const size_t work = std::max(n, n_dx);
+    elmo::k_step_setup<<<(int)std::min<size_t>((work + 255) / 256, 4096), elmo::kThreads, 0, st>>>(
+        (const uint16_t*)X, B, Bp, d, Xq, XT, (uint32_t*)dXacc, n_dx, (uint32_t*)cnt, (size_t)p.ntiles + 1, (uint32_t*)flag);
+    if (int rc = check_launch("k_step_setup")) return rc;
     const int row_grid = (B * elmo::kRowLanes + elmo::kThreads - 1) / elmo::kThreads;
     elmo::k_label_hist<<<row_grid, elmo::kThreads, 0, st>>>(indptr, indices, B, p.L, nnz, cnt, flag);
     if (int rc = check_launch("k_label_hist")) return rc;

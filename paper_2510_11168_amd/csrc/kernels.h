@@ -53,6 +53,24 @@ __global__ void __launch_bounds__(kThreads) k_prep_x(const uint16_t* __restrict_
   }
 }
 
+// k_prep_x plus the clearing of the step's scratch (input-gradient partial sums, bin counters,
+// validation flag) in one launch: the small heads are bound by the number of launches.
+__global__ void __launch_bounds__(kThreads) k_step_setup(const uint16_t* __restrict__ X, int B, int Bp, int d,
+                                                         uint8_t* __restrict__ Xq, uint16_t* __restrict__ XT,
+                                                         uint32_t* __restrict__ dx_words, size_t n_dx, uint32_t* __restrict__ cnt,
+                                                         size_t n_cnt, uint32_t* __restrict__ flag) {
+  const size_t n = (size_t)Bp * d, stride = (size_t)gridDim.x * kThreads, t0 = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  for (size_t i = t0; i < n; i += stride) {
+    const int b = (int)(i / d), j = (int)(i % d);
+    const uint32_t bits = b < B ? X[i] : 0u;
+    if (Xq) Xq[i] = (uint8_t)e4m3_rne(bf16_decode(bits));
+    XT[(size_t)j * Bp + b] = (uint16_t)bits;
+  }
+  for (size_t i = t0; i < n_dx; i += stride) dx_words[i] = 0u;
+  for (size_t i = t0; i < n_cnt; i += stride) cnt[i] = 0u;
+  if (flag && t0 == 0) *flag = 0u;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Per-batch label index: the positives (CSR by sample) regrouped by 128-label tile, so that the
 // logits epilogue of a tile finds its few positives with two loads (Algorithm 1 filters the
