@@ -139,3 +139,13 @@ def test_create_rejects_missing_or_small_buffers(b):
         b.elmo_head_destroy(None)
     with pytest.raises(b.ElmoError):
         b.elmo_quantize(None, 10, 0, 0, 0, 0, 0, None)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU; asking for more exits with a message (before touching the GPU)."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr or "--gpus 1" in r.stderr
+    assert r.stdout.strip() == ""
