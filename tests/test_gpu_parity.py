@@ -280,6 +280,20 @@ def test_large_batch_kernels_on_ragged_tiles(b, fmt, flags, d, tol):
     check_step(case, X, indptr, indices, 0.1, 17, 3, tol)
 
 
+@pytest.mark.parametrize("d,B", [(1024, 300), (1024, 70), (640, 70), (1536, 130)])
+def test_wider_embeddings(b, d, B):
+    """Embedding widths with four and six 256-column tiles and one that is no multiple of 256
+    (640: the small batch then takes the separate kernels), in both batch regimes."""
+    L, chunk = 2 * 256 + 77, 384
+    fmt, flags = o.E4M3, o.FLAG_SR | o.FLAG_KAHAN
+    case = Case(b, L, d, fmt, chunk, flags, B, w_std=0.05, comp_std=2e-4, seed=41)
+    rng = np.random.default_rng(43)
+    X = synth.make_x(rng, B, d)
+    indptr, indices = synth.ZipfLabels(L, 1.0).draw_csr(rng, B, "lognormal5")
+    say(f"[wide] d={d} B={B} L={L} chunk={chunk}")
+    check_step(case, X, indptr, indices, 0.1, 3, 2, 6e-2)
+
+
 @pytest.mark.parametrize("B", [70, 300])
 def test_kahan_for_head_labels_only(b, B):
     """Compensation on the first 256 labels only, boundary inside the second chunk (384 labels per
