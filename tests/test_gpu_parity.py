@@ -633,14 +633,26 @@ def test_xl_sweep_points_on_samples(b, B, chunk, kahan, dx_rows):
     _full_size_check(b, cfg, cfg.name, dx_rows, 1)
 
 
-def _full_size_check(b, cfg, name, dx_rows, steps):
+def test_xl_config_step_after_twenty_unchecked_steps(b):
+    """BASELINE config 4 runs 20 steps: the first 19 are only run (fresh batch each, as in the
+    benchmark), the 20th is checked against the oracle started from the device state before it --
+    what an error that builds up in the reused workspace or the compensation would break."""
+    _full_size_check(b, synth.CONFIGS["xl"], "xl after 19 steps", 2, 1, unchecked=19)
+
+
+def _full_size_check(b, cfg, name, dx_rows, steps, unchecked=0):
     tol = 6e-2 if cfg.fmt == o.E4M3 else 2e-2
     say(f"[{name}] L={cfg.L} d={cfg.d} B={cfg.B} chunk={cfg.chunk} fmt={cfg.fmt} flags={cfg.flags}: init")
     head = b.Head(cfg.L, cfg.d, cfg.fmt, cfg.chunk, cfg.flags, cfg.B, 64 * cfg.B)
     _init_on_device(b, head, cfg)
     zipf = synth.ZipfLabels(cfg.L, cfg.zipf_s)
     rng = np.random.default_rng(1)
-    for step in range(steps):                 # a second step starts from non-zero compensation
+    for step in range(unchecked):
+        X, indptr, indices = synth.make_batch(cfg, step, zipf)
+        head.step(dev(X), dev(indptr), dev(indices), cfg.lr, 0, step,
+                  torch.zeros(X.shape, dtype=torch.int16, device=DEV), None)
+    torch.cuda.synchronize()
+    for step in range(unchecked, unchecked + steps):   # a second step starts from non-zero compensation
         X, indptr, indices = synth.make_batch(cfg, step, zipf)
         ids = _sample_labels(cfg.L, cfg.chunk, indices, rng, 2048)
         idt = torch.from_numpy(ids).to(DEV)
@@ -649,7 +661,7 @@ def _full_size_check(b, cfg, name, dx_rows, steps):
         Cb = host_u16(head.compensation()[idt]) if head.comp is not None else None
         rows = np.sort(rng.choice(cfg.B, size=dx_rows, replace=False))
         W_all = None
-        if step == 0:
+        if step == unchecked:
             W_all = head.weights().cpu().numpy()
             W_all = W_all.view(np.uint16) if cfg.fmt == o.BF16 else W_all
         Xd, ip, ix = dev(X), dev(indptr), dev(indices)
