@@ -292,27 +292,35 @@ void launch_update(hipStream_t st, int grid, bool sr, bool kahan, const char* Gt
 
 // Small-batch fused input gradient + update.  Returns the launch's dynamic LDS size through the
 // template so that the attribute call and the launch agree.
-template <int FMT, bool SR, bool KAHAN, bool DX, bool WD>
+template <int FMT, bool SR, bool KAHAN, bool DX, bool WD, bool DROP>
 int launch_dx_update_one(hipStream_t st, int grid, const char* Gt, const char* XT, char* Wc, uint16_t* Cc, float* dXacc, int n,
-                         int d, int Bp, float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0, int tpg) {
-  static bool attr_done = false;
-  constexpr int smem = elmo::dxu_smem_bytes<FMT, KAHAN>();
-  if (!attr_done) {
-    ELMO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&elmo::k_dx_update<FMT, SR, KAHAN, DX, WD>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem));
-    attr_done = true;
+                         int d, int Bp, float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0, int tpg, elmo::DropArgs dr) {
+  constexpr int smem = elmo::dxu_smem_bytes<FMT, KAHAN, DROP>();
+  if constexpr (smem > 160 * 1024) {
+    return fail(-3, "internal: no single-pass kernel for this mode");      // the caller takes the separate kernels instead
+  } else {
+    static bool attr_done = false;
+    if (!attr_done) {
+      ELMO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&elmo::k_dx_update<FMT, SR, KAHAN, DX, WD, DROP>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, smem));
+      attr_done = true;
+    }
+    elmo::k_dx_update<FMT, SR, KAHAN, DX, WD, DROP><<<grid, elmo::kGemmThreads, smem, st>>>(Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, wd, seed,
+                                                                                            step, elem0, tpg, dr);
+    return 0;
   }
-  elmo::k_dx_update<FMT, SR, KAHAN, DX, WD><<<grid, elmo::kGemmThreads, smem, st>>>(Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, wd, seed,
-                                                                               step, elem0, tpg);
-  return 0;
 }
 template <int FMT>
 int launch_dx_update(hipStream_t st, int grid, bool sr, bool kahan, bool dx, const char* Gt, const char* XT, char* Wc, uint16_t* Cc,
-                     float* dXacc, int n, int d, int Bp, float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0, int tpg) {
-#define ELMO_DXU(SR_, KA_, DX_)                                                                                                     \
-  do {                                                                                                                               \
-    if (wd != 0.0f) return launch_dx_update_one<FMT, SR_, KA_, DX_, true>(st, grid, Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, wd, seed, step, elem0, tpg); \
-    return launch_dx_update_one<FMT, SR_, KA_, DX_, false>(st, grid, Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, wd, seed, step, elem0, tpg);              \
+                     float* dXacc, int n, int d, int Bp, float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0, int tpg,
+                     elmo::DropArgs dr) {
+#define ELMO_DXU3(SR_, KA_, DX_, WD_) \
+  return dr.thresh ? launch_dx_update_one<FMT, SR_, KA_, DX_, WD_, true>(st, grid, Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, wd, seed, step, elem0, tpg, dr) \
+                   : launch_dx_update_one<FMT, SR_, KA_, DX_, WD_, false>(st, grid, Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, wd, seed, step, elem0, tpg, dr)
+#define ELMO_DXU(SR_, KA_, DX_)                 \
+  do {                                          \
+    if (wd != 0.0f) ELMO_DXU3(SR_, KA_, DX_, true); \
+    ELMO_DXU3(SR_, KA_, DX_, false);            \
   } while (0)
   if (sr && kahan && dx) ELMO_DXU(true, true, true);
   if (sr && kahan) ELMO_DXU(true, true, false);
@@ -323,6 +331,7 @@ int launch_dx_update(hipStream_t st, int grid, bool sr, bool kahan, bool dx, con
   if (dx) ELMO_DXU(false, false, true);
   ELMO_DXU(false, false, false);
 #undef ELMO_DXU
+#undef ELMO_DXU3
 }
 
 // Opt in to more than 64 KiB of dynamic LDS for the tile kernels (done once per process).
@@ -397,9 +406,9 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
   int* flag = (p.flags & ELMO_VALIDATE) ? (int*)(h->ws + p.off_flag) : nullptr;
 
   // Small batches are bound by memory traffic: input gradient and update share one pass over W
-  // (not with dropout: the fused kernel updates the weights from the tile its product reads, and
-  // the product would need that tile masked).
-  const bool small_batch = Bp <= 128 && d % 256 == 0 && !p.drop_thresh;
+  // With dropout that kernel keeps a masked copy of the W tile in LDS, which does not fit next to
+  // BF16 weights with compensation: that one mode takes the separate kernels.
+  const bool small_batch = Bp <= 128 && d % 256 == 0 && !(p.drop_thresh && !fp8 && (p.flags & ELMO_KAHAN));
   const int col_blocks = d / 256, label_groups = small_batch ? 256 / col_blocks : 0;
   // label slices of the input-gradient product: at most one 512-thread workgroup per CU, so the
   // whole grid is resident at once (256 CUs) and no second, nearly empty round of workgroups runs
@@ -469,8 +478,8 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
         char* Wp = Wc + (size_t)l_off * d * esz;
         uint16_t* Cp = kahan ? Cc + (size_t)l_off * d : nullptr;
         int rc;
-        if (fp8) rc = launch_dx_update<elmo::FMT_E4M3>(st, groups_used * col_blocks, sr, kahan, dX_out != nullptr, Gp, (const char*)XT, Wp, Cp, dXacc, n_part, d, Bp, lr, p.weight_decay, seed, step, elem0, tpg);
-        else rc = launch_dx_update<elmo::FMT_BF16>(st, groups_used * col_blocks, sr, kahan, dX_out != nullptr, Gp, (const char*)XT, Wp, Cp, dXacc, n_part, d, Bp, lr, p.weight_decay, seed, step, elem0, tpg);
+        if (fp8) rc = launch_dx_update<elmo::FMT_E4M3>(st, groups_used * col_blocks, sr, kahan, dX_out != nullptr, Gp, (const char*)XT, Wp, Cp, dXacc, n_part, d, Bp, lr, p.weight_decay, seed, step, elem0, tpg, dr);
+        else rc = launch_dx_update<elmo::FMT_BF16>(st, groups_used * col_blocks, sr, kahan, dX_out != nullptr, Gp, (const char*)XT, Wp, Cp, dXacc, n_part, d, Bp, lr, p.weight_decay, seed, step, elem0, tpg, dr);
         if (rc) return rc;
         if (int rc2 = check_launch("k_dx_update")) return rc2;
       }

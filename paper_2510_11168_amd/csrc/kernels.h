@@ -795,18 +795,22 @@ template <int FMT, bool KAHAN> constexpr int dxu_stage_bytes() {
   return 32 * 256 * (FMT == FMT_E4M3 ? 1 : 2) + 32 * 256 + (KAHAN ? 32 * 512 : 0);
 }
 constexpr int kDxuGsBytes = 32 * 260 * 4;
-template <int FMT, bool KAHAN> constexpr int dxu_smem_bytes() { return kStages * dxu_stage_bytes<FMT, KAHAN>() + kDxuGsBytes; }
+// With dropout one more W tile: the masked copy the input-gradient product reads (the update
+// needs the stored weights, so the tile cannot be masked in place).
+template <int FMT, bool KAHAN, bool DROP = false> constexpr int dxu_smem_bytes() {
+  return kStages * dxu_stage_bytes<FMT, KAHAN>() + kDxuGsBytes + (DROP ? 32 * 256 * (FMT == FMT_E4M3 ? 1 : 2) : 0);
+}
 
 // The body is a separate inlined function with restrict-qualified parameters on purpose: inlining
 // it tags every LDS access inside with alias information, without which the compiler puts a full
 // vmcnt(0) wait in front of the transposing LDS reads (it cannot tell them from the asynchronous
 // loads still in flight for later stages) and the ring stops prefetching.  The waits that are
 // needed are the explicit ones below.
-template <int FMT, bool SR, bool KAHAN, bool DX, bool WD>
+template <int FMT, bool SR, bool KAHAN, bool DX, bool WD, bool DROP>
 __device__ __forceinline__ void dx_update_body(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restrict__ Wc,
                                                uint16_t* __restrict__ Cc, float* __restrict__ dXacc, int n, int d, int Bp,
                                                float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0, int tiles_per_group,
-                                               char* smem) {
+                                               DropArgs dr, char* smem) {
   constexpr int ESZ = FMT == FMT_E4M3 ? 1 : 2;
   constexpr int WROWB = 256 * ESZ;
   constexpr int WBYTES = 32 * WROWB, GBYTES = 32 * 256, SBYTES = dxu_stage_bytes<FMT, KAHAN>();
@@ -823,6 +827,7 @@ __device__ __forceinline__ void dx_update_body(const char* __restrict__ Gt, cons
   const int KS = Bp >> 4;                                   // k16 steps over the batch: 4 or 8
   char* ring = smem;
   float* gs = reinterpret_cast<float*>(smem + kStages * SBYTES);
+  char* wmk = smem + kStages * SBYTES + kDxuGsBytes;          // DROP: masked copy of the current W tile
 
   // X^T fragments of this wave's 32 columns (B operand of grad = G^T X), resident for the kernel
   bf16x8 xt[8];
@@ -865,6 +870,45 @@ __device__ __forceinline__ void dx_update_body(const char* __restrict__ Gt, cons
     const char* gsl = ws + WBYTES;
     const char* cs = gsl + GBYTES;
     const int l0 = t << 5;
+    const int l = tid >> 4, seg = tid & 15;                 // this thread's part of the tile: one label row, 16 consecutive columns
+    const size_t eoff = (size_t)(l0 + l) * d + j0 + seg * 16;
+    uint32_t w[8], km[4];
+    auto load_w = [&]() {
+      if (FMT == FMT_E4M3) {
+        const u32x4 t4 = *reinterpret_cast<const u32x4*>(ws + tile_off<WROWB>(l, seg));
+        w[0] = t4[0]; w[1] = t4[1]; w[2] = t4[2]; w[3] = t4[3];
+      } else {
+        const u32x4 ta = *reinterpret_cast<const u32x4*>(ws + tile_off<WROWB>(l, 2 * seg));
+        const u32x4 tb = *reinterpret_cast<const u32x4*>(ws + tile_off<WROWB>(l, 2 * seg + 1));
+        w[0] = ta[0]; w[1] = ta[1]; w[2] = ta[2]; w[3] = ta[3]; w[4] = tb[0]; w[5] = tb[1]; w[6] = tb[2]; w[7] = tb[3];
+      }
+    };
+    if (DROP) {
+      // the step's keep mask of these 16 elements (appendix "Low-Memory Dropout for Classifier"):
+      // the input-gradient product reads a masked copy, the update below masks the gradient
+      load_w();
+      const U4 mb = drop_block((elem0 + eoff) >> 4, seed, step);
+      const uint32_t tb = dr.thresh * 0x01010101u;
+      km[0] = keep_bytes(mb.x, tb); km[1] = keep_bytes(mb.y, tb); km[2] = keep_bytes(mb.z, tb); km[3] = keep_bytes(mb.w, tb);
+      if (DX) {
+        if (FMT == FMT_E4M3) {
+          *reinterpret_cast<u32x4*>(wmk + tile_off<WROWB>(l, seg)) = u32x4{w[0] & km[0], w[1] & km[1], w[2] & km[2], w[3] & km[3]};
+        } else {
+          u32x4 a, b;
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            a[2 * q] = w[2 * q] & __builtin_amdgcn_perm(km[q], km[q], 0x01010000u);
+            a[2 * q + 1] = w[2 * q + 1] & __builtin_amdgcn_perm(km[q], km[q], 0x03030202u);
+            b[2 * q] = w[4 + 2 * q] & __builtin_amdgcn_perm(km[2 + q], km[2 + q], 0x01010000u);
+            b[2 * q + 1] = w[5 + 2 * q] & __builtin_amdgcn_perm(km[2 + q], km[2 + q], 0x03030202u);
+          }
+          *reinterpret_cast<u32x4*>(wmk + tile_off<WROWB>(l, 2 * seg)) = a;
+          *reinterpret_cast<u32x4*>(wmk + tile_off<WROWB>(l, 2 * seg + 1)) = b;
+        }
+        barrier_lds();
+      }
+    }
+    const char* wdx = DROP ? wmk : ws;                      // what the input-gradient product reads
 
     // grad[32 labels x 32 columns of this wave] = G^T X
     f32x16 wa;
@@ -880,8 +924,8 @@ __device__ __forceinline__ void dx_update_body(const char* __restrict__ Gt, cons
         const bf16x8 a = frag_tr_bf16<256>(gsl, 16 * kk, 32 * bt, lane);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const bf16x8 b = FMT == FMT_E4M3 ? frag_tr_fp8<WROWB>(ws, 16 * kk, 128 * jh + 32 * q, lane)
-                                           : frag_tr_bf16<WROWB>(ws, 16 * kk, 128 * jh + 32 * q, lane);
+          const bf16x8 b = FMT == FMT_E4M3 ? frag_tr_fp8<WROWB>(wdx, 16 * kk, 128 * jh + 32 * q, lane)
+                                           : frag_tr_bf16<WROWB>(wdx, 16 * kk, 128 * jh + 32 * q, lane);
           dxa[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, dxa[q], 0, 0, 0);
         }
       }
@@ -890,19 +934,10 @@ __device__ __forceinline__ void dx_update_body(const char* __restrict__ Gt, cons
     for (int v = 0; v < 16; ++v) gs[acc_row(v, lane) * 260 + 32 * wave + (lane & 31)] = wa[v];
     barrier_lds();
 
-    // per-element update: thread -> one label row, 16 consecutive columns
-    const int l = tid >> 4, seg = tid & 15;
+    // per-element update
     if (l0 + l < n) {
-      const size_t eoff = (size_t)(l0 + l) * d + j0 + seg * 16;
-      uint32_t w[8], cc[8];
-      if (FMT == FMT_E4M3) {
-        const u32x4 t4 = *reinterpret_cast<const u32x4*>(ws + tile_off<WROWB>(l, seg));
-        w[0] = t4[0]; w[1] = t4[1]; w[2] = t4[2]; w[3] = t4[3];
-      } else {
-        const u32x4 ta = *reinterpret_cast<const u32x4*>(ws + tile_off<WROWB>(l, 2 * seg));
-        const u32x4 tb = *reinterpret_cast<const u32x4*>(ws + tile_off<WROWB>(l, 2 * seg + 1));
-        w[0] = ta[0]; w[1] = ta[1]; w[2] = ta[2]; w[3] = ta[3]; w[4] = tb[0]; w[5] = tb[1]; w[6] = tb[2]; w[7] = tb[3];
-      }
+      uint32_t cc[8];
+      if (!DROP) load_w();
       if (KAHAN) {
         const u32x4 ta = *reinterpret_cast<const u32x4*>(cs + tile_off<512>(l, 2 * seg));
         const u32x4 tb = *reinterpret_cast<const u32x4*>(cs + tile_off<512>(l, 2 * seg + 1));
@@ -913,6 +948,10 @@ __device__ __forceinline__ void dx_update_body(const char* __restrict__ Gt, cons
       for (int q = 0; q < 4; ++q) {
         const f32x4 t4 = *reinterpret_cast<const f32x4*>(gs + l * 260 + seg * 16 + 4 * q);
         gr[4 * q] = t4[0]; gr[4 * q + 1] = t4[1]; gr[4 * q + 2] = t4[2]; gr[4 * q + 3] = t4[3];
+      }
+      if (DROP) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) gr[i] = ((km[i >> 2] >> (8 * (i & 3))) & 1u) ? gr[i] * dr.scale : 0.0f;
       }
       U4 rb[2];
       if (SR) {
@@ -932,19 +971,25 @@ __device__ __forceinline__ void dx_update_body(const char* __restrict__ Gt, cons
   }
   if (DX) {
     float* out = dXacc + (size_t)g * 128 * d;
+    if (DROP) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) dxa[q][v] *= dr.scale;
+    }
 #pragma unroll
     for (int q = 0; q < 4; ++q)
       add_acc_to_global(out + (size_t)(32 * bt) * d + j0 + 128 * jh + 32 * q, d, lane, dxa[q]);
   }
 }
 
-template <int FMT, bool SR, bool KAHAN, bool DX, bool WD>
+template <int FMT, bool SR, bool KAHAN, bool DX, bool WD, bool DROP>
 __global__ void __launch_bounds__(kGemmThreads, 1)
 k_dx_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restrict__ Wc, uint16_t* __restrict__ Cc,
             float* __restrict__ dXacc, int n, int d, int Bp, float lr, float wd, uint64_t seed, uint64_t step, uint64_t elem0,
-            int tiles_per_group) {
+            int tiles_per_group, DropArgs dr) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  dx_update_body<FMT, SR, KAHAN, DX, WD>(Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, wd, seed, step, elem0, tiles_per_group, smem);
+  dx_update_body<FMT, SR, KAHAN, DX, WD, DROP>(Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, wd, seed, step, elem0, tiles_per_group, dr, smem);
 }
 
 // ---------------------------------------------------------------------------------------------

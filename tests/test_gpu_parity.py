@@ -362,6 +362,10 @@ def test_weight_decay(b, fmt, flags, B):
     (o.BF16, o.FLAG_KAHAN, 300, 256, 26),
     (o.BF16, o.FLAG_SR, 70, 128, 200),
     (o.BF16, 0, 300, 384, 128),
+    (o.E4M3, o.FLAG_SR | o.FLAG_KAHAN, 70, 512, 77),     # single-pass small-batch kernel with its masked tile copy
+    (o.BF16, o.FLAG_SR, 100, 256, 128),                  # the same, BF16 weights
+    (o.BF16, o.FLAG_KAHAN, 70, 256, 128),                # BF16 + compensation: no room for the copy, separate kernels
+    (o.E4M3, 0, 40, 256, 200),
 ])
 def test_classifier_dropout(b, fmt, flags, B, d, T):
     """Dropout on the weights inside the three products: the library regenerates the oracle's mask
