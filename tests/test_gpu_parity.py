@@ -576,6 +576,32 @@ def test_label_index_with_long_rows_crowded_bins_and_far_labels(b):
     assert abs(loss - o.bce_loss(Z, Y)) / o.bce_loss(Z, Y) < 2e-3
 
 
+@pytest.mark.parametrize("fmt,flags", [(o.E4M3, o.FLAG_SR | o.FLAG_KAHAN), (o.E4M3, 0), (o.BF16, o.FLAG_SR)])
+def test_saturating_updates_clip_to_the_largest_finite_value(b, fmt, flags):
+    """A learning rate so large that most updates leave the format's range: the result clips to the
+    largest finite value on both sides (no NaN, no infinity), rounding mode and compensation included."""
+    L, d, B, chunk = 3 * 128 + 50, 256, 70, 256
+    lr = 3.0e5 if fmt == o.E4M3 else 3.0e38     # BF16: products around the top of the FP32 range, some beyond it
+    case = Case(b, L, d, fmt, chunk, flags, B, w_std=0.05, seed=61)
+    rng = np.random.default_rng(63)
+    X = synth.make_x(rng, B, d)
+    indptr, indices = synth.ZipfLabels(L, 1.0).draw_csr(rng, B, "lognormal5")
+    say(f"[saturation] fmt={fmt} flags={flags} lr={lr:g}")
+    with np.errstate(over="ignore", invalid="ignore"):
+        ref = o.head_step(case.W0, case.C0, X, indptr, indices, lr, 2, 0, fmt, flags)
+    case.step(X, indptr, indices, lr, 2, 0)
+    Wn = case.W()
+    top = 0x7E if fmt == o.E4M3 else 0x7F7F
+    mag = (Wn & 0x7F) if fmt == o.E4M3 else (Wn & 0x7FFF)
+    clipped = float(np.mean(mag == top))
+    say(f"   {clipped:.3f} of the weights sit at the largest finite value")
+    assert np.all(mag <= top) and (clipped > 0.5 or fmt == o.BF16)      # finite everywhere; E4M3 mostly at +-448
+    dist = np.abs(ordered(Wn, fmt) - ordered(ref["W_new"], fmt))
+    # the sign of a clipped weight is the sign of a large FP32 sum, which both sides agree on
+    # except where the gradient itself is within rounding of zero
+    assert np.mean(dist <= 1) >= 0.999
+
+
 def test_validation_flag_reports_bad_labels_on_the_next_call(b):
     """Bad label ids are caught by the kernels' own bounds checks (nothing faults) and surface
     as error -4 on the following call."""
