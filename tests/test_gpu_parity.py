@@ -67,6 +67,28 @@ def rel_fro(a, ref):
     return float(np.linalg.norm(np.asarray(a, np.float64) - ref) / max(np.linalg.norm(ref), 1e-300))
 
 
+# dX: the contract is a relative Frobenius error of 2e-2 (BF16) / 6e-2 (FP8) over the whole matrix.
+# One completely wrong sample row of a 1024-row batch moves that norm by only 1/32, so the bound is
+# also taken row by row, and both are held to what the arithmetic gives when the two sides start
+# from the same bits: G and dX_out are rounded to BF16 (unit roundoff 2^-9), measured 1.7e-3.
+DX_SHARP, DX_SHARP_ROW = 6e-3, 1e-2
+
+
+def row_errors(a, ref):
+    a, ref = np.atleast_2d(np.asarray(a, np.float64)), np.atleast_2d(ref)
+    num, den = np.linalg.norm(a - ref, axis=1), np.linalg.norm(ref, axis=1)
+    return np.where(den > 0, num / np.where(den > 0, den, 1.0), np.where(num > 0, np.inf, 0.0))
+
+
+def assert_dx_close(dX, ref, tol, what="dX"):
+    """Whole-matrix contract bound, the same-operand bound, and the same-operand bound per row."""
+    e, rows = rel_fro(dX, ref), row_errors(dX, ref)
+    say(f"   {what}: rel-Fro {e:.2e}; worst row {rows.max():.2e} (row {int(rows.argmax())} of {len(rows)})")
+    assert e <= tol and e <= DX_SHARP, f"{what}: relative Frobenius error {e:.3e}"
+    assert rows.max() <= DX_SHARP_ROW, f"{what}: row {int(rows.argmax())} is off by {rows.max():.3e}"
+    return e
+
+
 # --------------------------------------------------------------------------------- quantisers
 def _quant_inputs():
     rng = np.random.default_rng(11)
@@ -212,12 +234,11 @@ def check_step(case, X, indptr, indices, lr, seed, step, tol, W_before=None, C_b
     dist = np.abs(ordered(Wn, case.fmt) - ordered(ref["W_new"], case.fmt))
     frac_exact = float(np.mean(dist == 0))
     frac_1ulp = float(np.mean(dist <= 1))
-    e_dx = rel_fro(dX, ref["dX_partial"])
     e_loss = abs(loss - ref["loss"]) / abs(ref["loss"])
-    say(f"   W': exact {frac_exact:.5f}, within 1 ulp {frac_1ulp:.6f}, max {dist.max()};  dX rel-Fro {e_dx:.2e};  loss rel {e_loss:.2e}")
+    say(f"   W': exact {frac_exact:.5f}, within 1 ulp {frac_1ulp:.6f}, max {dist.max()};  loss rel {e_loss:.2e}")
     assert frac_1ulp >= 0.999
     assert_far_misses_are_tiny(Wn, ref["W_new"], dist, case.fmt, lr)
-    assert e_dx <= tol
+    assert_dx_close(dX, ref["dX_partial"], tol)
     assert e_loss <= 2e-3
     if case.flags & o.FLAG_KAHAN:
         # compensation: compare the value the pair (w', c') represents, w' - c', with the oracle's
@@ -314,10 +335,10 @@ def test_kahan_for_head_labels_only(b, B):
     ref = o.head_step(case.W0, C_pad, X, indptr, indices, 0.1, 3, 5, fmt, flags, kahan_rows=k)
     Wn = case.W()
     dist = np.abs(ordered(Wn, fmt) - ordered(ref["W_new"], fmt))
-    say(f"   W': within 1 ulp head {np.mean(dist[:k] <= 1):.6f}, rest {np.mean(dist[k:] <= 1):.6f};  dX rel-Fro {rel_fro(dX, ref['dX_partial']):.2e}")
+    say(f"   W': within 1 ulp head {np.mean(dist[:k] <= 1):.6f}, rest {np.mean(dist[k:] <= 1):.6f}")
     assert np.mean(dist[:k] <= 1) >= 0.999 and np.mean(dist[k:] <= 1) >= 0.999
     assert_far_misses_are_tiny(Wn, ref["W_new"], dist, fmt, 0.1)
-    assert rel_fro(dX, ref["dX_partial"]) <= 6e-2
+    assert_dx_close(dX, ref["dX_partial"], 6e-2)
     same = dist[:k] == 0
     cg, cr = o.decode_bf16(case.C()), o.decode_bf16(ref["comp_new"][:k])
     scale = np.maximum(np.abs(o.decode(ref["W_new"][:k], fmt)), 2.0**-9)
@@ -352,7 +373,7 @@ def test_weight_decay(b, fmt, flags, B):
     assert moved > 0.01
     assert np.mean(dist <= 1) >= 0.999
     assert_far_misses_are_tiny(Wn, ref["W_new"], dist, fmt, lr)
-    assert rel_fro(dX, ref["dX_partial"]) <= 6e-2
+    assert_dx_close(dX, ref["dX_partial"], 6e-2 if fmt == o.E4M3 else 2e-2)
 
 
 @pytest.mark.parametrize("fmt,flags,B,d,T", [
@@ -391,7 +412,7 @@ def test_classifier_dropout(b, fmt, flags, B, d, T):
     assert rel_fro(plain["dX_partial"], ref["dX_partial"]) > 0.2        # the mask matters at this rate
     assert np.mean(dist <= 1) >= 0.999
     assert_far_misses_are_tiny(Wn, ref["W_new"], dist, fmt, lr)
-    assert e_dx <= (6e-2 if fmt == o.E4M3 else 2e-2)
+    assert_dx_close(dX, ref["dX_partial"], 6e-2 if fmt == o.E4M3 else 2e-2)
     assert e_loss <= 2e-3
     if flags == 0:
         keep = o.dropout_keep(77, 4, np.arange(L * d, dtype=np.int64).reshape(L, d), T)
@@ -429,9 +450,34 @@ def test_same_operand_error_is_at_bf16_roundoff(b):
     say("[same-operand] E4M3 L=2048 d=256 B=128")
     dX, _ = case.step(X, indptr, indices, 0.05, 1, 1)
     ref = o.head_step(case.W0, None, X, indptr, indices, 0.05, 1, 1, o.E4M3, o.FLAG_SR)
-    e = rel_fro(dX, ref["dX_partial"])
-    say(f"   dX rel-Fro {e:.2e}")
-    assert e <= 6e-3
+    assert_dx_close(dX, ref["dX_partial"], 6e-2)
+
+
+@pytest.mark.parametrize("fmt,flags,B", [
+    (o.E4M3, o.FLAG_SR | o.FLAG_KAHAN, 256), (o.E4M3, o.FLAG_SR | o.FLAG_KAHAN, 96), (o.BF16, o.FLAG_SR, 256), (o.BF16, o.FLAG_KAHAN, 96)])
+def test_which_logit_gradient_the_kernels_compute(b, fmt, flags, B):
+    """The logit gradient G = sigmoid(Z) - Y is held in 16 bits (Section 4.4 keeps the per-chunk
+    logit-gradient buffer in 16 bits for BF16 and FP8 training; Algorithm 1 forms sigmoid and the
+    "-1" in that buffer), so the oracle rounds its FP64 G once to BF16.  This test shows what that
+    reading is worth: the same GPU step is compared with the oracle as it stands and with the oracle
+    that keeps G in FP64 (g_exact).  The kernels must match the first at least as well as the second;
+    the figures of both are printed for the record."""
+    L, d, chunk, lr = 4096 + 77, 256, 1024, 0.05
+    case = Case(b, L, d, fmt, chunk, flags, B, w_std=0.02, seed=71)
+    rng = np.random.default_rng(72)
+    X = synth.make_x(rng, B, d)
+    indptr, indices = synth.ZipfLabels(L, 1.05).draw_csr(rng, B, "poisson7")
+    dX, _ = case.step(X, indptr, indices, lr, 5, 3)
+    Wn = case.W()
+    out = {}
+    for name, exact in (("G rounded to BF16", False), ("G kept in FP64", True)):
+        ref = o.head_step(case.W0, case.C0, X, indptr, indices, lr, 5, 3, fmt, flags, g_exact=exact)
+        dist = np.abs(ordered(Wn, fmt) - ordered(ref["W_new"], fmt))
+        out[exact] = (float(np.mean(dist == 0)), float(np.mean(dist <= 1)), rel_fro(dX, ref["dX_partial"]))
+        say(f"[G reading] fmt={fmt} flags={flags} B={B}  oracle with {name}: W' exact {out[exact][0]:.5f}, "
+            f"within 1 ulp {out[exact][1]:.6f}, dX rel-Fro {out[exact][2]:.2e}")
+    assert out[False][1] >= 0.999
+    assert out[False][0] >= out[True][0] and out[False][2] <= out[True][2] + 1e-4
 
 
 def test_weights_do_not_depend_on_chunk_and_steps_repeat(b):
@@ -571,7 +617,7 @@ def test_label_index_with_long_rows_crowded_bins_and_far_labels(b):
     hot = np.isin(sample, touched)
     assert np.max(np.abs(o.decode(Wn[hot], fmt) - o.decode(ref["W_new"][hot], fmt))) < 1e-3
     dX_ref, Z = o.input_gradient_rows(case.W0, X, indptr, indices, fmt, np.arange(B))
-    assert rel_fro(dX, dX_ref) <= 2e-2
+    assert_dx_close(dX, dX_ref, 2e-2)
     Y = o.csr_to_dense(indptr, indices, L)
     assert abs(loss - o.bce_loss(Z, Y)) / o.bce_loss(Z, Y) < 2e-3
 
@@ -646,7 +692,7 @@ def _init_on_device(b, head, cfg, seed=0):
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("name,dx_rows", [("mid", 8), ("large", 4), ("xl", 2)])
+@pytest.mark.parametrize("name,dx_rows", [("mid", 16), ("large", 16), ("xl", 16)])
 def test_full_size_configs_on_samples(b, name, dx_rows):
     """BASELINE configs 2-4 at full size in the launch configuration the benchmark times.
     Labels are independent given X, so the oracle evaluates a label sample exactly (all in-batch
@@ -654,11 +700,14 @@ def test_full_size_configs_on_samples(b, name, dx_rows):
     _full_size_check(b, synth.CONFIGS[name], name, dx_rows, 2)
 
 
-@pytest.mark.parametrize("B,chunk,kahan,dx_rows", [(128, 262144, True, 2), (32, 65536, True, 2), (4096, 65536, False, 2)])
+@pytest.mark.parametrize("B,chunk,kahan,dx_rows", [
+    (128, 262144, True, 16), (128, 65536, False, 16), (32, 65536, True, 16), (32, 262144, False, 16),
+    (4096, 65536, False, 16), (4096, 262144, True, 16)])
 def test_xl_sweep_points_on_samples(b, B, chunk, kahan, dx_rows):
     """BASELINE config 5 (the bandwidth-regime sweep at 3M labels) at full size, in the launch
-    configurations the benchmark times: the single-pass small-batch kernel at B = 128 and B = 32,
-    the 256 x 256-tile kernels with 16 batch tiles at B = 4096."""
+    configurations the benchmark times: all six (batch, chunk) points -- the small-batch kernels at
+    B = 128 and B = 32, the 256 x 256-tile kernels with 16 batch tiles at B = 4096 -- with the
+    compensation buffer on one chunk size of each batch and off on the other."""
     cfg = synth.xl_sweep(B, chunk, kahan)
     _full_size_check(b, cfg, cfg.name, dx_rows, 1)
 
@@ -684,12 +733,12 @@ def _full_size_check(b, cfg, name, dx_rows, steps, unchecked=0):
     torch.cuda.synchronize()
     for step in range(unchecked, unchecked + steps):   # a second step starts from non-zero compensation
         X, indptr, indices = synth.make_batch(cfg, step, zipf)
-        ids = _sample_labels(cfg.L, cfg.chunk, indices, rng, 2048)
+        ids = _sample_labels(cfg.L, cfg.chunk, indices, rng, 4096)
         idt = torch.from_numpy(ids).to(DEV)
         Wb = head.weights()[idt].cpu().numpy()
         Wb = Wb.view(np.uint16) if cfg.fmt == o.BF16 else Wb
         Cb = host_u16(head.compensation()[idt]) if head.comp is not None else None
-        rows = np.sort(rng.choice(cfg.B, size=dx_rows, replace=False))
+        rows = np.sort(rng.choice(cfg.B, size=min(dx_rows, cfg.B), replace=False))
         W_all = None
         if step == unchecked:
             W_all = head.weights().cpu().numpy()
@@ -718,15 +767,38 @@ def _full_size_check(b, cfg, name, dx_rows, steps, unchecked=0):
             say(f"[{name}] step {step}: oracle dX for rows {rows.tolist()} over all labels")
             dX_ref, _ = o.input_gradient_rows(W_all, X, indptr, indices, cfg.fmt, rows)
             got = o.decode_bf16(host_u16(dX))[rows]
-            e = rel_fro(got, dX_ref)
-            say(f"   dX rows rel-Fro {e:.2e}; loss {loss.item():.6g}")
-            assert e <= tol
+            assert_dx_close(got, dX_ref, tol, f"dX rows (loss {loss.item():.6g})")
             assert np.isfinite(loss.item()) and loss.item() > 0
     head.close()
 
 
 # --------------------------------------------------------------------------------- top-k
-def _check_topk(b, head, Wbits, X, k, fmt, tol):
+# Scores are FP32 sums of exact products (E4M3 x E4M3 and BF16 x BF16 products fit FP32), so they
+# differ from the FP64 logits by the summation rounding only: at most d * 2^-24 of the sum of the
+# terms' magnitudes; measured at most 2e-7 of the largest score.
+TOPK_TOL = 1e-5
+
+
+def assert_topk_row(idx_row, sc_row, z_row, ref_sc_row, eps, L):
+    """One query row against the oracle's logits z_row over all L labels.  Several answers are right
+    when scores tie to within rounding, so: what is unique -- the sorted scores -- must equal the
+    oracle's k best to eps; every returned id must be valid (distinct, in range, reported with its own
+    logit, scoring at least the oracle's k-th value - eps); and the set must be complete: no label
+    whose logit beats the weakest returned one by more than eps may be missing (a result that drops
+    the true best label and returns the (k+1)-th instead fails here)."""
+    k = len(idx_row)
+    assert len(set(idx_row.tolist())) == k and idx_row.min() >= 0 and idx_row.max() < L
+    assert np.all(np.diff(sc_row) <= 0)
+    got_z = z_row[idx_row]
+    assert np.all(np.abs(sc_row - got_z) <= eps), "a score is not its label's logit"
+    assert np.all(got_z >= ref_sc_row[-1] - eps), "a returned label scores below the k-th best"
+    assert np.all(np.abs(sc_row - ref_sc_row) <= eps), "the sorted scores are not the k best"
+    above = np.nonzero(z_row > got_z.min() + eps)[0]
+    missing = np.setdiff1d(above, idx_row)
+    assert missing.size == 0, f"labels {missing[:5].tolist()} beat the weakest returned score and are absent"
+
+
+def _check_topk(b, head, Wbits, X, k, fmt, tol=TOPK_TOL):
     B = X.shape[0]
     idx = torch.zeros((B, k), dtype=torch.int32, device=DEV)
     sc = torch.zeros((B, k), dtype=torch.float32, device=DEV)
@@ -736,16 +808,11 @@ def _check_topk(b, head, Wbits, X, k, fmt, tol):
     Z = o.logits(Wbits, X, fmt)
     ref_idx, ref_sc = o.topk(Z, k)
     exact = float(np.mean(idx == ref_idx))
-    scale = np.abs(ref_sc).max()
-    eps = tol * scale
+    eps = tol * max(np.abs(Z).max(), 1e-30)
     for i in range(B):
-        assert len(set(idx[i].tolist())) == k and idx[i].min() >= 0 and idx[i].max() < Wbits.shape[0]
-        # what is unique: the score multiset (to tolerance); what must be valid: every returned id
-        # scores at least the oracle's k-th value minus eps, and is reported with its own logit
-        assert np.all(Z[i, idx[i]] >= ref_sc[i, -1] - eps)
-        assert np.all(np.abs(sc[i] - Z[i, idx[i]]) <= eps)
-        assert np.all(np.diff(sc[i]) <= 0)
-    say(f"   top-{k}: ids identical to the FP64 order in {exact:.4f} of the slots")
+        assert_topk_row(idx[i], sc[i], Z[i], ref_sc[i], eps, Wbits.shape[0])
+    worst = float(np.abs(sc - np.take_along_axis(Z, idx.astype(np.int64), axis=1)).max())
+    say(f"   top-{k}: ids identical to the FP64 order in {exact:.4f} of the slots; largest score error {worst:.2e} (eps {eps:.2e})")
     return exact
 
 
@@ -756,7 +823,7 @@ def test_topk_small_brute_force(b, fmt):
     X = synth.make_x(np.random.default_rng(1), B, d)
     for k in (1, 5, 100, 128):
         say(f"[topk-small] fmt={fmt} k={k}")
-        _check_topk(b, case.head, case.W0, X, k, fmt, 2e-3 if fmt == o.BF16 else 2e-3)
+        _check_topk(b, case.head, case.W0, X, k, fmt)
 
 
 def test_topk_ties_prefer_smaller_ids(b):
@@ -785,7 +852,7 @@ def test_topk_rising_scores_take_the_unbounded_path(b):
     W = o.round_bf16(ramp.astype(np.float32))
     case.load(W, None)
     say("[topk-rising] L=40000 B=9 k=20")
-    exact = _check_topk(b, case.head, W, X, k, o.BF16, 2e-3)
+    exact = _check_topk(b, case.head, W, X, k, o.BF16)
     assert exact > 0.9
 
 
@@ -823,13 +890,14 @@ def test_topk_mid_size(b):
     W = head.weights().cpu().numpy().view(np.uint16)
     X = synth.make_x(np.random.default_rng(3), 64, cfg.d)
     say("[topk-mid] L=131072 B=64 k=100")
-    _check_topk(b, head, W, X, 100, cfg.fmt, 2e-3)
+    _check_topk(b, head, W, X, 100, cfg.fmt)
 
 
 def test_topk_xl_k100_on_sampled_queries(b):
     """BASELINE config 5, inference part: elmo_head_topk with k = 100 over all 3M logits for 1024
     queries.  Every row is checked for shape properties (distinct ids in range, scores sorted);
-    six sampled rows are checked against the oracle's logits over all labels."""
+    sixteen sampled rows are checked against the oracle's logits over all labels (scores, validity
+    and completeness of the returned set)."""
     cfg = synth.CONFIGS["xl"]
     B, k = 1024, 100
     head = b.Head(cfg.L, cfg.d, cfg.fmt, cfg.chunk, 0, B, 64)
@@ -844,15 +912,14 @@ def test_topk_xl_k100_on_sampled_queries(b):
     assert idx.min() >= 0 and idx.max() < cfg.L
     assert np.all(np.diff(sc, axis=1) <= 0)
     assert all(len(set(r.tolist())) == k for r in idx)
-    rows = np.sort(np.random.default_rng(10).choice(B, size=6, replace=False))
+    rows = np.sort(np.random.default_rng(10).choice(B, size=16, replace=False))
     W = head.weights().cpu().numpy()
     Z = np.empty((len(rows), cfg.L))
     for l0 in range(0, cfg.L, 262144):
         Z[:, l0:l0 + 262144] = o.logits(W[l0:l0 + 262144], X[rows], cfg.fmt)
     ref_idx, ref_sc = o.topk(Z, k)
-    eps = 2e-3 * np.abs(ref_sc).max()
+    eps = TOPK_TOL * np.abs(Z).max()
     for j, i in enumerate(rows):
-        assert np.all(Z[j, idx[i]] >= ref_sc[j, -1] - eps)
-        assert np.all(np.abs(sc[i] - Z[j, idx[i]]) <= eps)
+        assert_topk_row(idx[i], sc[i], Z[j], ref_sc[j], eps, cfg.L)
     say(f"   ids identical to the FP64 order in {np.mean(idx[rows] == ref_idx):.4f} of the sampled slots")
     head.close()
