@@ -88,9 +88,13 @@ int elmo_head_sizes(int64_t L, int32_t d, int weight_dtype, int64_t chunk, int32
 size_t elmo_logit_buffer_bytes(int64_t batch, int64_t labels);
 
 /* Create a head over caller-owned buffers.  Requirements: L >= 1; d a positive multiple of 128, at most 2^20;
- * chunk a positive multiple of 128 (the labels processed per pass, Section 4.2 "chunking"; it need
- * not divide L, the last chunk is short); buffers at least as large as elmo_head_sizes says and
- * 256-byte aligned.  Launches nothing.  *out receives the handle. */
+ * chunk >= 1 (the labels processed per pass, Section 4.2 "chunking"; it need not divide L, the last
+ * chunk is short.  The kernels work on whole 128-label tiles, so a pass takes round_up(chunk, 128)
+ * labels; the updated weights do not depend on the chunk size at all and the input gradient only
+ * through the order of its FP32 sums, so the rounding shows in the workspace size only); buffers at
+ * least as large as elmo_head_sizes says and 256-byte aligned.  Launches nothing.  *out receives the
+ * handle.  Heads may be created and stepped from several host threads (one head per thread at a
+ * time); the library's one-time set-up is guarded. */
 int elmo_head_create(int64_t L, int32_t d, int weight_dtype, int64_t chunk,
                      const elmo_head_opts* opts, elmo_head_t** out);
 
@@ -116,7 +120,10 @@ int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const int32_t* indp
 
 /* Top-k scoring (the top_k of the P@k definition): for each of the B rows of X the k labels with
  * the largest logit over all L labels, ordered by (logit descending, label id ascending).
- * idx_out [B, k] int32, score_out [B, k] float (either may be NULL).  1 <= k <= min(L, 128). */
+ * idx_out [B, k] int32, score_out [B, k] float (either may be NULL).  1 <= k <= L.
+ * Up to k = 128 the labels are swept once; larger k is produced in pages of 128 entries, one more
+ * sweep per page (each page admits only what ranks strictly after the last entry of the page
+ * before it), exact for any k. */
 int elmo_head_topk(elmo_head_t* h, const void* X, int32_t B, int32_t k, int32_t* idx_out,
                    float* score_out, void* hip_stream);
 
@@ -125,7 +132,7 @@ int elmo_head_topk(elmo_head_t* h, const void* X, int32_t B, int32_t k, int32_t*
  * first j entries of idx and among the row's positives, summed over the B rows, j = 1..k; then
  * P@j = hits_out[j-1] / (j * B).  idx [B, k] int32 as written by elmo_head_topk (best first);
  * indptr / indices: the CSR positives of the same B rows (ids ascending within a row); hits_out
- * [k] int64.  All device pointers; 1 <= k <= 128.  Needs no head. */
+ * [k] int64.  All device pointers; 1 <= k <= 2^20 and B * k < 2^31.  Needs no head. */
 int elmo_precision_hits(const int32_t* idx, int32_t B, int32_t k, const int32_t* indptr,
                         const int32_t* indices, int64_t* hits_out, void* hip_stream);
 

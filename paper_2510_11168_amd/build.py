@@ -5,8 +5,7 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-# ELMO_HEAD_LIB points the binding at another build of the same library (e.g. an experiment)
-LIB_PATH = os.environ.get("ELMO_HEAD_LIB") or os.path.join(HERE, "libelmo_head.so")
+LIB_PATH = os.path.join(HERE, "libelmo_head.so")
 SOURCES = [os.path.join(HERE, "csrc", "elmo_head.hip")]
 HEADERS = [os.path.join(HERE, "csrc", h) for h in ("numerics.h", "tiles.h", "kernels.h", "topk.h")] + [
     os.path.join(os.path.dirname(HERE), "include", "elmo_head.h")]

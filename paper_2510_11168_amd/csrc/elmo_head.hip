@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -53,8 +54,12 @@ int make_plan(int64_t L, int d, int fmt, int64_t chunk, int maxB, int64_t max_nn
   if (L > (int64_t)1 << 31) return fail(-1, "L must fit 31 bits (got %lld)", (long long)L);
   if (d < 128 || d % 128 != 0) return fail(-1, "d must be a positive multiple of 128 (got %d)", d);
   if (d > (1 << 20)) return fail(-1, "d must be at most 2^20 (got %d)", d);   // tile loads use 24-bit x 24-bit row offsets
-  if (chunk < 128 || chunk % 128 != 0) return fail(-1, "chunk must be a positive multiple of 128 (got %lld)", (long long)chunk);
+  if (chunk < 1) return fail(-1, "chunk must be >= 1 (got %lld)", (long long)chunk);
   if (chunk > ((int64_t)1 << 30)) return fail(-1, "chunk too large (got %lld)", (long long)chunk);
+  // The kernels work on whole 128-label tiles: a pass takes the next multiple of 128 labels.  The
+  // results do not depend on the chunk size (every label's quantities depend on its own weight row
+  // only), so the rounding only shows in the workspace size.
+  chunk = (chunk + 127) / 128 * 128;
   if (maxB < 1 || maxB > 65536) return fail(-1, "max_B must be in [1, 65536] (got %d)", maxB);
   if (max_nnz < 1 || max_nnz > ((int64_t)1 << 30)) return fail(-1, "max_nnz must be in [1, 2^30] (got %lld)", (long long)max_nnz);
   if (fmt != ELMO_BF16 && fmt != ELMO_FP8_E4M3) return fail(-2, "unsupported weight_dtype %d", fmt);
@@ -73,7 +78,7 @@ int make_plan(int64_t L, int d, int fmt, int64_t chunk, int maxB, int64_t max_nn
   const int tiles_j = (d + 255) / 256;           // 256-column tiles of the input-gradient product
   // slices x padded batch of the input-gradient partials: about one workgroup per CU
   p.dx_rows = std::min(65536 / tiles_j + 256 * p.tiles_b_max + 256, 64 * 256 * p.tiles_b_max);
-  if (d % 256 == 0) p.dx_rows = std::max(p.dx_rows, 256 / (d / 256) * 128);   // small-batch path: one 128-row slice per label group
+  if (d % 256 == 0) p.dx_rows = std::max(p.dx_rows, std::max(1, 256 / (d / 256)) * 128);   // small-batch path: one 128-row slice per label group
   const int64_t chunk_eff = std::min<int64_t>(chunk, (L + 127) / 128 * 128);
   size_t o = 0;
   p.off_xq = o;  o += align256(fmt == ELMO_FP8_E4M3 ? (size_t)p.Bp_max * d : 0);
@@ -299,12 +304,14 @@ int launch_dx_update_one(hipStream_t st, int grid, const char* Gt, const char* X
   if constexpr (smem > 160 * 1024) {
     return fail(-3, "internal: no single-pass kernel for this mode");      // the caller takes the separate kernels instead
   } else {
-    static bool attr_done = false;
-    if (!attr_done) {
-      ELMO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&elmo::k_dx_update<FMT, SR, KAHAN, DX, WD, DROP>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, smem));
-      attr_done = true;
-    }
+    // once per process and instantiation, safe against two host threads stepping two heads
+    static std::once_flag once;
+    static hipError_t attr_rc = hipSuccess;
+    std::call_once(once, [] {
+      attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&elmo::k_dx_update<FMT, SR, KAHAN, DX, WD, DROP>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    });
+    if (attr_rc != hipSuccess) return fail(-3, "hipFuncSetAttribute(k_dx_update) failed: %s", hipGetErrorString(attr_rc));
     elmo::k_dx_update<FMT, SR, KAHAN, DX, WD, DROP><<<grid, elmo::kGemmThreads, smem, st>>>(Gt, XT, Wc, Cc, dXacc, n, d, Bp, lr, wd, seed,
                                                                                             step, elem0, tpg, dr);
     return 0;
@@ -334,10 +341,9 @@ int launch_dx_update(hipStream_t st, int grid, bool sr, bool kahan, bool dx, con
 #undef ELMO_DXU3
 }
 
-// Opt in to more than 64 KiB of dynamic LDS for the tile kernels (done once per process).
-int raise_lds_limits() {
-  static bool done = false;
-  if (done) return 0;
+// Opt in to more than 64 KiB of dynamic LDS for the tile kernels: once per process, whichever
+// host thread comes first (std::call_once below); every caller sees the same outcome.
+int raise_lds_limits_once() {
 #define ELMO_ATTR(k, bytes) ELMO_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))
 #define ELMO_ATTR_LOGITS(F, LO) \
   ELMO_ATTR((elmo::k_logits<F, LO, 256, false>), elmo::logits_smem<256>()); ELMO_ATTR((elmo::k_logits<F, LO, 256, true>), elmo::logits_smem<256>()); \
@@ -370,8 +376,18 @@ int raise_lds_limits() {
   ELMO_ATTR((elmo::k_topk_chunk<true>), elmo::kTopkSmem);
   ELMO_ATTR((elmo::k_topk_chunk<false>), elmo::kTopkSmem);
 #undef ELMO_ATTR
-  done = true;
   return 0;
+}
+int raise_lds_limits() {
+  static std::once_flag once;
+  static int rc = 0;
+  static char text[sizeof g_err];
+  std::call_once(once, [] {
+    rc = raise_lds_limits_once();
+    if (rc) memcpy(text, g_err, sizeof text);      // the error text is thread-local: keep it for later callers
+  });
+  if (rc) memcpy(g_err, text, sizeof g_err);
+  return rc;
 }
 
 }  // namespace
@@ -409,7 +425,7 @@ extern "C" int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const in
   // With dropout that kernel keeps a masked copy of the W tile in LDS, which does not fit next to
   // BF16 weights with compensation: that one mode takes the separate kernels.
   const bool small_batch = Bp <= 128 && d % 256 == 0 && !(p.drop_thresh && !fp8 && (p.flags & ELMO_KAHAN));
-  const int col_blocks = d / 256, label_groups = small_batch ? 256 / col_blocks : 0;
+  const int col_blocks = d / 256, label_groups = small_batch ? std::max(1, 256 / col_blocks) : 0;   // widths above 65536: one group
   // label slices of the input-gradient product: at most one 512-thread workgroup per CU, so the
   // whole grid is resident at once (256 CUs) and no second, nearly empty round of workgroups runs
   int S = std::max(1, 256 / (tiles_b * tiles_j));
@@ -530,7 +546,7 @@ extern "C" int elmo_head_topk(elmo_head_t* h, const void* X, int32_t B, int32_t 
   const Plan& p = h->p;
   if (!X) return fail(-1, "X must not be NULL");
   if (B < 1 || B > p.maxB) return fail(-1, "B = %d outside [1, max_B = %d]", B, p.maxB);
-  if (k < 1 || k > elmo::kTopkMaxK || k > p.L) return fail(-1, "k = %d outside [1, min(L, %d)]", k, elmo::kTopkMaxK);
+  if (k < 1 || k > p.L) return fail(-1, "k = %d outside [1, L = %lld]", k, (long long)p.L);
   if (int rc = poll_validation(h)) return rc;
   if (int rc = raise_lds_limits()) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
@@ -556,7 +572,8 @@ extern "C" int elmo_precision_hits(const int32_t* idx, int32_t B, int32_t k, con
                                    int64_t* hits_out, void* hip_stream) {
   if (!idx || !indptr || !hits_out) return fail(-1, "idx, indptr and hits_out must not be NULL");
   if (B < 1) return fail(-1, "B must be >= 1 (got %d)", B);
-  if (k < 1 || k > elmo::kTopkMaxK) return fail(-1, "k = %d outside [1, %d]", k, elmo::kTopkMaxK);
+  if (k < 1 || k > (1 << 20)) return fail(-1, "k = %d outside [1, 2^20]", k);
+  if ((int64_t)B * k > INT32_MAX) return fail(-1, "B * k = %lld does not fit 31 bits", (long long)B * k);
   hipStream_t st = (hipStream_t)hip_stream;
   unsigned long long* hits = reinterpret_cast<unsigned long long*>(hits_out);
   elmo::k_fill_u32<<<1, elmo::kThreads, 0, st>>>((uint32_t*)hits, (size_t)k * 2, 0u);

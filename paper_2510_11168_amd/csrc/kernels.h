@@ -41,7 +41,7 @@ __global__ void __launch_bounds__(kThreads) k_fill_u32(uint32_t* __restrict__ p,
 
 // Step set-up of the inputs (Algorithm 1: "X.t().to(float8_e4m3fn)"): the E4M3 cast Xq [Bp, d]
 // used by the logits product and the transposed BF16 copy XT [d, Bp] used by the weight-gradient
-// product; rows B..Bp-1 are zero padding.
+// product; rows B..Bp-1 are zero padding.  Either output may be absent.
 __global__ void __launch_bounds__(kThreads) k_prep_x(const uint16_t* __restrict__ X, int B, int Bp, int d,
                                                      uint8_t* __restrict__ Xq, uint16_t* __restrict__ XT) {
   const size_t n = (size_t)Bp * d;
@@ -49,7 +49,7 @@ __global__ void __launch_bounds__(kThreads) k_prep_x(const uint16_t* __restrict_
     const int b = (int)(i / d), j = (int)(i % d);
     const uint32_t bits = b < B ? X[i] : 0u;
     if (Xq) Xq[i] = (uint8_t)e4m3_rne(bf16_decode(bits));
-    XT[(size_t)j * Bp + b] = (uint16_t)bits;
+    if (XT) XT[(size_t)j * Bp + b] = (uint16_t)bits;
   }
 }
 

@@ -12,6 +12,12 @@
 // the label id) is flagged and recomputed by the fallback path below, which has no capacity
 // limit: 64 query rows per workgroup walk a label segment keeping a sorted k-list in LDS, and a
 // merge kernel joins the segments.  Order: score descending, label id ascending on ties.
+//
+// k above 128: the result is produced in pages of 128 entries.  Every page is one more sweep over
+// the labels that only admits (score, id) pairs strictly after the last entry of the page before
+// it in that order (the row's cursor), so page p holds entries 128 p .. 128 p + 127 of the full
+// ranking exactly.  Costs one pass over W per 128 entries; k <= 128 (evaluation uses k <= 100) is
+// a single sweep with no cursor.
 #pragma once
 #include <limits.h>
 
@@ -22,7 +28,7 @@
 
 namespace elmo {
 
-constexpr int kTopkMaxK = 128;
+constexpr int kTopkMaxK = 128;                     // entries selected per sweep (one page)
 constexpr int kTopkCand = 4096;                    // candidate list length per row (main path)
 constexpr int kTopkLevel0 = 2048;                  // labels of the first level; later levels grow 16x
 constexpr int kTopkRows = 64;                       // query rows per workgroup
@@ -37,7 +43,10 @@ inline int topk_segments(int tiles_b) { return std::max(1, std::min(64, 512 / ti
 
 // Main-path scratch: thresholds, counters, overflow flags and candidate lists per (padded) row.
 inline size_t topk_main_rows(int Bp_max) { return (size_t)(Bp_max + 255) / 256 * 256; }
-inline size_t topk_main_bytes(int Bp_max) { return topk_main_rows(Bp_max) * (12 + (size_t)kTopkCand * 8) + 1024; }
+inline size_t topk_main_bytes(int Bp_max) { return topk_main_rows(Bp_max) * (28 + (size_t)kTopkCand * 8) + 1024; }
+
+// (score, id) strictly after the cursor (cs, ci) in the order score descending, id ascending.
+__device__ inline bool topk_after(float z, int l, float cs, int ci) { return z < cs || (z == cs && l > ci); }
 
 // Bytes of per-segment partial lists for any batch of at most Bp_max rows, plus the main path's.
 inline size_t topk_scratch_bytes(int Bp_max, int64_t /*chunk*/) {
@@ -51,7 +60,7 @@ template <bool FP8>
 __global__ void __launch_bounds__(kThreads, 1)
 k_topk_chunk(const char* __restrict__ Xa, int a_rows, const char* __restrict__ W, int64_t L, int d, int k, int P,
              int tiles_per_seg, float* __restrict__ part_sc, int* __restrict__ part_id, const int* __restrict__ only_rows,
-             int B) {
+             int B, const float* __restrict__ cur_sc, const int* __restrict__ cur_id) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   if (only_rows) {   // fallback use: nothing to do unless one of this group's rows is flagged
     const int r = (blockIdx.x / P) * kTopkRows + (threadIdx.x & 63);
@@ -140,11 +149,15 @@ k_topk_chunk(const char* __restrict__ Xa, int a_rows, const char* __restrict__ W
     {  // pre-filter: which of this row-quarter's 32 scores beat the row's current k-th best
       const int r = tid >> 2, q = tid & 3;
       const float tau = lsc[r * kTopkLP + k - 1];
+      const bool paged = cur_sc != nullptr && b0 + r < B;
+      const float cs = paged ? cur_sc[b0 + r] : INFINITY;
+      const int ci = paged ? cur_id[b0 + r] : -1;
       uint32_t m = 0;
 #pragma unroll 8
       for (int e = 0; e < 32; ++e) {
         const int l = 32 * q + e;
-        if (l < vw && zs[r * kTopkZP + l] > tau) m |= 1u << e;
+        const float z = zs[r * kTopkZP + l];
+        if (l < vw && z > tau && (!paged || topk_after(z, (int)l0 + l, cs, ci))) m |= 1u << e;
       }
       hit[r * 4 + q] = m;
     }
@@ -198,9 +211,12 @@ __device__ inline void bitonic_sort_pairs(float* sc, int* id, int N2, int tid) {
 
 // Merge the P per-segment lists of one row: bitonic sort of P*k (padded to a power of two) pairs
 // by (score descending, id ascending), first k written out.
+// Output row pitch out_ld, first column out_off (the page); next_sc / next_id receive the row's new cursor.
 __global__ void __launch_bounds__(kThreads) k_topk_merge(const float* __restrict__ part_sc, const int* __restrict__ part_id,
                                                          int P, int k, int N2, int* __restrict__ idx_out,
-                                                         float* __restrict__ score_out, const int* __restrict__ only_rows) {
+                                                         float* __restrict__ score_out, const int* __restrict__ only_rows,
+                                                         int out_ld, int out_off, float* __restrict__ next_sc,
+                                                         int* __restrict__ next_id) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   float* sc = reinterpret_cast<float*>(smem);
   int* id = reinterpret_cast<int*>(smem + (size_t)N2 * 4);
@@ -220,9 +236,10 @@ __global__ void __launch_bounds__(kThreads) k_topk_merge(const float* __restrict
   __syncthreads();
   bitonic_sort_pairs(sc, id, N2, tid);
   for (int i = tid; i < k; i += kThreads) {
-    if (idx_out) idx_out[(size_t)b * k + i] = id[i];
-    if (score_out) score_out[(size_t)b * k + i] = sc[i];
+    if (idx_out) idx_out[(size_t)b * out_ld + out_off + i] = id[i];
+    if (score_out) score_out[(size_t)b * out_ld + out_off + i] = sc[i];
   }
+  if (tid == 0 && next_sc) { next_sc[b] = sc[k - 1]; next_id[b] = id[k - 1]; }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -244,7 +261,7 @@ template <bool FP8, bool FIRST>
 __global__ void __launch_bounds__(kGemmThreads, 1)
 k_topk_filter(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wl, int n, int l_begin, int d, int Bp, int B,
               const float* __restrict__ tau, int* __restrict__ cnt, int* __restrict__ ovf, float* __restrict__ cand_sc,
-              int* __restrict__ cand_id) {
+              int* __restrict__ cand_id, const float* __restrict__ cur_sc, const int* __restrict__ cur_id) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave >> 1, wn = wave & 1;
   const int tiles_b = (Bp + 255) >> 8;
@@ -255,7 +272,14 @@ k_topk_filter(const char* __restrict__ Xa, int a_rows, const char* __restrict__ 
   f32x16 acc[2][4];
   logits_tile_product<FP8, 256, 4>(Xa + (size_t)b0 * rowb, a_rows - b0, Wl + (size_t)l0 * rowb, n - l0, rowb, smem, wave, lane, acc);
   float* tau_s = reinterpret_cast<float*>(smem);
-  for (int i = tid; i < 256; i += kGemmThreads) tau_s[i] = b0 + i < B ? tau[b0 + i] : INFINITY;   // padding rows never emit
+  float* cs_s = tau_s + 256;                         // the rows' cursors (pages after the first), else +inf / -1
+  int* ci_s = reinterpret_cast<int*>(cs_s + 256);
+  const bool paged = cur_sc != nullptr;
+  for (int i = tid; i < 256; i += kGemmThreads) {
+    tau_s[i] = b0 + i < B ? tau[b0 + i] : INFINITY;   // padding rows never emit
+    cs_s[i] = paged && b0 + i < B ? cur_sc[b0 + i] : INFINITY;
+    ci_s[i] = paged && b0 + i < B ? cur_id[b0 + i] : -1;
+  }
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -270,11 +294,11 @@ k_topk_filter(const char* __restrict__ Xa, int a_rows, const char* __restrict__ 
         const float z = acc[i][j][v];
         if (FIRST) {
           if (l < n && row < B) {
-            const bool live = z > -INFINITY;
+            const bool live = z > -INFINITY && (!paged || topk_after(z, l_begin + l, cs_s[b], ci_s[b]));
             cand_sc[(size_t)row * kTopkCand + l] = live ? z : -INFINITY;
             cand_id[(size_t)row * kTopkCand + l] = live ? l_begin + l : INT_MAX;
           }
-        } else if (l < n && z > t) {
+        } else if (l < n && z > t && (!paged || topk_after(z, l_begin + l, cs_s[b], ci_s[b]))) {
           const int slot = atomicAdd(&cnt[row], 1);
           if (slot < kTopkCand) {
             cand_sc[(size_t)row * kTopkCand + slot] = z;
@@ -290,13 +314,14 @@ k_topk_filter(const char* __restrict__ Xa, int a_rows, const char* __restrict__ 
 // Per row: sort the candidates, keep the k best at the front of the list, raise the threshold.
 __global__ void __launch_bounds__(kThreads) k_topk_select(float* __restrict__ tau, int* __restrict__ cnt, float* __restrict__ cand_sc,
                                                           int* __restrict__ cand_id, int k, int* __restrict__ idx_out,
-                                                          float* __restrict__ score_out) {
+                                                          float* __restrict__ score_out, int out_ld, int out_off,
+                                                          float* __restrict__ next_sc, int* __restrict__ next_id) {
   __shared__ float sc[kTopkCand];
   __shared__ int id[kTopkCand];
   const int b = blockIdx.x, tid = threadIdx.x;
   const int m = min(cnt[b], kTopkCand);
   int N2 = 2;
-  while (N2 < m) N2 <<= 1;
+  while (N2 < max(m, k)) N2 <<= 1;                   // the first k sorted slots are read below even when fewer candidates exist
   for (int i = tid; i < N2; i += kThreads) {
     sc[i] = i < m ? cand_sc[(size_t)b * kTopkCand + i] : -INFINITY;
     id[i] = i < m ? cand_id[(size_t)b * kTopkCand + i] : INT_MAX;
@@ -314,9 +339,10 @@ __global__ void __launch_bounds__(kThreads) k_topk_select(float* __restrict__ ta
   }
   if (idx_out || score_out)
     for (int i = tid; i < k; i += kThreads) {
-      if (idx_out) idx_out[(size_t)b * k + i] = id[i];
-      if (score_out) score_out[(size_t)b * k + i] = sc[i];
+      if (idx_out) idx_out[(size_t)b * out_ld + out_off + i] = id[i];
+      if (score_out) score_out[(size_t)b * out_ld + out_off + i] = sc[i];
     }
+  if (tid == 0 && next_sc) { next_sc[b] = sc[k - 1]; next_id[b] = id[k - 1]; }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -352,36 +378,20 @@ inline int topk_launch_error(const char* what, char* err, size_t errsz) {
 }
 
 inline int topk_run(hipStream_t st, bool fp8, const char* Xa, int a_rows, const char* W, int64_t L, int d, int64_t /*chunk*/,
-                    int B, int Bp, int k, char* scratch, int* idx_out, float* score_out, char* err, size_t errsz) {
-  // ---- main path
+                    int B, int Bp, int k_total, char* scratch, int* idx_out, float* score_out, char* err, size_t errsz) {
   const size_t rows = topk_main_rows(Bp);
   float* tau = reinterpret_cast<float*>(scratch);
   int* cnt = reinterpret_cast<int*>(scratch + rows * 4);
   int* ovf = reinterpret_cast<int*>(scratch + rows * 8);
-  float* cand_sc = reinterpret_cast<float*>(scratch + rows * 12);
-  int* cand_id = reinterpret_cast<int*>(scratch + rows * 12 + rows * (size_t)kTopkCand * 4);
+  float* cursor_sc[2] = {reinterpret_cast<float*>(scratch + rows * 12), reinterpret_cast<float*>(scratch + rows * 16)};
+  int* cursor_id[2] = {reinterpret_cast<int*>(scratch + rows * 20), reinterpret_cast<int*>(scratch + rows * 24)};
+  float* cand_sc = reinterpret_cast<float*>(scratch + rows * 28);
+  int* cand_id = reinterpret_cast<int*>(scratch + rows * 28 + rows * (size_t)kTopkCand * 4);
   char* fb_scratch = scratch + topk_main_bytes(Bp);
   const size_t rowb = (size_t)d * (fp8 ? 1 : 2);
   static_assert(kTopkLevel0 <= kTopkCand, "the first level writes one slot per label");
-  k_topk_init<<<(int)((rows + kThreads - 1) / kThreads), kThreads, 0, st>>>(tau, cnt, ovf, (int)rows,
-                                                                             (int)std::min<int64_t>(L, kTopkLevel0));
-  if (int rc = topk_launch_error("k_topk_init", err, errsz)) return rc;
   const int tiles_b256 = (Bp + 255) / 256;
-  for (int64_t begin = 0, end = std::min<int64_t>(L, kTopkLevel0); begin < L; begin = end, end = std::min<int64_t>(L, end * 17)) {
-    const int n = (int)(end - begin);
-    const int grid = (n + 255) / 256 * tiles_b256;
-    const char* Wl = W + (size_t)begin * rowb;
-    const bool first = begin == 0;
-    if (fp8 && first) k_topk_filter<true, true><<<grid, kGemmThreads, logits_smem<256>(), st>>>(Xa, a_rows, Wl, n, (int)begin, d, Bp, B, tau, cnt, ovf, cand_sc, cand_id);
-    else if (fp8) k_topk_filter<true, false><<<grid, kGemmThreads, logits_smem<256>(), st>>>(Xa, a_rows, Wl, n, (int)begin, d, Bp, B, tau, cnt, ovf, cand_sc, cand_id);
-    else if (first) k_topk_filter<false, true><<<grid, kGemmThreads, logits_smem<256>(), st>>>(Xa, a_rows, Wl, n, (int)begin, d, Bp, B, tau, cnt, ovf, cand_sc, cand_id);
-    else k_topk_filter<false, false><<<grid, kGemmThreads, logits_smem<256>(), st>>>(Xa, a_rows, Wl, n, (int)begin, d, Bp, B, tau, cnt, ovf, cand_sc, cand_id);
-    if (int rc = topk_launch_error("k_topk_filter", err, errsz)) return rc;
-    const bool last = end == L;
-    k_topk_select<<<B, kThreads, 0, st>>>(tau, cnt, cand_sc, cand_id, k, last ? idx_out : nullptr, last ? score_out : nullptr);
-    if (int rc = topk_launch_error("k_topk_select", err, errsz)) return rc;
-  }
-  // ---- fallback for rows whose candidate list overflowed (does nothing when no row is flagged)
+  // fallback geometry (rows whose candidate list overflowed)
   const int tiles_b = (B + kTopkRows - 1) / kTopkRows;
   const int tiles_l = (int)((L + 127) / 128);
   int P = topk_segments(tiles_b);
@@ -394,13 +404,47 @@ inline int topk_run(hipStream_t st, bool fp8, const char* Xa, int a_rows, const 
     snprintf(err, errsz, "top-k scratch plan exceeded");
     return -3;
   }
-  if (fp8) k_topk_chunk<true><<<tiles_b * P, kThreads, kTopkSmem, st>>>(Xa, a_rows, W, L, d, k, P, tps, part_sc, part_id, ovf, B);
-  else k_topk_chunk<false><<<tiles_b * P, kThreads, kTopkSmem, st>>>(Xa, a_rows, W, L, d, k, P, tps, part_sc, part_id, ovf, B);
-  if (int rc = topk_launch_error("k_topk_chunk", err, errsz)) return rc;
-  int N2 = 2;
-  while (N2 < P * k) N2 <<= 1;
-  k_topk_merge<<<B, kThreads, (size_t)N2 * 8, st>>>(part_sc, part_id, P, k, N2, idx_out, score_out, ovf);
-  return topk_launch_error("k_topk_merge", err, errsz);
+  // one sweep over the labels per page of kTopkMaxK entries; pages after the first admit only what
+  // lies strictly after the row's cursor (the last entry of the page before)
+  for (int page = 0, off = 0; off < k_total; ++page, off += kTopkMaxK) {
+    const int k = std::min(kTopkMaxK, k_total - off);
+    const float* cs = page ? cursor_sc[page & 1] : nullptr;
+    const int* ci = page ? cursor_id[page & 1] : nullptr;
+    const bool more = off + k < k_total;
+    float* ns = more ? cursor_sc[(page + 1) & 1] : nullptr;
+    int* ni = more ? cursor_id[(page + 1) & 1] : nullptr;
+    // ---- main path
+    k_topk_init<<<(int)((rows + kThreads - 1) / kThreads), kThreads, 0, st>>>(tau, cnt, ovf, (int)rows,
+                                                                               (int)std::min<int64_t>(L, kTopkLevel0));
+    if (int rc = topk_launch_error("k_topk_init", err, errsz)) return rc;
+    for (int64_t begin = 0, end = std::min<int64_t>(L, kTopkLevel0); begin < L; begin = end, end = std::min<int64_t>(L, end * 17)) {
+      const int n = (int)(end - begin);
+      const int grid = (n + 255) / 256 * tiles_b256;
+      const char* Wl = W + (size_t)begin * rowb;
+      const bool first = begin == 0;
+#define ELMO_TOPK_FILTER(F, FI) \
+  k_topk_filter<F, FI><<<grid, kGemmThreads, logits_smem<256>(), st>>>(Xa, a_rows, Wl, n, (int)begin, d, Bp, B, tau, cnt, ovf, cand_sc, cand_id, cs, ci)
+      if (fp8 && first) ELMO_TOPK_FILTER(true, true);
+      else if (fp8) ELMO_TOPK_FILTER(true, false);
+      else if (first) ELMO_TOPK_FILTER(false, true);
+      else ELMO_TOPK_FILTER(false, false);
+#undef ELMO_TOPK_FILTER
+      if (int rc = topk_launch_error("k_topk_filter", err, errsz)) return rc;
+      const bool last = end == L;
+      k_topk_select<<<B, kThreads, 0, st>>>(tau, cnt, cand_sc, cand_id, k, last ? idx_out : nullptr, last ? score_out : nullptr,
+                                            k_total, off, last ? ns : nullptr, last ? ni : nullptr);
+      if (int rc = topk_launch_error("k_topk_select", err, errsz)) return rc;
+    }
+    // ---- fallback for rows whose candidate list overflowed (does nothing when no row is flagged)
+    if (fp8) k_topk_chunk<true><<<tiles_b * P, kThreads, kTopkSmem, st>>>(Xa, a_rows, W, L, d, k, P, tps, part_sc, part_id, ovf, B, cs, ci);
+    else k_topk_chunk<false><<<tiles_b * P, kThreads, kTopkSmem, st>>>(Xa, a_rows, W, L, d, k, P, tps, part_sc, part_id, ovf, B, cs, ci);
+    if (int rc = topk_launch_error("k_topk_chunk", err, errsz)) return rc;
+    int N2 = 2;
+    while (N2 < P * k) N2 <<= 1;
+    k_topk_merge<<<B, kThreads, (size_t)N2 * 8, st>>>(part_sc, part_id, P, k, N2, idx_out, score_out, ovf, k_total, off, ns, ni);
+    if (int rc = topk_launch_error("k_topk_merge", err, errsz)) return rc;
+  }
+  return 0;
 }
 
 }  // namespace elmo

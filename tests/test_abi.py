@@ -119,7 +119,8 @@ def test_workspace_is_one_chunks_buffer_plus_small_terms(b):
     ((0, 768, 0, 1024, 8, 8, 0), -1),            # L
     ((100, 100, 0, 1024, 8, 8, 0), -1),          # d not a multiple of 128
     ((100, (1 << 20) + 128, 0, 1024, 8, 8, 0), -1),   # d beyond the supported width
-    ((100, 768, 0, 100, 8, 8, 0), -1),           # chunk not a multiple of 128
+    ((100, 768, 0, 0, 8, 8, 0), -1),             # chunk must be positive
+    ((100, 768, 0, -128, 8, 8, 0), -1),
     ((100, 768, 0, 1024, 0, 8, 0), -1),          # max_B
     ((100, 768, 0, 1024, 8, 0, 0), -1),          # max_nnz
     ((100, 768, 7, 1024, 8, 8, 0), -2),          # format
@@ -131,6 +132,33 @@ def test_bad_plans_are_rejected(b, args, code):
     assert e.value.code == code and len(str(e.value)) > 20
 
 
+def test_any_positive_chunk_is_planned_in_whole_128_label_tiles(b):
+    """chunk need not be a multiple of anything: a pass takes the next multiple of 128 labels, and
+    only the workspace size shows it."""
+    L, d, B = 100000, 256, 64
+    sizes = {c: b.elmo_head_sizes(L, d, b.ELMO_BF16, c, B, 512, 0)[2] for c in (1, 100, 128, 129, 256, 1000, 1024)}
+    assert sizes[1] == sizes[100] == sizes[128] and sizes[129] == sizes[256] and sizes[1000] == sizes[1024]
+    assert sizes[256] - sizes[128] == b.elmo_logit_buffer_bytes(B, 128)
+
+
+def test_very_wide_heads_are_planned(b):
+    """Widths above 65536 columns have more column blocks than compute units: the plan still holds one
+    input-gradient slice for the small-batch path (no division by zero on the host)."""
+    _, _, ws = b.elmo_head_sizes(256, 65536 + 256, b.ELMO_FP8_E4M3, 128, 4, 16, b.ELMO_SR)
+    assert ws >= 128 * (65536 + 256) * 4
+
+
+def test_topk_and_hits_argument_checks(b):
+    with pytest.raises(b.ElmoError):
+        b.elmo_precision_hits(None, 4, 5, None, None, None)
+    with pytest.raises(b.ElmoError) as e:
+        b._check(b._lib.elmo_precision_hits(16, 4, 0, 16, 16, 16, None))
+    assert e.value.code == -1
+    with pytest.raises(b.ElmoError) as e:
+        b._check(b._lib.elmo_precision_hits(16, 1 << 20, 1 << 12, 16, 16, 16, None))
+    assert e.value.code == -1
+
+
 def test_create_rejects_missing_or_small_buffers(b):
     with pytest.raises(b.ElmoError) as e:
         b.elmo_head_create(1000, 256, b.ELMO_BF16, 512, flags=0, max_B=8, max_nnz=64, W=None, comp=None, workspace=None)
@@ -139,6 +167,37 @@ def test_create_rejects_missing_or_small_buffers(b):
         b.elmo_head_destroy(None)
     with pytest.raises(b.ElmoError):
         b.elmo_quantize(None, 10, 0, 0, 0, 0, 0, None)
+
+
+def test_host_code_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The library's host side (argument checks, buffer planner, handle life cycle, host Philox and
+    dropout mask) compiled with -fsanitize=address,undefined and driven by tests/abi_host_check.c
+    through the C ABI.  The device side is built as usual (the sanitizers instrument host code only);
+    nothing is launched."""
+    import shutil
+    import subprocess
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    clang = "/opt/rocm/lib/llvm/bin/clang"
+    if not (os.path.exists(hipcc) and os.path.exists(clang)):
+        pytest.skip("no ROCm toolchain")
+    san = ["-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined"]
+    lib = tmp_path / "libelmo_head_san.so"
+    from paper_2510_11168_amd import build
+    cmd = [hipcc, *build.HIPCC_FLAGS, "-g"]
+    for f in san:
+        cmd += ["-Xarch_host", f]
+    cmd += ["-o", str(lib), os.path.join(ROOT, "paper_2510_11168_amd", "csrc", "elmo_head.hip")]
+    r = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stderr[-3000:]
+    exe = tmp_path / "abi_host_check"
+    r = subprocess.run([clang, "-O1", "-g", *san, "-I", os.path.join(ROOT, "include"), os.path.join(ROOT, "tests", "abi_host_check.c"),
+                        "-L", str(tmp_path), "-lelmo_head_san", f"-Wl,-rpath,{tmp_path}", "-o", str(exe)],
+                       capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stderr[-3000:]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=600, env=env)
+    assert r.returncode == 0 and "host-side ABI checks passed" in r.stdout, (r.stdout + r.stderr)[-4000:]
+    assert "Sanitizer" not in r.stderr and "runtime error" not in r.stderr, r.stderr[-4000:]
 
 
 def test_bench_refuses_more_than_one_gpu():

@@ -489,7 +489,7 @@ def test_weights_do_not_depend_on_chunk_and_steps_repeat(b):
     indptr, indices = synth.ZipfLabels(L, 1.0).draw_csr(rng, B, "fixed5")
     flags = o.FLAG_SR | o.FLAG_KAHAN
     outs = []
-    for chunk in (128, 384, 1024):
+    for chunk in (128, 384, 1024, 100, 1, 777):         # any positive chunk: a pass takes the next multiple of 128 labels
         case = Case(b, L, d, o.E4M3, chunk, flags, B, w_std=0.05, seed=1)
         say(f"[chunk-invariance] chunk={chunk}")
         dX, _ = case.step(X, indptr, indices, 0.05, 9, 4)
@@ -824,6 +824,71 @@ def test_topk_small_brute_force(b, fmt):
     for k in (1, 5, 100, 128):
         say(f"[topk-small] fmt={fmt} k={k}")
         _check_topk(b, case.head, case.W0, X, k, fmt)
+
+
+@pytest.mark.parametrize("fmt,L,B,ks", [(o.E4M3, 3000 + 17, 70, (129, 300, 500)), (o.BF16, 300, 9, (256, 300)), (o.E4M3, 131, 3, (131,))])
+def test_topk_beyond_one_page(b, fmt, L, B, ks):
+    """k above 128 comes in pages of 128 entries, every page one more sweep that admits only what
+    ranks strictly after the page before: against the oracle's full sort, up to k = L (the whole
+    ranking of every row), with a last page of a single entry (k = 129) and a head smaller than two pages."""
+    d = 256
+    case = Case(b, L, d, fmt, 1024, 0, B, w_std=0.05, seed=19)
+    X = synth.make_x(np.random.default_rng(4), B, d)
+    for k in ks:
+        say(f"[topk-pages] fmt={fmt} L={L} B={B} k={k}")
+        _check_topk(b, case.head, case.W0, X, k, fmt)
+    with pytest.raises(b.ElmoError):
+        case.head.topk(dev(X), L + 1, None, None)
+
+
+def test_topk_pages_with_tied_scores_and_the_unbounded_path(b):
+    """Pages across ties and across the overflow path: all-zero weights (every score ties, the answer
+    is ids 0..k-1 whatever the page boundaries cut through) and scores rising with the label id (every
+    page overflows the fast path's candidate lists)."""
+    L, d, B, k = 1000, 128, 5, 300
+    case = Case(b, L, d, o.BF16, 512, 0, B)
+    case.load(np.zeros((L, d), np.uint16), None)
+    idx = torch.zeros((B, k), dtype=torch.int32, device=DEV)
+    sc = torch.ones((B, k), dtype=torch.float32, device=DEV)
+    say("[topk-pages] ties")
+    case.head.topk(dev(synth.make_x(np.random.default_rng(0), B, d)), k, idx, sc)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), np.tile(np.arange(k), (B, 1))) and np.all(sc.cpu().numpy() == 0)
+    L, d, B, k = 40000, 128, 9, 260
+    rng = np.random.default_rng(5)
+    X = synth.make_x(rng, B, d)
+    u = o.decode_bf16(X).mean(axis=0)
+    u /= np.linalg.norm(u)
+    ramp = np.linspace(0.0, 2.0, L)[:, None] * u[None, :] + rng.standard_normal((L, d)) * 1e-3
+    case = Case(b, L, d, o.BF16, 4096, 0, B)
+    W = o.round_bf16(ramp.astype(np.float32))
+    case.load(W, None)
+    say("[topk-pages] rising scores, k=260")
+    assert _check_topk(b, case.head, W, X, k, o.BF16) > 0.9
+
+
+def test_topk_mid_size_k500(b):
+    """k = 500 over the Mid head's 131072 labels (four pages)."""
+    cfg = synth.CONFIGS["mid"]
+    head = b.Head(cfg.L, cfg.d, cfg.fmt, cfg.chunk, 0, 64, 64)
+    _init_on_device(b, head, cfg)
+    W = head.weights().cpu().numpy().view(np.uint16)
+    X = synth.make_x(np.random.default_rng(3), 48, cfg.d)
+    say("[topk-mid] L=131072 B=48 k=500")
+    _check_topk(b, head, W, X, 500, cfg.fmt)
+    head.close()
+
+
+def test_wide_head_on_the_small_batch_path(b):
+    """An embedding wider than 65536 columns with a small batch: more column blocks than the 256
+    workgroups the single-pass kernel spreads over label groups, so one label group does all tiles."""
+    L, d, B = 40, 65536 + 256, 4
+    case = Case(b, L, d, o.E4M3, 128, o.FLAG_SR, B, max_nnz=64, w_std=0.01, seed=5)
+    rng = np.random.default_rng(6)
+    X = synth.make_x(rng, B, d)
+    indptr, indices = synth.ZipfLabels(L, 1.0).draw_csr(rng, B, "fixed5")
+    say(f"[wide head] L={L} d={d} B={B}")
+    check_step(case, X, indptr, indices, 0.05, 1, 0, 6e-2)
 
 
 def test_topk_ties_prefer_smaller_ids(b):
