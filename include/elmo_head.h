@@ -127,6 +127,21 @@ int elmo_head_step(elmo_head_t* h, const void* X, int32_t B, const int32_t* indp
 int elmo_head_topk(elmo_head_t* h, const void* X, int32_t B, int32_t k, int32_t* idx_out,
                    float* score_out, void* hip_stream);
 
+/* Top-k scoring for callers that cannot allocate device memory or keep a head: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same result as
+ * elmo_head_topk on a head over the same weights (same kernels), but the call takes the weights
+ * directly and needs no workspace: its scratch (staged E4M3 copy of X, thresholds, candidate lists)
+ * is a device array of 18 MiB inside the library, one copy per GPU the library runs on, held until
+ * the process ends.  The call allocates and frees nothing and launches only kernels (no memset
+ * node).  Limits, rejected with -1: B <= 128 queries, d a multiple of 128 up to 4096, 1 <= k <= L.
+ * W [L, d] in weight_dtype (ELMO_BF16 or ELMO_FP8_E4M3), X [B, d] BF16, both device pointers,
+ * 16-byte aligned; idx_out [B, k] int32, score_out [B, k] float (either may be NULL).
+ * All calls on one GPU share that GPU's array and nothing of it survives a call: calls that overlap
+ * in time on one GPU (two streams, two host threads) race.  The first call on a device looks the
+ * array's address up (hipGetSymbolAddress); make that call outside any stream capture. */
+int elmo_topk_static(const void* W, int64_t L, int32_t d, int weight_dtype, const void* X, int32_t B,
+                     int32_t k, int32_t* idx_out, float* score_out, void* hip_stream);
+
 /* Precision at k (evaluation section, P@k(y, y^) = (1/k) sum over l in top_k(y^) of y_l), as exact
  * integer numerators: hits_out[j-1] = number of (row, label) pairs with the label among the row's
  * first j entries of idx and among the row's positives, summed over the B rows, j = 1..k; then

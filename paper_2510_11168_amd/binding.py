@@ -65,6 +65,9 @@ _lib.elmo_precision_hits.restype = C.c_int
 _lib.elmo_precision_hits.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.elmo_head_topk.restype = C.c_int
 _lib.elmo_head_topk.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.elmo_topk_static.restype = C.c_int
+_lib.elmo_topk_static.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                  C.c_void_p, C.c_void_p]
 _lib.elmo_head_destroy.restype = C.c_int
 _lib.elmo_head_destroy.argtypes = [C.c_void_p]
 _lib.elmo_head_profile.restype = C.c_int
@@ -85,7 +88,7 @@ _lib.elmo_dropout_keep16.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, C.c_uin
 EXPORTS = ("elmo_last_error", "elmo_logit_buffer_bytes", "elmo_head_sizes", "elmo_head_create",
            "elmo_head_step", "elmo_head_topk", "elmo_head_destroy", "elmo_quantize", "elmo_philox4x32_10",
            "elmo_head_profile", "elmo_head_profile_read", "elmo_precision_hits", "elmo_quantize_em",
-           "elmo_dropout_keep16", "elmo_kahan_adamw")
+           "elmo_dropout_keep16", "elmo_kahan_adamw", "elmo_topk_static")
 
 
 def _check(rc: int) -> None:
@@ -141,6 +144,10 @@ def elmo_head_step(h, X, B, indptr, indices, nnz, lr, seed, step, dX_out=None, l
 
 def elmo_head_topk(h, X, B, k, idx_out=None, score_out=None, stream=None) -> None:
     _check(_lib.elmo_head_topk(h, _ptr(X), B, k, _ptr(idx_out), _ptr(score_out), _stream(stream)))
+
+
+def elmo_topk_static(W, L, d, weight_dtype, X, B, k, idx_out=None, score_out=None, stream=None) -> None:
+    _check(_lib.elmo_topk_static(_ptr(W), L, d, weight_dtype, _ptr(X), B, k, _ptr(idx_out), _ptr(score_out), _stream(stream)))
 
 
 def elmo_quantize_em(src, n, exp_bits, man_bits, mode, seed, step, first_elem, dst, stream=None) -> None:

@@ -568,6 +568,71 @@ extern "C" int elmo_head_topk(elmo_head_t* h, const void* X, int32_t B, int32_t 
   return rc;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Top-k without a head, a workspace or any allocation: the scratch of the top-k kernels (thresholds,
+// counters, candidate lists, per-segment lists of the overflow path) and the E4M3 copy of X live
+// in a file-scope device array.  Every GPU the library runs on holds its own copy of that array at
+// its own address until the process ends; the address is looked up once per device.
+// ---------------------------------------------------------------------------------------------
+namespace {
+constexpr int kStaticMaxB = 128;                                  // queries per call
+constexpr int kStaticMaxD = 4096;                                 // embedding width
+constexpr size_t kStaticXqBytes = (size_t)kStaticMaxB * kStaticMaxD;
+constexpr size_t kStaticBytes = (size_t)18 << 20;                 // 0.5 MiB staged inputs + 16.1 MiB top-k scratch for 128 rows
+constexpr int kStaticMaxDevices = 64;
+std::mutex g_static_mu;
+char* g_static_ptr[kStaticMaxDevices] = {};
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+namespace {
+// Device address of `scratch` on the current device.  In host code the array's name is only a
+// stand-in for the symbol, never a device address: the address comes from the runtime, per device.
+int static_scratch(char** out) {
+  int dev = -1;
+  ELMO_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kStaticMaxDevices) return fail(-3, "device ordinal %d outside [0, %d)", dev, kStaticMaxDevices);
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void* p = nullptr;
+    ELMO_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(-3, "hipGetSymbolAddress returned a null address");
+    g_static_ptr[dev] = (char*)p;
+  }
+  *out = g_static_ptr[dev];
+  return 0;
+}
+}  // namespace
+
+extern "C" int elmo_topk_static(const void* W, int64_t L, int32_t d, int weight_dtype, const void* X, int32_t B, int32_t k,
+                                int32_t* idx_out, float* score_out, void* hip_stream) {
+  if (!W || !X) return fail(-1, "W and X must not be NULL");
+  if (L < 1 || L > (int64_t)1 << 31) return fail(-1, "L must be in [1, 2^31] (got %lld)", (long long)L);
+  if (d < 128 || d % 128 != 0 || d > kStaticMaxD) return fail(-1, "d must be a multiple of 128 in [128, %d] (got %d)", kStaticMaxD, d);
+  if (weight_dtype != ELMO_BF16 && weight_dtype != ELMO_FP8_E4M3) return fail(-2, "unsupported weight_dtype %d", weight_dtype);
+  if (B < 1 || B > kStaticMaxB) return fail(-1, "B = %d outside [1, %d]: the static scratch holds the lists of %d queries", B, kStaticMaxB, kStaticMaxB);
+  if (k < 1 || k > L) return fail(-1, "k = %d outside [1, L = %lld]", k, (long long)L);
+  if (((uintptr_t)W | (uintptr_t)X) & 15) return fail(-1, "W and X must be 16-byte aligned");
+  const bool fp8 = weight_dtype == ELMO_FP8_E4M3;
+  const int Bp = round_up(B, 64);
+  if (kStaticXqBytes + elmo::topk_scratch_bytes(Bp, 0) > kStaticBytes) return fail(-3, "internal: static scratch plan exceeded");
+  if (int rc = raise_lds_limits()) return rc;
+  char* base = nullptr;
+  if (int rc = static_scratch(&base)) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  uint8_t* Xq = (uint8_t*)base;
+  if (fp8) {   // E4M3 copy of X, rows B..Bp-1 zero (the BF16 product reads X itself and clamps its rows)
+    const size_t n = (size_t)Bp * d;
+    elmo::k_prep_x<<<(int)std::min<size_t>((n + 255) / 256, 4096), elmo::kThreads, 0, st>>>((const uint16_t*)X, B, Bp, d, Xq, nullptr);
+    if (int rc = check_launch("k_prep_x")) return rc;
+  }
+  // every call starts from the scratch the last call left: topk_run re-initialises the thresholds,
+  // counters and overflow flags of all rows itself, and reads candidate slots only below the counters
+  return elmo::topk_run(st, fp8, fp8 ? (const char*)Xq : (const char*)X, fp8 ? Bp : B, (const char*)W, L, d, 0, B, Bp, k,
+                        base + kStaticXqBytes, idx_out, score_out, g_err, sizeof g_err);
+}
+
 extern "C" int elmo_precision_hits(const int32_t* idx, int32_t B, int32_t k, const int32_t* indptr, const int32_t* indices,
                                    int64_t* hits_out, void* hip_stream) {
   if (!idx || !indptr || !hits_out) return fail(-1, "idx, indptr and hits_out must not be NULL");

@@ -136,6 +136,11 @@ int main(void) {
     CHECK(elmo_precision_hits((int32_t*)(uintptr_t)0x1000, 1 << 20, 1 << 12, (int32_t*)(uintptr_t)0x1000, NULL, (int64_t*)(uintptr_t)0x1000, NULL) == -1);
     CHECK(elmo_kahan_adamw(NULL, NULL, NULL, NULL, NULL, 8, ELMO_BF16, 1e-3f, 0.9, 0.999, 1e-8f, 0.0f, 1, NULL) == -1);
     CHECK(elmo_kahan_adamw(NULL, NULL, NULL, NULL, NULL, 0, ELMO_BF16, 1e-3f, 0.9, 0.999, 1e-8f, 0.0f, 1, NULL) == 0);
+    CHECK(elmo_topk_static(NULL, 10, 256, ELMO_BF16, NULL, 1, 1, NULL, NULL, NULL) == -1);
+    CHECK(elmo_topk_static((void*)(uintptr_t)0x1000, 1000, 256, ELMO_BF16, (void*)(uintptr_t)0x2000, 129, 5, NULL, NULL, NULL) == -1);
+    CHECK(elmo_topk_static((void*)(uintptr_t)0x1000, 1000, 8192, ELMO_BF16, (void*)(uintptr_t)0x2000, 8, 5, NULL, NULL, NULL) == -1);
+    CHECK(elmo_topk_static((void*)(uintptr_t)0x1000, 1000, 256, 7, (void*)(uintptr_t)0x2000, 8, 5, NULL, NULL, NULL) == -2);
+    CHECK(elmo_topk_static((void*)(uintptr_t)0x1000, 1000, 256, ELMO_BF16, (void*)(uintptr_t)0x2000, 8, 1001, NULL, NULL, NULL) == -1);
   }
   if (failures) {
     fprintf(stderr, "%d host-side ABI checks failed\n", failures);

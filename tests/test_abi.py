@@ -157,6 +157,9 @@ def test_topk_and_hits_argument_checks(b):
     with pytest.raises(b.ElmoError) as e:
         b._check(b._lib.elmo_precision_hits(16, 1 << 20, 1 << 12, 16, 16, 16, None))
     assert e.value.code == -1
+    with pytest.raises(b.ElmoError) as e:      # the allocation-free top-k refuses what its fixed scratch cannot hold
+        b._check(b._lib.elmo_topk_static(16, 1000, 256, b.ELMO_BF16, 16, 129, 5, None, None, None))
+    assert e.value.code == -1 and "128" in str(e.value)
 
 
 def test_create_rejects_missing_or_small_buffers(b):
