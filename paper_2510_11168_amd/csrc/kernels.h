@@ -221,6 +221,10 @@ constexpr int kGemmWaves = 8;
 constexpr int kStages = 3;                                       // ring depth of the small-batch kernel
 constexpr int kWideRingBytes = 2 * (256 + 256) * 128;            // K-contiguous operands, 128-byte slabs, 2 stages
 
+// Register fragments of one step of a product: FM x FN blocks of 32 x 32 outputs.
+template <int FM, int FN> struct FragBF16 { bf16x8 a[FM], b[FN]; };
+template <int FM, int FN> struct FragFP8 { i32x8 a[FM], b[FN]; };
+
 template <int FN> __device__ inline void zero_acc(f32x16 (&acc)[2][FN]) {
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -693,32 +697,33 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
       creg[it][1] = *reinterpret_cast<const u32x4*>(Cc + eoff + 8);
     }
   };
-  if (has_cols) {
+  if (has_cols) {   // passes 0 and 1 of the first half before the product, passes 2 and 3 right after it
 #pragma unroll
-    for (int it = 0; it < 4; ++it) fetch(it, 0);
+    for (int it = 0; it < 2; ++it) fetch(it, 0);
   }
 
   f32x16 acc[2][4];
   zero_acc(acc);
   // K loop over the batch in slabs of 64 samples
-  ring_pipeline_pp<256, 128, 256, 128, 2, kGemmWaves, kUpdUneven, kUpdLateAfter>(
+  ring_pipeline_sw<256, 128, 256, 128, 2, kGemmWaves, kUpdUneven, 4, 6, 8, FragBF16<2, 4>>(
       Gt + (size_t)l0 * stride, stride, n - l0, 0, 128, 8, XT + (size_t)j0 * stride, stride, d - j0, 0, 128, 8, Bp >> 6, smem, wave,
-      lane, [&](const char* sa, const char* sb, int q0, int q1) {
+      lane,
+      [&](FragBF16<2, 4>& f, const char* sa, const char* sb, int kk) {
 #pragma unroll
-        for (int kk = q0; kk < q1; ++kk) {
-          bf16x8 a[2], b[4];
+        for (int i = 0; i < 2; ++i) f.a[i] = frag_bf16(sa, wm * 64 + 32 * i, kk, lane);
 #pragma unroll
-          for (int i = 0; i < 2; ++i) a[i] = frag_bf16(sa, wm * 64 + 32 * i, kk, lane);
+        for (int j = 0; j < 4; ++j) f.b[j] = frag_bf16(sb, wn * 128 + 32 * j, kk, lane);
+      },
+      [&](const FragBF16<2, 4>& f) {
 #pragma unroll
-          for (int j = 0; j < 4; ++j) b[j] = frag_bf16(sb, wn * 128 + 32 * j, kk, lane);
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-          for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-        }
+          for (int j = 0; j < 4; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
       });
   if (!has_cols) return;                             // after the ring's last barrier: no barrier follows
+#pragma unroll
+  for (int it = 2; it < 4; ++it) fetch(it, 0);
 
   // This wave's LDS area: a 32 x 128 FP32 half-block, [label][column], turns the MFMA layout into
   // 16 consecutive columns per lane.  Nothing below synchronises the workgroup.

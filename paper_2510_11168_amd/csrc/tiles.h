@@ -94,9 +94,18 @@ __device__ inline void dma_tile(const char* __restrict__ g, size_t stride, int r
     const int rc = min(r, rows_valid - 1);
     // 32-bit lane offset on top of the (wave-uniform) slab pointer: the load then takes the
     // scalar-base + vector-offset form and needs no 64-bit address arithmetic per lane
-    uint32_t off = __umul24((uint32_t)rc, (uint32_t)stride) + (uint32_t)(c * 16);
-    asm volatile("" : "+v"(off));   // stays a 32-bit register (its 64-bit extension would be hoisted as a pair)
-    __builtin_amdgcn_global_load_lds(ELMO_GLOBAL_PTR(g + off), ELMO_LDS_PTR(void, lds_tile + rbase * ROWB), 16, 0, 0);
+    const uint32_t off = __umul24((uint32_t)rc, (uint32_t)stride) + (uint32_t)(c * 16);
+    // The load is written as an assembly statement (M0 = LDS address of lane 0's 16 bytes, lane i
+    // lands 16 i bytes further; scalar base + 32-bit lane offset).  Issued through the builtin, the
+    // compiler books it as an access that may touch both memory and LDS, and while one is in
+    // flight it turns every wait for LDS fragment reads into lgkmcnt(0) -- which also waits for
+    // the reads of the next step issued just before -- and puts vmcnt(0) in front of LDS reads it
+    // cannot tell from the load's destination.  Completion is tracked by the explicit vmcnt
+    // waits of the rings (loads complete in issue order; the compiler's own vmcnt waits only
+    // become stricter by loads it does not know of).
+    // (the low 32 bits of a generic pointer into LDS are the LDS byte address)
+    const uint32_t dst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds_tile + (uint32_t)(rbase * ROWB));
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"(off), "s"(g) : "memory", "m0");
   }
 }
 template <int ROWS, int ROWB, int NW> constexpr int dma_loads_per_wave() { return ROWS * ROWB / 1024 / NW; }
@@ -239,6 +248,96 @@ __device__ inline void ring_pipeline_pp(const char* __restrict__ ga, size_t stri
         off_b = (size_t)ks * adv_b; vb = vb0 - ks * dvb;
       },
       [&](const char* sa, const char* sb, int q0, int q1, int) { mma(sa, sb, q0, q1); }, static_cast<Prep&&>(prep));
+}
+
+// Software-pipelined form of the ring for one output tile.  The product of a slab is KSTEPS
+// fragment steps; ld(f, stageA, stageB, kk) reads the fragments of step kk into registers and
+// mm(f) issues that step's MFMAs.  Two fragment sets alternate: the LDS reads of step kk + 1 are
+// issued before the MFMAs of step kk, and the last step of a slab is multiplied after the next
+// slab's barrier, behind the first fragment reads of that slab.  A wave then meets one wait per
+// slab (the barrier) instead of one LDS round trip per half slab with the matrix cores idle:
+// with ring_pipeline_pp the compiler's schedule was read / wait / 8 MFMAs per step, and the K
+// loops ran at about twice the MFMA time.
+// Early waves issue their asynchronous loads right after the barrier, late waves after
+// KSTEPS / 2 steps, as in ring_stream_pp.  Fragments of the stage being left are all in registers
+// (lgkmcnt(0)) before a wave arrives at the barrier that lets other waves overwrite that stage.
+// NRD / NMM: LDS reads per ld() and MFMAs per mm(); the scheduler is told to issue a step's reads
+// ahead of the MFMAs they overlap with (it otherwise sinks them behind the MFMAs to save registers).
+template <int NRD, int NMM> __device__ __forceinline__ void sched_reads_then_mfma() {
+  __builtin_amdgcn_sched_group_barrier(0x100, NRD, 0);
+  __builtin_amdgcn_sched_group_barrier(0x008, NMM, 0);
+}
+template <int AROWS, int AROWB, int BROWS, int BROWB, int NST, int NW, bool UNEVEN, int KSTEPS, int NRD, int NMM, class F, class Ld, class Mm>
+__device__ inline void ring_pipeline_sw(const char* __restrict__ ga, size_t stride_a, int va0, int dva, size_t adv_a, int chunks_a,
+                                        const char* __restrict__ gb, size_t stride_b, int vb0, int dvb, size_t adv_b, int chunks_b,
+                                        int nk, char* smem, int wave, int lane, Ld&& ld, Mm&& mm) {
+  static_assert(KSTEPS >= 2 && KSTEPS % 2 == 0, "fragment steps come in pairs");
+  constexpr int ABYTES = AROWS * AROWB, SBYTES = ABYTES + BROWS * BROWB, NH = NW / 2, BH = BROWS / 2;
+  constexpr int LPS_ALL = dma_loads_per_wave<AROWS, AROWB, NW>() + dma_loads_per_wave<BROWS, BROWB, NW>();
+  constexpr int LPS_LATE = UNEVEN ? dma_loads_per_wave<BH, BROWB, NH>() : LPS_ALL;
+  constexpr int LPS_EARLY = UNEVEN ? dma_loads_per_wave<AROWS, AROWB, NH>() + LPS_LATE : LPS_ALL;
+  static_assert(NST >= 2 && NST <= 3 && (NST - 2) * LPS_EARLY <= 63, "ring depth");
+  const bool late = wave >= NH;
+  auto issue = [&](int ks) {
+    char* st = smem + (ks % NST) * SBYTES;
+    const size_t off_a = (size_t)ks * adv_a, off_b = (size_t)ks * adv_b;
+    const int va = va0 - ks * dva, vb = vb0 - ks * dvb;
+    if (!UNEVEN) {
+      dma_tile<AROWS, AROWB, NW>(ga + off_a, stride_a, va, st, wave, lane, chunks_a);
+      dma_tile<BROWS, BROWB, NW>(gb + off_b, stride_b, vb, st + ABYTES, wave, lane, chunks_b);
+    } else if (!late) {
+      dma_tile<AROWS, AROWB, NH>(ga + off_a, stride_a, va, st, wave, lane, chunks_a);
+      dma_tile<BH, BROWB, NH>(gb + off_b, stride_b, vb, st + ABYTES, wave, lane, chunks_b);
+    } else {
+      dma_tile<BH, BROWB, NH>(gb + off_b + (size_t)min(BH, vb - 1) * stride_b, stride_b, max(vb - BH, 1),
+                              st + ABYTES + BH * BROWB, wave - NH, lane, chunks_b);
+    }
+  };
+  for (int s = 0; s < NST - 1; ++s)
+    if (s < nk) issue(s);
+  F f0, f1;
+  // Nothing that counts on lgkmcnt may be pending when the loop is entered: scalar loads (kernel
+  // arguments first used after the loop) return out of order, and while one is outstanding the
+  // compiler turns every wait for a step's fragments into lgkmcnt(0), which also waits for the
+  // reads of the next step that were just issued.
+  __builtin_amdgcn_s_waitcnt(0xC07F);
+  for (int ks = 0; ks < nk; ++ks) {
+    if (NST == 2 || ks + 1 >= nk) wait_vmcnt<0>();
+    else if (late) wait_vmcnt<LPS_LATE>();
+    else wait_vmcnt<LPS_EARLY>();
+    barrier_nofence();
+    const bool more = ks + NST - 1 < nk;
+    if (more && !late) issue(ks + NST - 1);
+    const char* sa = smem + (ks % NST) * SBYTES;
+    const char* sb = sa + ABYTES;
+    __builtin_amdgcn_sched_barrier(0);
+    ld(f0, sa, sb, 0);
+    if (ks > 0) {                          // last step of the slab before, behind this slab's first reads
+      mm(f1);
+      sched_reads_then_mfma<NRD, NMM>();
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 1; kk < KSTEPS; kk += 2) {
+      ld(f1, sa, sb, kk);
+      mm(f0);
+      sched_reads_then_mfma<NRD, NMM>();
+      __builtin_amdgcn_sched_barrier(0);
+      if (kk + 1 == KSTEPS / 2 || (KSTEPS == 2 && kk == 1)) {
+        if (more && late) issue(ks + NST - 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (kk + 1 < KSTEPS) {
+        ld(f0, sa, sb, kk + 1);
+        mm(f1);
+        sched_reads_then_mfma<NRD, NMM>();
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0xC07F);    // lgkmcnt(0): every fragment of this stage is in registers
+  }
+  mm(f1);
+  barrier_nofence();   // every wave is done with the ring: the caller may reuse the memory
 }
 
 // ---------------------------------------------------------------------------------------------
