@@ -210,12 +210,12 @@ __global__ void __launch_bounds__(kThreads) k_label_scatter(const int* __restric
 // a tile of this size halves the fill traffic per flop of a 256 x 128 tile, and the ping-pong
 // issue order of the ring hides most of what is left.
 // ---------------------------------------------------------------------------------------------
-// How each product splits a slab's loads between the early and the late waves (tiles.h): uneven =
-// three quarters early; late issue after this many quarters of the slab's MFMAs.  Measured per
-// kernel: the update kernel's K loop is 2 % faster uneven but then spills; issuing after one or
-// three quarters was never better than after two.
-constexpr bool kUpdUneven = false, kDxUneven = true;
-constexpr int kUpdLateAfter = 2, kDxLateAfter = 2;
+// How the input-gradient product splits a slab's loads between the early and the late waves
+// (tiles.h, ring_stream_pp): uneven = three quarters early; late issue after this many quarters of
+// the slab's MFMAs (issuing after one or three quarters was never better than after two).  The
+// update product uses the paced ring instead (ring_pipeline_paced).
+constexpr bool kDxUneven = true;
+constexpr int kDxLateAfter = 2;
 constexpr int kGemmThreads = 512;
 constexpr int kGemmWaves = 8;
 constexpr int kStages = 3;                                       // ring depth of the small-batch kernel
@@ -705,7 +705,7 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
   f32x16 acc[2][4];
   zero_acc(acc);
   // K loop over the batch in slabs of 64 samples
-  ring_pipeline_sw<256, 128, 256, 128, 2, kGemmWaves, kUpdUneven, 4, 6, 8, FragBF16<2, 4>>(
+  ring_pipeline_paced<256, 128, 256, 128, kGemmWaves, 4, 6, 8, FragBF16<2, 4>>(
       Gt + (size_t)l0 * stride, stride, n - l0, 0, 128, 8, XT + (size_t)j0 * stride, stride, d - j0, 0, 128, 8, Bp >> 6, smem, wave,
       lane,
       [&](FragBF16<2, 4>& f, const char* sa, const char* sb, int kk) {
@@ -714,12 +714,9 @@ k_update(const char* __restrict__ Gt, const char* __restrict__ XT, char* __restr
 #pragma unroll
         for (int j = 0; j < 4; ++j) f.b[j] = frag_bf16(sb, wn * 128 + 32 * j, kk, lane);
       },
-      [&](const FragBF16<2, 4>& f) {
+      [&](const FragBF16<2, 4>& f, int i) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
       });
   if (!has_cols) return;                             // after the ring's last barrier: no barrier follows
 #pragma unroll

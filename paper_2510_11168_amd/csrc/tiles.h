@@ -73,7 +73,8 @@ __device__ inline void barrier_lds() {
 // whole tile rows; each lane fetches the global chunk that belongs at its swizzled position.
 // Rows at or beyond rows_valid (>= 1) re-read the last valid row.  Issues ROWS*ROWB/4096 loads per
 // wave; completion is tracked by vmcnt in issue order.
-template <int ROWS, int ROWB, int NW>
+// I0, I1: only loads I0 .. I1-1 of the wave's NI loads (default: all), for callers that pace them.
+template <int ROWS, int ROWB, int NW, int I0 = 0, int I1 = 1 << 20>
 __device__ inline void dma_tile(const char* __restrict__ g, size_t stride, int rows_valid, char* lds_tile, int wave, int lane,
                                 int chunks_valid = 1 << 20) {
   constexpr int RPI = 1024 / ROWB, CPR = ROWB / 16, NI = ROWS / RPI / NW;
@@ -87,7 +88,7 @@ __device__ inline void dma_tile(const char* __restrict__ g, size_t stride, int r
     g = reinterpret_cast<const char*>(((uintptr_t)hi << 32) | lo);
   }
 #pragma unroll
-  for (int i = 0; i < NI; ++i) {
+  for (int i = (I0 > 0 ? I0 : 0); i < (I1 < NI ? I1 : NI); ++i) {
     const int rbase = (wave * NI + i) * RPI;
     const int r = rbase + lane / CPR;
     const int c = min((lane % CPR) ^ swz_key<ROWB>(r), chunks_valid - 1);   // chunks past a short row re-read its last one
@@ -250,93 +251,94 @@ __device__ inline void ring_pipeline_pp(const char* __restrict__ ga, size_t stri
       [&](const char* sa, const char* sb, int q0, int q1, int) { mma(sa, sb, q0, q1); }, static_cast<Prep&&>(prep));
 }
 
-// Software-pipelined form of the ring for one output tile.  The product of a slab is KSTEPS
-// fragment steps; ld(f, stageA, stageB, kk) reads the fragments of step kk into registers and
-// mm(f) issues that step's MFMAs.  Two fragment sets alternate: the LDS reads of step kk + 1 are
-// issued before the MFMAs of step kk, and the last step of a slab is multiplied after the next
-// slab's barrier, behind the first fragment reads of that slab.  A wave then meets one wait per
-// slab (the barrier) instead of one LDS round trip per half slab with the matrix cores idle:
-// with ring_pipeline_pp the compiler's schedule was read / wait / 8 MFMAs per step, and the K
-// loops ran at about twice the MFMA time.
-// Early waves issue their asynchronous loads right after the barrier, late waves after
-// KSTEPS / 2 steps, as in ring_stream_pp.  Fragments of the stage being left are all in registers
+// Software-pipelined, paced form of the two-stage ring for one output tile.  The product of a slab
+// is KSTEPS fragment steps; ld(f, stageA, stageB, kk) reads the fragments of step kk into registers
+// and mm(f, h) issues half h (0 / 1) of that step's MFMAs.  Two fragment sets alternate: the LDS
+// reads of step kk + 1 are issued before the MFMAs of step kk, and the last step of a slab is
+// multiplied after the next slab's barrier, behind the first fragment reads of that slab, so a
+// wave meets one wait per slab (the barrier) instead of an LDS round trip with idle matrix cores
+// at every half slab (what the compiler makes of ring_pipeline_pp: read, wait, 8 MFMAs per step).
+// Every wave issues its equal share of the next slab's asynchronous loads in four quarters,
+// between the MFMA groups of the first two steps after the barrier, instead of half of the waves
+// issuing everything at once.  Fragments of the stage being left are all in registers
 // (lgkmcnt(0)) before a wave arrives at the barrier that lets other waves overwrite that stage.
-// NRD / NMM: LDS reads per ld() and MFMAs per mm(); the scheduler is told to issue a step's reads
+// NRD / NMM: LDS reads per ld() and MFMAs per step; the scheduler is told to issue a step's reads
 // ahead of the MFMAs they overlap with (it otherwise sinks them behind the MFMAs to save registers).
+// Measured on the update product (per chunk of the 3M-label FP8 head, B = 1024): 282 us with
+// ring_pipeline_pp, 274 us software-pipelined with the early / late split, 267 us paced.  What
+// bounds the loop is the round trip of a slab's loads (about 3 k clocks for 64 KiB whether or not
+// the lines are already in L2; the same loop without MFMAs and fragment reads takes 0.8 of the
+// full loop's time, without loads 0.65), and 160 KiB of LDS do not hold a third 64 KiB stage.
 template <int NRD, int NMM> __device__ __forceinline__ void sched_reads_then_mfma() {
   __builtin_amdgcn_sched_group_barrier(0x100, NRD, 0);
   __builtin_amdgcn_sched_group_barrier(0x008, NMM, 0);
 }
-template <int AROWS, int AROWB, int BROWS, int BROWB, int NST, int NW, bool UNEVEN, int KSTEPS, int NRD, int NMM, class F, class Ld, class Mm>
-__device__ inline void ring_pipeline_sw(const char* __restrict__ ga, size_t stride_a, int va0, int dva, size_t adv_a, int chunks_a,
-                                        const char* __restrict__ gb, size_t stride_b, int vb0, int dvb, size_t adv_b, int chunks_b,
-                                        int nk, char* smem, int wave, int lane, Ld&& ld, Mm&& mm) {
+template <int AROWS, int AROWB, int BROWS, int BROWB, int NW, int KSTEPS, int NRD, int NMM, class F, class Ld, class Mm>
+__device__ inline void ring_pipeline_paced(const char* __restrict__ ga, size_t stride_a, int va0, int dva, size_t adv_a, int chunks_a,
+                                           const char* __restrict__ gb, size_t stride_b, int vb0, int dvb, size_t adv_b, int chunks_b,
+                                           int nk, char* smem, int wave, int lane, Ld&& ld, Mm&& mm) {
   static_assert(KSTEPS >= 2 && KSTEPS % 2 == 0, "fragment steps come in pairs");
-  constexpr int ABYTES = AROWS * AROWB, SBYTES = ABYTES + BROWS * BROWB, NH = NW / 2, BH = BROWS / 2;
-  constexpr int LPS_ALL = dma_loads_per_wave<AROWS, AROWB, NW>() + dma_loads_per_wave<BROWS, BROWB, NW>();
-  constexpr int LPS_LATE = UNEVEN ? dma_loads_per_wave<BH, BROWB, NH>() : LPS_ALL;
-  constexpr int LPS_EARLY = UNEVEN ? dma_loads_per_wave<AROWS, AROWB, NH>() + LPS_LATE : LPS_ALL;
-  static_assert(NST >= 2 && NST <= 3 && (NST - 2) * LPS_EARLY <= 63, "ring depth");
-  const bool late = wave >= NH;
-  auto issue = [&](int ks) {
-    char* st = smem + (ks % NST) * SBYTES;
-    const size_t off_a = (size_t)ks * adv_a, off_b = (size_t)ks * adv_b;
-    const int va = va0 - ks * dva, vb = vb0 - ks * dvb;
-    if (!UNEVEN) {
-      dma_tile<AROWS, AROWB, NW>(ga + off_a, stride_a, va, st, wave, lane, chunks_a);
-      dma_tile<BROWS, BROWB, NW>(gb + off_b, stride_b, vb, st + ABYTES, wave, lane, chunks_b);
-    } else if (!late) {
-      dma_tile<AROWS, AROWB, NH>(ga + off_a, stride_a, va, st, wave, lane, chunks_a);
-      dma_tile<BH, BROWB, NH>(gb + off_b, stride_b, vb, st + ABYTES, wave, lane, chunks_b);
-    } else {
-      dma_tile<BH, BROWB, NH>(gb + off_b + (size_t)min(BH, vb - 1) * stride_b, stride_b, max(vb - BH, 1),
-                              st + ABYTES + BH * BROWB, wave - NH, lane, chunks_b);
-    }
+  constexpr int ABYTES = AROWS * AROWB, SBYTES = ABYTES + BROWS * BROWB;
+  constexpr int NA = dma_loads_per_wave<AROWS, AROWB, NW>(), NB = dma_loads_per_wave<BROWS, BROWB, NW>();
+  static_assert(NA % 2 == 0 && NB % 2 == 0, "loads are issued in four quarters");
+  auto issue_a = [&](int ks, auto half) {
+    constexpr int H = decltype(half)::value;
+    dma_tile<AROWS, AROWB, NW, H * NA / 2, (H + 1) * NA / 2>(ga + (size_t)ks * adv_a, stride_a, va0 - ks * dva, smem + (ks & 1) * SBYTES, wave, lane, chunks_a);
   };
-  for (int s = 0; s < NST - 1; ++s)
-    if (s < nk) issue(s);
+  auto issue_b = [&](int ks, auto half) {
+    constexpr int H = decltype(half)::value;
+    dma_tile<BROWS, BROWB, NW, H * NB / 2, (H + 1) * NB / 2>(gb + (size_t)ks * adv_b, stride_b, vb0 - ks * dvb, smem + (ks & 1) * SBYTES + ABYTES, wave, lane, chunks_b);
+  };
+  using H0 = std::integral_constant<int, 0>;
+  using H1 = std::integral_constant<int, 1>;
+  issue_a(0, H0{}); issue_a(0, H1{}); issue_b(0, H0{}); issue_b(0, H1{});
   F f0, f1;
-  // Nothing that counts on lgkmcnt may be pending when the loop is entered: scalar loads (kernel
-  // arguments first used after the loop) return out of order, and while one is outstanding the
-  // compiler turns every wait for a step's fragments into lgkmcnt(0), which also waits for the
-  // reads of the next step that were just issued.
-  __builtin_amdgcn_s_waitcnt(0xC07F);
   for (int ks = 0; ks < nk; ++ks) {
-    if (NST == 2 || ks + 1 >= nk) wait_vmcnt<0>();
-    else if (late) wait_vmcnt<LPS_LATE>();
-    else wait_vmcnt<LPS_EARLY>();
+    wait_vmcnt<0>();
     barrier_nofence();
-    const bool more = ks + NST - 1 < nk;
-    if (more && !late) issue(ks + NST - 1);
-    const char* sa = smem + (ks % NST) * SBYTES;
+    const bool more = ks + 1 < nk;
+    const char* sa = smem + (ks & 1) * SBYTES;
     const char* sb = sa + ABYTES;
     __builtin_amdgcn_sched_barrier(0);
     ld(f0, sa, sb, 0);
     if (ks > 0) {                          // last step of the slab before, behind this slab's first reads
-      mm(f1);
-      sched_reads_then_mfma<NRD, NMM>();
+      mm(f1, 0);
+      sched_reads_then_mfma<NRD, NMM / 2>();
+      __builtin_amdgcn_sched_barrier(0);
+      if (more) issue_a(ks + 1, H0{});
+      __builtin_amdgcn_sched_barrier(0);
+      mm(f1, 1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (more) issue_a(ks + 1, H1{});
+    } else if (more) {
+      issue_a(ks + 1, H0{});
+      issue_a(ks + 1, H1{});
     }
     __builtin_amdgcn_sched_barrier(0);
+    ld(f1, sa, sb, 1);
+    mm(f0, 0);
+    sched_reads_then_mfma<NRD, NMM / 2>();
+    __builtin_amdgcn_sched_barrier(0);
+    if (more) issue_b(ks + 1, H0{});
+    __builtin_amdgcn_sched_barrier(0);
+    mm(f0, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    if (more) issue_b(ks + 1, H1{});
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int kk = 1; kk < KSTEPS; kk += 2) {
-      ld(f1, sa, sb, kk);
-      mm(f0);
+    for (int kk = 2; kk < KSTEPS; kk += 2) {
+      ld(f0, sa, sb, kk);
+      mm(f1, 0); mm(f1, 1);
       sched_reads_then_mfma<NRD, NMM>();
       __builtin_amdgcn_sched_barrier(0);
-      if (kk + 1 == KSTEPS / 2 || (KSTEPS == 2 && kk == 1)) {
-        if (more && late) issue(ks + NST - 1);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      if (kk + 1 < KSTEPS) {
-        ld(f0, sa, sb, kk + 1);
-        mm(f1);
-        sched_reads_then_mfma<NRD, NMM>();
-        __builtin_amdgcn_sched_barrier(0);
-      }
+      ld(f1, sa, sb, kk + 1);
+      mm(f0, 0); mm(f0, 1);
+      sched_reads_then_mfma<NRD, NMM>();
+      __builtin_amdgcn_sched_barrier(0);
     }
     __builtin_amdgcn_s_waitcnt(0xC07F);    // lgkmcnt(0): every fragment of this stage is in registers
   }
-  mm(f1);
+  mm(f1, 0); mm(f1, 1);
   barrier_nofence();   // every wave is done with the ring: the caller may reuse the memory
 }
 

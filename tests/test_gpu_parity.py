@@ -224,17 +224,17 @@ class Case:
                 None if loss is None else float(loss.item()))
 
 
-def check_step(case, X, indptr, indices, lr, seed, step, tol, W_before=None, C_before=None):
+def check_step(case, X, indptr, indices, lr, seed, step, tol, W_before=None, C_before=None, want_loss=True):
     """Run one GPU step and compare everything with the oracle fed the same starting bits."""
     W_before = case.W() if W_before is None else W_before
     C_before = case.C() if C_before is None else C_before
-    dX, loss = case.step(X, indptr, indices, lr, seed, step)
+    dX, loss = case.step(X, indptr, indices, lr, seed, step, want_loss=want_loss)
     ref = o.head_step(W_before, C_before, X, indptr, indices, lr, seed, step, case.fmt, case.flags)
     Wn = case.W()
     dist = np.abs(ordered(Wn, case.fmt) - ordered(ref["W_new"], case.fmt))
     frac_exact = float(np.mean(dist == 0))
     frac_1ulp = float(np.mean(dist <= 1))
-    e_loss = abs(loss - ref["loss"]) / abs(ref["loss"])
+    e_loss = abs(loss - ref["loss"]) / abs(ref["loss"]) if want_loss else 0.0
     say(f"   W': exact {frac_exact:.5f}, within 1 ulp {frac_1ulp:.6f}, max {dist.max()};  loss rel {e_loss:.2e}")
     assert frac_1ulp >= 0.999
     assert_far_misses_are_tiny(Wn, ref["W_new"], dist, case.fmt, lr)
@@ -424,6 +424,32 @@ def test_classifier_dropout(b, fmt, flags, B, d, T):
     assert np.array_equal(other.W(), Wn)
     with pytest.raises(b.ElmoError):
         case.head.step(dev(X), dev(indptr), dev(indices), lr, 77, 1 << 63)
+
+
+@pytest.mark.parametrize("B,d,flags,L,chunk", [
+    (70, 768, o.FLAG_SR | o.FLAG_KAHAN, 9 * 128 + 77, 512),     # 128-row padded batch, the width of the 3M-label head
+    (128, 256, o.FLAG_SR, 2048 + 1, 1024),                       # full batch tile, one label past a tile boundary
+    (33, 512, o.FLAG_KAHAN, 700, 384),                           # 64-row padded batch
+    (64, 1536, 0, 300, 256),                                     # 64 rows x 1536 columns: the largest resident input
+    (5, 256, o.FLAG_SR, 40, 128),                                # fewer labels than one strip group
+])
+def test_small_batch_logits_without_loss(b, B, d, flags, L, chunk):
+    """A step that asks for no loss value (what the benchmark times) runs the logits kernel built
+    without the loss terms.  Checked against the oracle like every step, and bit for bit against
+    the same step with a loss output: both accumulate every logit over K in the same order, so G
+    and the updated weights must agree.  Small batches (padded to 64 or 128 rows), E4M3 weights,
+    crowded first label bins, ragged label counts."""
+    rng = np.random.default_rng(91)
+    X = synth.make_x(rng, B, d)
+    indptr, indices = synth.ZipfLabels(L, 1.3).draw_csr(rng, B, "lognormal5")    # steep: the first bins are crowded
+    say(f"[stream logits] B={B} d={d} flags={flags} L={L} chunk={chunk} nnz={len(indices)}")
+    case = Case(b, L, d, o.E4M3, chunk, flags, B, w_std=0.05, comp_std=2e-4, seed=92)
+    check_step(case, X, indptr, indices, 0.1, 11, 3, 6e-2, want_loss=False)
+    other = Case(b, L, d, o.E4M3, chunk, flags, B, w_std=0.05, comp_std=2e-4, seed=92)
+    dX2, _ = other.step(X, indptr, indices, 0.1, 11, 3, want_loss=True)
+    assert np.array_equal(other.W(), case.W())
+    if flags & o.FLAG_KAHAN:
+        assert np.array_equal(other.C(), case.C())
 
 
 def test_many_batch_tiles(b):
