@@ -42,8 +42,10 @@ Readings taken where the paper is silent (each is repeated at the function that 
   hold eight 16-bit fields; element e uses field e % 8 (field f = word f // 2, low half first).
 * The 16-bit field r decides the rounding by add-and-truncate on the magnitude: the 16 most
   significant dropped bits of |t| plus r carry into the kept bits or not.  For BF16 (16 dropped
-  bits of an FP32 value) this is Eq. (1) exactly.  For E4M3 (20 dropped bits in the normal range)
-  the probability is Eq. (1)'s rounded down to a multiple of 2^-16.
+  bits of an FP32 value) this is Eq. (1) exactly.  For E4M3 this DEPARTS from Eq. (1): 20 bits are
+  dropped in the normal range, the field has 16, so the probability of rounding up is Eq. (1)'s
+  rounded DOWN to a multiple of 2^-16 -- a bias of less than 2^-16 of a grid step toward zero per
+  rounding (pinned exactly: over all 65536 fields the number that round up is floor(p 2^16)).
 * Rounding acts on sign and magnitude separately; a result that rounds to zero keeps its sign.
 * The weight gradient is summed over the batch with no 1/B factor (Algorithm 1, fuse_update).
 * grad W uses the BF16 inputs X, the logits use the E4M3 cast of X (Algorithm 1).

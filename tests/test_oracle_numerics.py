@@ -331,3 +331,83 @@ def test_simulated_format_special_values_and_sr():
     # Eq. (1) by enumeration for a 3-bit mantissa: x = 1 + 3/32 lies 3/4 of the way from 1 to 1.125
     ups = sum(float(o.round_em(np.float32(1.09375), 3, 3, np.array(rr))) == 1.125 for rr in range(0, 65536, 64))
     assert ups == 1024 * 3 // 4
+
+
+def _em_grid(E, M):
+    """Every non-negative value of the (E, M) format of the IEEE pattern, as exact fractions, in
+    ascending order, with the mantissa code's parity (for ties to even)."""
+    from fractions import Fraction
+    bias = 2 ** (E - 1) - 1
+    vals = []
+    for e in range(0, 2 ** E - 1):                   # the top exponent code is reserved
+        for m in range(2 ** M):
+            v = Fraction(m, 2 ** M) * Fraction(2) ** (1 - bias) if e == 0 else (1 + Fraction(m, 2 ** M)) * Fraction(2) ** (e - bias)
+            vals.append((v, (e * 2 ** M + m) & 1))
+    return vals
+
+
+@pytest.mark.parametrize("E,M", [(3, 4), (2, 1), (4, 3), (6, 9)])
+def test_simulated_format_against_a_brute_force_over_its_whole_grid(E, M):
+    """Formats torch has no cast for: the oracle's formula against the definition carried out in
+    exact rational arithmetic -- enumerate every value of the format, find the two neighbours of
+    |x| by search, round to the nearer one (ties to the even code) or, stochastically, up iff
+    floor(2^16 (|x| - lo) / (hi - lo)) + r >= 2^16 -- on inputs in the subnormal range of the
+    format, across the subnormal / normal boundary, on grid points and midpoints, next to the
+    largest finite value and beyond it."""
+    import bisect
+    from fractions import Fraction
+    grid = _em_grid(E, M)
+    gv = [v for v, _ in grid]
+    top = gv[-1]
+    rng = np.random.default_rng(E * 100 + M)
+    pts = [float(v) for v in rng.choice(np.array([float(x) for x in gv]), 60)]
+    mids = [float((gv[i] + gv[i + 1]) / 2) for i in rng.integers(0, len(gv) - 1, 60)] + [float((gv[0] + gv[1]) / 2), float((gv[-2] + gv[-1]) / 2)]
+    sub = (rng.random(80) * float(gv[2 ** M]) * 1.5).tolist()                  # subnormals and the first normals
+    near_top = (float(top) * (1 + rng.uniform(-2.0 ** -M, 2.0 ** -M, 40))).tolist() + [float(top) * 1.5, float(top) * 64, 3.0e38]
+    wide = (np.exp(rng.uniform(np.log(float(gv[1]) / 4), np.log(float(top)), 300))).tolist()
+    x = np.array(pts + mids + sub + near_top + wide + [0.0], dtype=np.float32)
+    x = np.concatenate([x, -x])
+    r = rng.integers(0, 65536, size=x.size).astype(np.uint32)
+    got_rne = o.round_em(x, E, M)
+    got_sr = o.round_em(x, E, M, r)
+    for i, xv in enumerate(x.tolist()):
+        a = abs(Fraction(xv))
+        if a >= top:
+            want_rne = want_sr = top
+        else:
+            k = bisect.bisect_right(gv, a) - 1                                 # gv[k] <= a < gv[k + 1]
+            lo, hi = gv[k], gv[k + 1]
+            frac = (a - lo) / (hi - lo)
+            want_rne = hi if (frac > Fraction(1, 2) or (frac == Fraction(1, 2) and grid[k][1] == 1)) else lo
+            want_sr = hi if (int(frac * 65536) + int(r[i]) >= 65536) else lo
+        for name, got, want in (("nearest", got_rne[i], want_rne), ("stochastic", got_sr[i], want_sr)):
+            assert Fraction(float(abs(got))) == want, (E, M, name, xv, float(got), float(want))
+            assert np.signbit(got) == np.signbit(np.float32(xv))
+
+
+def test_update_rows_tracks_the_true_sum_over_many_steps_with_compensation():
+    """The update rule itself (not only the stand-alone Kahan stream) over 300 steps of the same
+    small gradient: without compensation round-to-nearest cancels every step (Section 4.1); with the
+    BF16 compensation the pair w - c follows w0 - n lr g, for BF16 and for E4M3 weights, under
+    nearest and under stochastic rounding."""
+    n_steps, lr = 300, 0.05
+    for fmt, w0, g in ((o.BF16, 1.0, 2.0**-6), (o.E4M3, 0.25, 2.0**-4)):      # lr g = 1/10 of a spacing (BF16), 1/10 (E4M3)
+        elem = np.arange(8, dtype=np.int64)
+        dW = np.full(8, g)
+        W0 = o.quantize(np.full(8, w0, np.float32), fmt)
+        Wp = W0.copy()
+        for s in range(20):
+            Wp, _ = o.update_rows(Wp, None, dW, lr, fmt, 0, 0, s, elem)
+        assert np.array_equal(Wp, W0)                                          # cancelled every time
+        for flags in (o.FLAG_KAHAN, o.FLAG_KAHAN | o.FLAG_SR):
+            W, C = W0.copy(), np.zeros(8, np.uint16)
+            for s in range(n_steps):
+                W, C = o.update_rows(W, C, dW, lr, fmt, flags, 3, s, elem)
+            true = w0 - n_steps * lr * g
+            est = o.decode(W, fmt).astype(np.float64) - o.decode_bf16(C).astype(np.float64)
+            spacing = {o.BF16: 2.0**-7, o.E4M3: 2.0**-3}[fmt] * 2.0 ** np.floor(np.log2(abs(true)))
+            assert np.all(np.abs(o.decode(W, fmt) - true) <= spacing)            # w itself within one spacing
+            # c is itself held in BF16: every step loses up to half a unit of c, i.e. 2^-9 (nearest; |c| <= spacing / 2) or
+            # 2^-8 (stochastic; |c| <= spacing) of a spacing, adding up like a random walk over the 300 steps
+            bound = spacing * (2.0**-3 if flags & o.FLAG_SR else 2.0**-5)
+            assert np.all(np.abs(est - true) <= bound), (fmt, flags, est, true)
