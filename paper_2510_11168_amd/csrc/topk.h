@@ -1,14 +1,20 @@
 // Top-k scoring over all labels (the top_k of the paper's P@k definition) for gfx950.
 //
-// The [B, L] score matrix is never formed.  Main path: the labels are visited in a few levels of
-// geometrically growing size (2048, then 16x more each time).  A level computes its logits tile
-// by tile on the matrix cores exactly as the training step does (E4M3 x E4M3 or BF16 x BF16,
-// FP32 accumulation) and appends every score that beats the row's threshold -- the k-th best
-// score over all earlier levels -- to the row's candidate list; a select kernel then sorts the
-// candidates, keeps the k best and raises the threshold.  A later label that merely ties the
-// threshold can never enter the top k (same score, larger id), so the comparison is strict and
-// the result exact.  With thresholds from 1/16 of the labels about 16 k candidates per row
-// survive a level; the lists hold 4096.  A row whose list overflows (scores rising steeply with
+// The [B, L] score matrix is never formed.  Main path: the labels are visited in levels of
+// geometrically growing size (the first 2048, then each level takes the labels seen so far from
+// N to 4 N).  A level computes its logits tile by tile on the matrix cores exactly as the
+// training step does (E4M3 x E4M3 or BF16 x BF16, FP32 accumulation) and appends every score that
+// beats the row's threshold -- the k-th best score over all earlier levels -- to the row's
+// candidate list; a select kernel then sorts the candidates, keeps the k best and raises the
+// threshold.  A later label that merely ties the threshold can never enter the top k (same score,
+// larger id), so the comparison is strict and the result exact.  With thresholds from a quarter
+// of the labels a level is expected to append about 3 k scores per row (scores in no particular
+// order along the label axis); the lists hold 4096.  Every append is an atomic addition on the
+// row's counter, and those cost more than anything else besides the product: with levels growing
+// 17-fold (about 16 k appends per row and level, 3600 per row in all at 3 M labels) the two middle
+// levels took up to five times their product's time; growing 4-fold (1500 appends per row in all,
+// and selects over 400 instead of 1700 candidates) measured 9 % faster end to end, 3-fold the same,
+// 2-fold slower again (more launches).  A row whose list overflows (scores rising steeply with
 // the label id) is flagged and recomputed by the fallback path below, which has no capacity
 // limit: 64 query rows per workgroup walk a label segment keeping a sorted k-list in LDS, and a
 // merge kernel joins the segments.  Order: score descending, label id ascending on ties.
@@ -30,7 +36,10 @@ namespace elmo {
 
 constexpr int kTopkMaxK = 128;                     // entries selected per sweep (one page)
 constexpr int kTopkCand = 4096;                    // candidate list length per row (main path)
-constexpr int kTopkLevel0 = 2048;                  // labels of the first level; later levels grow 16x
+constexpr int kTopkCntStride = 32;                 // ints between two rows' candidate counters: one 128-byte line each, so that the
+                                                   // atomic additions of different rows do not queue up on the same few lines
+constexpr int kTopkGrowth = 4;                     // labels seen after a level / labels seen before it
+constexpr int kTopkLevel0 = 2048;                  // labels of the first level
 constexpr int kTopkRows = 64;                       // query rows per workgroup
 constexpr int kTopkZP = 132;                        // floats per staged row
 constexpr int kTopkLP = 129;                        // list pitch (odd: one row per thread, no bank clash)
@@ -43,7 +52,7 @@ inline int topk_segments(int tiles_b) { return std::max(1, std::min(64, 512 / ti
 
 // Main-path scratch: thresholds, counters, overflow flags and candidate lists per (padded) row.
 inline size_t topk_main_rows(int Bp_max) { return (size_t)(Bp_max + 255) / 256 * 256; }
-inline size_t topk_main_bytes(int Bp_max) { return topk_main_rows(Bp_max) * (28 + (size_t)kTopkCand * 8) + 1024; }
+inline size_t topk_main_bytes(int Bp_max) { return topk_main_rows(Bp_max) * (24 + (size_t)kTopkCntStride * 4 + (size_t)kTopkCand * 8) + 1024; }
 
 // (score, id) strictly after the cursor (cs, ci) in the order score descending, id ascending.
 __device__ inline bool topk_after(float z, int l, float cs, int ci) { return z < cs || (z == cs && l > ci); }
@@ -249,7 +258,7 @@ __global__ void __launch_bounds__(kThreads) k_topk_merge(const float* __restrict
 __global__ void __launch_bounds__(kThreads) k_topk_init(float* __restrict__ tau, int* __restrict__ cnt, int* __restrict__ ovf, int rows,
                                                         int cnt0) {
   const int i = blockIdx.x * kThreads + threadIdx.x;
-  if (i < rows) { tau[i] = -INFINITY; cnt[i] = cnt0; ovf[i] = 0; }
+  if (i < rows) { tau[i] = -INFINITY; cnt[(size_t)i * kTopkCntStride] = cnt0; ovf[i] = 0; }
 }
 
 // Logits of labels [l_begin, l_begin + n) for all rows, 256 x 256 tiles as in the training step;
@@ -269,9 +278,9 @@ k_topk_filter(const char* __restrict__ Xa, int a_rows, const char* __restrict__ 
   const int lt = wg / tiles_b, bt = wg % tiles_b;
   const int b0 = bt << 8, l0 = lt << 8;
   const size_t rowb = (size_t)d * (FP8 ? 1 : 2);
-  f32x16 acc[2][4];
-  logits_tile_product<FP8, 256, 4>(Xa + (size_t)b0 * rowb, a_rows - b0, Wl + (size_t)l0 * rowb, n - l0, rowb, smem, wave, lane, acc);
-  float* tau_s = reinterpret_cast<float*>(smem);
+  // thresholds and cursors of the tile's rows: in LDS behind the ring, loaded before the product
+  // so that their way in overlaps the first slabs' (the K loop's barriers publish them)
+  float* tau_s = reinterpret_cast<float*>(smem + logits_mask_offset<256>());
   float* cs_s = tau_s + 256;                         // the rows' cursors (pages after the first), else +inf / -1
   int* ci_s = reinterpret_cast<int*>(cs_s + 256);
   const bool paged = cur_sc != nullptr;
@@ -280,7 +289,8 @@ k_topk_filter(const char* __restrict__ Xa, int a_rows, const char* __restrict__ 
     cs_s[i] = paged && b0 + i < B ? cur_sc[b0 + i] : INFINITY;
     ci_s[i] = paged && b0 + i < B ? cur_id[b0 + i] : -1;
   }
-  __syncthreads();
+  f32x16 acc[2][4];
+  logits_tile_product<FP8, 256, 4>(Xa + (size_t)b0 * rowb, a_rows - b0, Wl + (size_t)l0 * rowb, n - l0, rowb, smem, wave, lane, acc);
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -299,7 +309,7 @@ k_topk_filter(const char* __restrict__ Xa, int a_rows, const char* __restrict__ 
             cand_id[(size_t)row * kTopkCand + l] = live ? l_begin + l : INT_MAX;
           }
         } else if (l < n && z > t && (!paged || topk_after(z, l_begin + l, cs_s[b], ci_s[b]))) {
-          const int slot = atomicAdd(&cnt[row], 1);
+          const int slot = atomicAdd(&cnt[(size_t)row * kTopkCntStride], 1);
           if (slot < kTopkCand) {
             cand_sc[(size_t)row * kTopkCand + slot] = z;
             cand_id[(size_t)row * kTopkCand + slot] = l_begin + l;
@@ -319,7 +329,7 @@ __global__ void __launch_bounds__(kThreads) k_topk_select(float* __restrict__ ta
   __shared__ float sc[kTopkCand];
   __shared__ int id[kTopkCand];
   const int b = blockIdx.x, tid = threadIdx.x;
-  const int m = min(cnt[b], kTopkCand);
+  const int m = min(cnt[(size_t)b * kTopkCntStride], kTopkCand);
   int N2 = 2;
   while (N2 < max(m, k)) N2 <<= 1;                   // the first k sorted slots are read below even when fewer candidates exist
   for (int i = tid; i < N2; i += kThreads) {
@@ -334,7 +344,7 @@ __global__ void __launch_bounds__(kThreads) k_topk_select(float* __restrict__ ta
     cand_id[(size_t)b * kTopkCand + i] = id[i];
   }
   if (tid == 0) {
-    cnt[b] = keep;
+    cnt[(size_t)b * kTopkCntStride] = keep;
     tau[b] = m >= k ? sc[k - 1] : -INFINITY;
   }
   if (idx_out || score_out)
@@ -381,12 +391,13 @@ inline int topk_run(hipStream_t st, bool fp8, const char* Xa, int a_rows, const 
                     int B, int Bp, int k_total, char* scratch, int* idx_out, float* score_out, char* err, size_t errsz) {
   const size_t rows = topk_main_rows(Bp);
   float* tau = reinterpret_cast<float*>(scratch);
-  int* cnt = reinterpret_cast<int*>(scratch + rows * 4);
-  int* ovf = reinterpret_cast<int*>(scratch + rows * 8);
-  float* cursor_sc[2] = {reinterpret_cast<float*>(scratch + rows * 12), reinterpret_cast<float*>(scratch + rows * 16)};
-  int* cursor_id[2] = {reinterpret_cast<int*>(scratch + rows * 20), reinterpret_cast<int*>(scratch + rows * 24)};
-  float* cand_sc = reinterpret_cast<float*>(scratch + rows * 28);
-  int* cand_id = reinterpret_cast<int*>(scratch + rows * 28 + rows * (size_t)kTopkCand * 4);
+  int* ovf = reinterpret_cast<int*>(scratch + rows * 4);
+  float* cursor_sc[2] = {reinterpret_cast<float*>(scratch + rows * 8), reinterpret_cast<float*>(scratch + rows * 12)};
+  int* cursor_id[2] = {reinterpret_cast<int*>(scratch + rows * 16), reinterpret_cast<int*>(scratch + rows * 20)};
+  int* cnt = reinterpret_cast<int*>(scratch + rows * 24);                    // one counter per 128-byte line
+  const size_t lists0 = rows * (24 + (size_t)kTopkCntStride * 4);
+  float* cand_sc = reinterpret_cast<float*>(scratch + lists0);
+  int* cand_id = reinterpret_cast<int*>(scratch + lists0 + rows * (size_t)kTopkCand * 4);
   char* fb_scratch = scratch + topk_main_bytes(Bp);
   const size_t rowb = (size_t)d * (fp8 ? 1 : 2);
   static_assert(kTopkLevel0 <= kTopkCand, "the first level writes one slot per label");
@@ -417,7 +428,7 @@ inline int topk_run(hipStream_t st, bool fp8, const char* Xa, int a_rows, const 
     k_topk_init<<<(int)((rows + kThreads - 1) / kThreads), kThreads, 0, st>>>(tau, cnt, ovf, (int)rows,
                                                                                (int)std::min<int64_t>(L, kTopkLevel0));
     if (int rc = topk_launch_error("k_topk_init", err, errsz)) return rc;
-    for (int64_t begin = 0, end = std::min<int64_t>(L, kTopkLevel0); begin < L; begin = end, end = std::min<int64_t>(L, end * 17)) {
+    for (int64_t begin = 0, end = std::min<int64_t>(L, kTopkLevel0); begin < L; begin = end, end = std::min<int64_t>(L, end * kTopkGrowth)) {
       const int n = (int)(end - begin);
       const int grid = (n + 255) / 256 * tiles_b256;
       const char* Wl = W + (size_t)begin * rowb;
