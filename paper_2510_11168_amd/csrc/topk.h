@@ -255,22 +255,21 @@ __global__ void __launch_bounds__(kThreads) k_topk_merge(const float* __restrict
 // Main path: threshold filter fused into the logits tile, and the per-row select.
 // ---------------------------------------------------------------------------------------------
 // cnt0: candidates per row that the first level writes without counting (all of its labels).
+// Rows at or beyond B (padding up to whole 256-row tiles) get an infinite threshold: they never emit.
 __global__ void __launch_bounds__(kThreads) k_topk_init(float* __restrict__ tau, int* __restrict__ cnt, int* __restrict__ ovf, int rows,
-                                                        int cnt0) {
+                                                        int B, int cnt0) {
   const int i = blockIdx.x * kThreads + threadIdx.x;
-  if (i < rows) { tau[i] = -INFINITY; cnt[(size_t)i * kTopkCntStride] = cnt0; ovf[i] = 0; }
+  if (i < rows) { tau[i] = i < B ? -INFINITY : INFINITY; cnt[(size_t)i * kTopkCntStride] = cnt0; ovf[i] = 0; }
 }
 
-// Logits of labels [l_begin, l_begin + n) for all rows, 256 x 256 tiles as in the training step;
-// every score above its row's threshold is appended to that row's candidate list.  FIRST: the
-// first level has no threshold yet and at most kTopkCand labels: label l of the level goes to slot l
-// of every row, no counting (scores that could never be selected, NaN or -inf, are stored as
-// empty slots).
-template <bool FP8, bool FIRST>
+// Logits of labels [l_begin, l_begin + n) for all rows, 256 x 256 tiles as in the training step.
+// The first level has no threshold yet and at most kTopkCand labels: label l of the level goes to
+// slot l of every row, no counting (scores that could never be selected, NaN or -inf, are stored
+// as empty slots).
+template <bool FP8>
 __global__ void __launch_bounds__(kGemmThreads, 1)
-k_topk_filter(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wl, int n, int l_begin, int d, int Bp, int B,
-              const float* __restrict__ tau, int* __restrict__ cnt, int* __restrict__ ovf, float* __restrict__ cand_sc,
-              int* __restrict__ cand_id, const float* __restrict__ cur_sc, const int* __restrict__ cur_id) {
+k_topk_first(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wl, int n, int l_begin, int d, int Bp, int B,
+             float* __restrict__ cand_sc, int* __restrict__ cand_id, const float* __restrict__ cur_sc, const int* __restrict__ cur_id) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave >> 1, wn = wave & 1;
   const int tiles_b = (Bp + 255) >> 8;
@@ -278,14 +277,12 @@ k_topk_filter(const char* __restrict__ Xa, int a_rows, const char* __restrict__ 
   const int lt = wg / tiles_b, bt = wg % tiles_b;
   const int b0 = bt << 8, l0 = lt << 8;
   const size_t rowb = (size_t)d * (FP8 ? 1 : 2);
-  // thresholds and cursors of the tile's rows: in LDS behind the ring, loaded before the product
-  // so that their way in overlaps the first slabs' (the K loop's barriers publish them)
-  float* tau_s = reinterpret_cast<float*>(smem + logits_mask_offset<256>());
-  float* cs_s = tau_s + 256;                         // the rows' cursors (pages after the first), else +inf / -1
+  // cursors of the tile's rows (pages after the first), else +inf / -1: in LDS behind the ring,
+  // loaded before the product (the K loop's barriers publish them)
+  float* cs_s = reinterpret_cast<float*>(smem + logits_mask_offset<256>());
   int* ci_s = reinterpret_cast<int*>(cs_s + 256);
   const bool paged = cur_sc != nullptr;
   for (int i = tid; i < 256; i += kGemmThreads) {
-    tau_s[i] = b0 + i < B ? tau[b0 + i] : INFINITY;   // padding rows never emit
     cs_s[i] = paged && b0 + i < B ? cur_sc[b0 + i] : INFINITY;
     ci_s[i] = paged && b0 + i < B ? cur_id[b0 + i] : -1;
   }
@@ -297,28 +294,189 @@ k_topk_filter(const char* __restrict__ Xa, int a_rows, const char* __restrict__ 
     for (int v = 0; v < 16; ++v) {
       const int b = wm * 64 + 32 * i + acc_row(v, lane);
       const int row = b0 + b;
-      const float t = tau_s[b];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int l = l0 + wn * 128 + 32 * j + (lane & 31);
         const float z = acc[i][j][v];
-        if (FIRST) {
-          if (l < n && row < B) {
-            const bool live = z > -INFINITY && (!paged || topk_after(z, l_begin + l, cs_s[b], ci_s[b]));
-            cand_sc[(size_t)row * kTopkCand + l] = live ? z : -INFINITY;
-            cand_id[(size_t)row * kTopkCand + l] = live ? l_begin + l : INT_MAX;
-          }
-        } else if (l < n && z > t && (!paged || topk_after(z, l_begin + l, cs_s[b], ci_s[b]))) {
-          const int slot = atomicAdd(&cnt[(size_t)row * kTopkCntStride], 1);
-          if (slot < kTopkCand) {
-            cand_sc[(size_t)row * kTopkCand + slot] = z;
-            cand_id[(size_t)row * kTopkCand + slot] = l_begin + l;
-          } else {
-            ovf[row] = 1;
-          }
+        if (l < n && row < B) {
+          const bool live = z > -INFINITY && (!paged || topk_after(z, l_begin + l, cs_s[b], ci_s[b]));
+          cand_sc[(size_t)row * kTopkCand + l] = live ? z : -INFINITY;
+          cand_id[(size_t)row * kTopkCand + l] = live ? l_begin + l : INT_MAX;
         }
       }
     }
+}
+
+// The levels after the first: one workgroup per CU walks the tiles w, w + gridDim, ... of the level
+// and keeps the ring of K slabs running from one tile into the next, so a tile's first slabs are
+// on their way while the tile before it is being filtered (a workgroup per tile pays the first
+// slab's round trip, a third of a tile's K loop at d = 768, and the launch of the next workgroup
+// between any two tiles of a CU).  The thresholds (and cursors) of a tile's 256 rows are fetched
+// by asynchronous loads into one of two LDS buffers behind the ring a tile ahead; the two-stage
+// ring waits for all of a wave's loads at every slab, so they need no accounting of their own.
+// DENSE: for the small early levels, where a large share of the scores still passes (several per
+// row among a wave's 128 labels): the 32 lanes of a half wave hold 4 x 32 labels of one row per
+// accumulator index (i, v); the half's first lane reserves the slots of all of the half's passes
+// with one atomic addition, the sixteen additions of one i are issued before the first result is
+// waited for, and the slots are handed out by position in the vote masks.  With one addition per
+// passing score these levels took four times their product's time; in the large levels, where a
+// wave rarely sees two passes of one row, the plain form is the faster one.
+template <bool FP8, bool DENSE>
+__global__ void __launch_bounds__(kGemmThreads, 1)
+k_topk_filter_run(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wl, int n, int l_begin, int d, int Bp,
+                  const float* __restrict__ tau, int* __restrict__ cnt, int* __restrict__ ovf, float* __restrict__ cand_sc,
+                  int* __restrict__ cand_id, const float* __restrict__ cur_sc, const int* __restrict__ cur_id) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave >> 1, wn = wave & 1;
+  const int tiles_b = (Bp + 255) >> 8, ntiles = ((n + 255) >> 8) * tiles_b;
+  const int G = (int)gridDim.x, w0 = (int)blockIdx.x;
+  if (w0 >= ntiles) return;
+  const int mine = (ntiles - w0 + G - 1) / G;                          // this workgroup's tiles
+  const size_t rowb = (size_t)d * (FP8 ? 1 : 2);
+  const int nk = (int)(rowb >> 7);
+  const bool paged = cur_sc != nullptr;
+  constexpr int kSide = 3 * 256 * 4;                                   // [thresholds | cursor scores | cursor ids] of 256 rows
+  char* side = smem + logits_mask_offset<256>();
+  static_assert(2 * kSide <= 256 * 8 * 4, "the two side buffers take the place of the training kernel's mask");
+  auto tile_of = [&](int t, int& b0, int& l0) {
+    const int wg = xcd_logical_id(w0 + t * G, ntiles);
+    l0 = (wg / tiles_b) << 8;
+    b0 = (wg % tiles_b) << 8;
+  };
+  auto dma_rows = [&](const void* src, char* dst) {                    // 256 consecutive 4-byte values -> LDS, issued by one wave
+    const char* g = reinterpret_cast<const char*>(src);
+    uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)g), hi = __builtin_amdgcn_readfirstlane((uint32_t)((uintptr_t)g >> 32));
+    asm volatile("" : "+s"(lo), "+s"(hi));
+    g = reinterpret_cast<const char*>(((uintptr_t)hi << 32) | lo);
+    const uint32_t d32 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(d32), "v"((uint32_t)(lane * 16)), "s"(g) : "memory", "m0");
+  };
+  auto fetch_side = [&](int t) {
+    if (wave != 0 || t >= mine) return;
+    int b0, l0;
+    tile_of(t, b0, l0);
+    char* dst = side + (t & 1) * kSide;
+    dma_rows(tau + b0, dst);
+    if (paged) {
+      dma_rows(cur_sc + b0, dst + 1024);
+      dma_rows(cur_id + b0, dst + 2048);
+    }
+  };
+  f32x16 acc[2][4];
+  auto filter = [&](int t) {
+    int b0, l0;
+    tile_of(t, b0, l0);
+    const float* tau_s = reinterpret_cast<const float*>(side + (t & 1) * kSide);
+    const float* cs_s = tau_s + 256;
+    const int* ci_s = reinterpret_cast<const int*>(cs_s + 256);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int b = wm * 64 + 32 * i + acc_row(v, lane);
+        const float th = tau_s[b];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int l = l0 + wn * 128 + 32 * j + (lane & 31);
+          const float z = acc[i][j][v];
+          if (l < n && z > th && (!paged || topk_after(z, l_begin + l, cs_s[b], ci_s[b]))) {
+            const int row = b0 + b;
+            const int slot = atomicAdd(&cnt[(size_t)row * kTopkCntStride], 1);
+            if (slot < kTopkCand) {
+              cand_sc[(size_t)row * kTopkCand + slot] = z;
+              cand_id[(size_t)row * kTopkCand + slot] = l_begin + l;
+            } else {
+              ovf[row] = 1;
+            }
+          }
+        }
+      }
+  };
+  auto filter_dense = [&](int t) {
+    int b0, l0;
+    tile_of(t, b0, l0);
+    const float* tau_s = reinterpret_cast<const float*>(side + (t & 1) * kSide);
+    const float* cs_s = tau_s + 256;
+    const int* ci_s = reinterpret_cast<const int*>(cs_s + 256);
+    const int half = lane >> 5;
+    const uint32_t below = (1u << (lane & 31)) - 1u;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      uint32_t pbits[4] = {0u, 0u, 0u, 0u};                              // bit v of pbits[j]: acc[i][j][v] passes
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int b = wm * 64 + 32 * i + acc_row(v, lane);
+        const float th = tau_s[b];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int l = l0 + wn * 128 + 32 * j + (lane & 31);
+          const float z = acc[i][j][v];
+          const bool pass = l < n && z > th && (!paged || topk_after(z, l_begin + l, cs_s[b], ci_s[b]));
+          pbits[j] |= (uint32_t)pass << v;
+        }
+      }
+      const uint32_t anyj = pbits[0] | pbits[1] | pbits[2] | pbits[3];
+      if (__builtin_amdgcn_ballot_w64(anyj != 0u) == 0ull) continue;
+      int base[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        base[v] = 0;
+        if (__builtin_amdgcn_ballot_w64((anyj >> v) & 1u) == 0ull) continue;
+        uint32_t tot = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint64_t bal = __builtin_amdgcn_ballot_w64((pbits[j] >> v) & 1u);
+          tot += __builtin_popcount(half ? (uint32_t)(bal >> 32) : (uint32_t)bal);
+        }
+        if ((lane & 31) == 0 && tot != 0u)
+          base[v] = atomicAdd(&cnt[(size_t)(b0 + wm * 64 + 32 * i + acc_row(v, lane)) * kTopkCntStride], (int)tot);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) asm volatile("" : "+v"(pbits[j]));      // the votes are taken again below rather than kept over the additions
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        if (__builtin_amdgcn_ballot_w64((anyj >> v) & 1u) == 0ull) continue;
+        const int base_lo = __builtin_amdgcn_readlane(base[v], 0), base_hi = __builtin_amdgcn_readlane(base[v], 32);
+        int run = half ? base_hi : base_lo;
+        const int row = b0 + wm * 64 + 32 * i + acc_row(v, lane);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const bool pass = (pbits[j] >> v) & 1u;
+          const uint64_t bal = __builtin_amdgcn_ballot_w64(pass);
+          const uint32_t mine_m = half ? (uint32_t)(bal >> 32) : (uint32_t)bal;
+          if (pass) {
+            const int slot = run + __builtin_popcount(mine_m & below);
+            if (slot < kTopkCand) {
+              cand_sc[(size_t)row * kTopkCand + slot] = acc[i][j][v];
+              cand_id[(size_t)row * kTopkCand + slot] = l_begin + l0 + wn * 128 + 32 * j + (lane & 31);
+            } else {
+              ovf[row] = 1;
+            }
+          }
+          run += __builtin_popcount(mine_m);
+        }
+      }
+    }
+  };
+  fetch_side(0);
+  ring_stream_pp<256, 128, 256, 128, 2, kGemmWaves, true>(
+      Xa, rowb, 8, Wl, rowb, 8, mine * nk, smem, wave, lane,
+      [&](int ks, size_t& off_a, int& va, size_t& off_b, int& vb) {
+        const int t = ks / nk, sl = ks - t * nk;
+        int b0, l0;
+        tile_of(t, b0, l0);
+        off_a = (size_t)b0 * rowb + (size_t)sl * 128; va = a_rows - b0;
+        off_b = (size_t)l0 * rowb + (size_t)sl * 128; vb = n - l0;
+      },
+      [&](const char* sa, const char* sb, int q0, int q1, int ks) {
+        const int t = ks / nk, sl = ks - t * nk;
+        if (q0 == 0 && sl == 0) {
+          zero_acc(acc);
+          fetch_side(t + 1);
+        }
+        logits_slab_product<FP8, 4>(sa, sb, q0 >> 1, wm, wn, lane, acc);
+        if (q1 == 4 && sl == nk - 1) { if constexpr (DENSE) filter_dense(t); else filter(t); }
+      });
 }
 
 // Per row: sort the candidates, keep the k best at the front of the list, raise the threshold.
@@ -425,7 +583,7 @@ inline int topk_run(hipStream_t st, bool fp8, const char* Xa, int a_rows, const 
     float* ns = more ? cursor_sc[(page + 1) & 1] : nullptr;
     int* ni = more ? cursor_id[(page + 1) & 1] : nullptr;
     // ---- main path
-    k_topk_init<<<(int)((rows + kThreads - 1) / kThreads), kThreads, 0, st>>>(tau, cnt, ovf, (int)rows,
+    k_topk_init<<<(int)((rows + kThreads - 1) / kThreads), kThreads, 0, st>>>(tau, cnt, ovf, (int)rows, B,
                                                                                (int)std::min<int64_t>(L, kTopkLevel0));
     if (int rc = topk_launch_error("k_topk_init", err, errsz)) return rc;
     for (int64_t begin = 0, end = std::min<int64_t>(L, kTopkLevel0); begin < L; begin = end, end = std::min<int64_t>(L, end * kTopkGrowth)) {
@@ -433,14 +591,21 @@ inline int topk_run(hipStream_t st, bool fp8, const char* Xa, int a_rows, const 
       const int grid = (n + 255) / 256 * tiles_b256;
       const char* Wl = W + (size_t)begin * rowb;
       const bool first = begin == 0;
-#define ELMO_TOPK_FILTER(F, FI) \
-  k_topk_filter<F, FI><<<grid, kGemmThreads, logits_smem<256>(), st>>>(Xa, a_rows, Wl, n, (int)begin, d, Bp, B, tau, cnt, ovf, cand_sc, cand_id, cs, ci)
-      if (fp8 && first) ELMO_TOPK_FILTER(true, true);
-      else if (fp8) ELMO_TOPK_FILTER(true, false);
-      else if (first) ELMO_TOPK_FILTER(false, true);
-      else ELMO_TOPK_FILTER(false, false);
-#undef ELMO_TOPK_FILTER
-      if (int rc = topk_launch_error("k_topk_filter", err, errsz)) return rc;
+#define ELMO_TOPK_FIRST(F) \
+  k_topk_first<F><<<grid, kGemmThreads, logits_smem<256>(), st>>>(Xa, a_rows, Wl, n, (int)begin, d, Bp, B, cand_sc, cand_id, cs, ci)
+#define ELMO_TOPK_FILTER_RUN(F, DE) \
+  k_topk_filter_run<F, DE><<<std::min(grid, 256), kGemmThreads, logits_smem<256>(), st>>>(Xa, a_rows, Wl, n, (int)begin, d, Bp, tau, cnt, ovf, cand_sc, cand_id, cs, ci)
+      // expected passes per row among a wave's 128 labels of this level: k (growth - 1) 128 / n
+      const bool dense = (int64_t)k * (kTopkGrowth - 1) * 128 >= n;
+      if (fp8 && first) ELMO_TOPK_FIRST(true);
+      else if (first) ELMO_TOPK_FIRST(false);
+      else if (fp8 && dense) ELMO_TOPK_FILTER_RUN(true, true);
+      else if (fp8) ELMO_TOPK_FILTER_RUN(true, false);
+      else if (dense) ELMO_TOPK_FILTER_RUN(false, true);
+      else ELMO_TOPK_FILTER_RUN(false, false);
+#undef ELMO_TOPK_FIRST
+#undef ELMO_TOPK_FILTER_RUN
+      if (int rc = topk_launch_error("top-k level kernel", err, errsz)) return rc;
       const bool last = end == L;
       k_topk_select<<<B, kThreads, 0, st>>>(tau, cnt, cand_sc, cand_id, k, last ? idx_out : nullptr, last ? score_out : nullptr,
                                             k_total, off, last ? ns : nullptr, last ? ni : nullptr);
