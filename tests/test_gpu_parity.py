@@ -852,6 +852,21 @@ def test_topk_small_brute_force(b, fmt):
         _check_topk(b, case.head, case.W0, X, k, fmt)
 
 
+@pytest.mark.parametrize("fmt", [o.E4M3, o.BF16])
+def test_topk_one_slab_per_tile_and_several_batch_tiles(b, fmt):
+    """d = 128: an E4M3 tile is a single 128-byte K slab, so the kernel that keeps its ring running from
+    tile to tile changes tile at every slab (thresholds of the next tile's rows fetched a tile ahead);
+    300 queries are two batch tiles, the second ragged; 9000 + 5 labels are the first level, three
+    more levels (one of them with the aggregated appends) and a ragged last label tile; k = 100 and a
+    second page (k = 130)."""
+    L, d, B = 9000 + 5, 128, 300
+    case = Case(b, L, d, fmt, 4096, 0, B, w_std=0.05, seed=23)
+    X = synth.make_x(np.random.default_rng(5), B, d)
+    for k in (100, 130):
+        say(f"[topk-one-slab] fmt={fmt} k={k}")
+        _check_topk(b, case.head, case.W0, X, k, fmt)
+
+
 @pytest.mark.parametrize("fmt,L,B,ks", [(o.E4M3, 3000 + 17, 70, (129, 300, 500)), (o.BF16, 300, 9, (256, 300)), (o.E4M3, 131, 3, (131,))])
 def test_topk_beyond_one_page(b, fmt, L, B, ks):
     """k above 128 comes in pages of 128 entries, every page one more sweep that admits only what
