@@ -8,10 +8,10 @@
 // candidate list; a select kernel then sorts the candidates, keeps the k best and raises the
 // threshold.  A later label that merely ties the threshold can never enter the top k (same score,
 // larger id), so the comparison is strict and the result exact.  With thresholds from a quarter
-// of the labels a level is expected to append about 3 k scores per row (scores in no particular
+// of the labels a level is expected to append about 3 x k scores per row (scores in no particular
 // order along the label axis); the lists hold 4096.  Every append is an atomic addition on the
 // row's counter, and those cost more than anything else besides the product: with levels growing
-// 17-fold (about 16 k appends per row and level, 3600 per row in all at 3 M labels) the two middle
+// 17-fold (about 16 x k appends per row and level, 3600 per row in all at 3 M labels and k = 100) the two middle
 // levels took up to five times their product's time; growing 4-fold (1500 appends per row in all,
 // and selects over 400 instead of 1700 candidates) measured 9 % faster end to end, 3-fold the same,
 // 2-fold slower again (more launches).  A row whose list overflows (scores rising steeply with
