@@ -4,7 +4,7 @@
 A step = one pass of the whole hot path (step set-up, then per label chunk: logits + BCE epilogue,
 input gradient, fused update -- the last two in one kernel when the batch is at most 128 rows --;
 then the finalise kernel) over one fresh synthetic batch that is already resident in HBM.
-Default workload: the 3M-label FP8 head of the benchmark spec (L = 3,000,000, d = 768, B = 1024, E4M3
+Default workload: the 3M-label FP8 head, the headline configuration (L = 3,000,000, d = 768, B = 1024, E4M3
 weights + BF16 Kahan buffer + stochastic rounding, about 8 Zipf(1.05) positives per sample,
 chunk = 131072).
 

@@ -252,7 +252,7 @@ def check_step(case, X, indptr, indices, lr, seed, step, tol, W_before=None, C_b
 
 
 def test_tiny_config_three_steps(b):
-    """BASELINE config 1: L=8192, d=256, B=64, BF16 + SR, chunk 2048, lr 0.05, 3 steps."""
+    """Benchmark configuration 1: L=8192, d=256, B=64, BF16 + SR, chunk 2048, lr 0.05, 3 steps."""
     cfg = synth.CONFIGS["tiny"]
     case = Case(b, cfg.L, cfg.d, cfg.fmt, cfg.chunk, cfg.flags, cfg.B)
     zipf = synth.ZipfLabels(cfg.L, cfg.zipf_s)
@@ -720,7 +720,7 @@ def _init_on_device(b, head, cfg, seed=0):
 
 @pytest.mark.parametrize("name,dx_rows", [("mid", 16), ("large", 16), ("xl", 16)])
 def test_full_size_configs_on_samples(b, name, dx_rows):
-    """BASELINE configs 2-4 at full size in the launch configuration the benchmark times.
+    """Benchmark configurations 2-4 at full size in the launch configuration the benchmark times.
     Labels are independent given X, so the oracle evaluates a label sample exactly (all in-batch
     positives, chunk-boundary rows, the ragged tail, random rows) and a few full rows of dX."""
     _full_size_check(b, synth.CONFIGS[name], name, dx_rows, 2)
@@ -730,7 +730,7 @@ def test_full_size_configs_on_samples(b, name, dx_rows):
     (128, 262144, True, 16), (128, 65536, False, 16), (32, 65536, True, 16), (32, 262144, False, 16),
     (4096, 65536, False, 16), (4096, 262144, True, 16)])
 def test_xl_sweep_points_on_samples(b, B, chunk, kahan, dx_rows):
-    """BASELINE config 5 (the bandwidth-regime sweep at 3M labels) at full size, in the launch
+    """Benchmark configuration 5 (the bandwidth-regime sweep at 3M labels) at full size, in the launch
     configurations the benchmark times: all six (batch, chunk) points -- the small-batch kernels at
     B = 128 and B = 32, the 256 x 256-tile kernels with 16 batch tiles at B = 4096 -- with the
     compensation buffer on one chunk size of each batch and off on the other."""
@@ -739,7 +739,7 @@ def test_xl_sweep_points_on_samples(b, B, chunk, kahan, dx_rows):
 
 
 def test_xl_config_step_after_twenty_unchecked_steps(b):
-    """BASELINE config 4 runs 20 steps: the first 19 are only run (fresh batch each, as in the
+    """Benchmark configuration 4 runs 20 steps: the first 19 are only run (fresh batch each, as in the
     benchmark), the 20th is checked against the oracle started from the device state before it --
     what an error that builds up in the reused workspace or the compensation would break."""
     _full_size_check(b, synth.CONFIGS["xl"], "xl after 19 steps", 2, 1, unchecked=19)
@@ -1000,7 +1000,7 @@ def test_topk_mid_size(b):
 
 
 def test_topk_xl_k100_on_sampled_queries(b):
-    """BASELINE config 5, inference part: elmo_head_topk with k = 100 over all 3M logits for 1024
+    """Benchmark configuration 5, inference part: elmo_head_topk with k = 100 over all 3M logits for 1024
     queries.  Every row is checked for shape properties (distinct ids in range, scores sorted);
     sixteen sampled rows are checked against the oracle's logits over all labels (scores, validity
     and completeness of the returned set)."""
