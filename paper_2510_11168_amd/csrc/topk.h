@@ -14,7 +14,10 @@
 // 17-fold (about 16 x k appends per row and level, 3600 per row in all at 3 M labels and k = 100) the two middle
 // levels took up to five times their product's time; growing 4-fold (1500 appends per row in all,
 // and selects over 400 instead of 1700 candidates) measured 9 % faster end to end, 3-fold the same,
-// 2-fold slower again (more launches).  A row whose list overflows (scores rising steeply with
+// 2-fold slower again (more launches).  In the large levels a pass is rare (a few per row and
+// million labels), so the filter first takes one wave-wide vote per sample on the largest of a
+// lane's four scores and skips the four compares when no lane passes (13 % end to end).
+// A row whose list overflows (scores rising steeply with
 // the label id) is flagged and recomputed by the fallback path below, which has no capacity
 // limit: 64 query rows per workgroup walk a label segment keeping a sorted k-list in LDS, and a
 // merge kernel joins the segments.  Order: score descending, label id ascending on ties.
@@ -375,6 +378,10 @@ k_topk_filter_run(const char* __restrict__ Xa, int a_rows, const char* __restric
       for (int v = 0; v < 16; ++v) {
         const int b = wm * 64 + 32 * i + acc_row(v, lane);
         const float th = tau_s[b];
+        // passes are rare in these levels (a few per row and million labels): one vote on the largest of the
+        // lane's four scores of this sample skips the rest for the whole wave nine times out of ten
+        const float zmax = fmaxf(fmaxf(acc[i][0][v], acc[i][1][v]), fmaxf(acc[i][2][v], acc[i][3][v]));
+        if (__builtin_amdgcn_ballot_w64(zmax > th) == 0ull) continue;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const int l = l0 + wn * 128 + 32 * j + (lane & 31);
