@@ -371,10 +371,10 @@ int raise_lds_limits_once() {
   ELMO_ATTR((elmo::k_dx<false, true>), elmo::dx_smem_bytes<false>());
   ELMO_ATTR((elmo::k_topk_first<true>), elmo::logits_smem<256>());
   ELMO_ATTR((elmo::k_topk_first<false>), elmo::logits_smem<256>());
-  ELMO_ATTR((elmo::k_topk_filter_run<true, true>), elmo::logits_smem<256>());
-  ELMO_ATTR((elmo::k_topk_filter_run<true, false>), elmo::logits_smem<256>());
-  ELMO_ATTR((elmo::k_topk_filter_run<false, true>), elmo::logits_smem<256>());
-  ELMO_ATTR((elmo::k_topk_filter_run<false, false>), elmo::logits_smem<256>());
+  ELMO_ATTR((elmo::k_topk_filter_run<true, true>), elmo::kTopkRunSmem);
+  ELMO_ATTR((elmo::k_topk_filter_run<true, false>), elmo::kTopkRunSmem);
+  ELMO_ATTR((elmo::k_topk_filter_run<false, true>), elmo::kTopkRunSmem);
+  ELMO_ATTR((elmo::k_topk_filter_run<false, false>), elmo::kTopkRunSmem);
   ELMO_ATTR((elmo::k_topk_chunk<true>), elmo::kTopkSmem);
   ELMO_ATTR((elmo::k_topk_chunk<false>), elmo::kTopkSmem);
 #undef ELMO_ATTR

@@ -324,6 +324,17 @@ k_topk_first(const char* __restrict__ Xa, int a_rows, const char* __restrict__ W
 // waited for, and the slots are handed out by position in the vote masks.  With one addition per
 // passing score these levels took four times their product's time; in the large levels, where a
 // wave rarely sees two passes of one row, the plain form is the faster one.
+// Large levels, appends: a row's counter is shared by every workgroup that holds one of the row's
+// tiles, on all XCDs, so an append is a device-scope atomic addition carried out at the memory
+// side, and the wave waits a memory round trip for its slot before it can go on.  A workgroup
+// therefore keeps one batch tile for all of its label tiles (the grid is a multiple of the number
+// of batch tiles) and collects its passes in LDS lists of kTopkLdsCap entries per row (LDS
+// atomics); at its end it reserves each row's slots with one global addition and copies the
+// entries.  A row whose LDS list is full appends directly as before.
+constexpr int kTopkLdsCap = 8;
+constexpr int kTopkSide = 3 * 256 * 4;                // [thresholds | cursor scores | cursor ids] of a tile's 256 rows
+constexpr int kTopkRunSmem = kWideRingBytes + 2 * kTopkSide + 256 * 4 + 256 * kTopkLdsCap * 8;   // ring, two side buffers, LDS lists
+static_assert(kTopkRunSmem <= 160 * 1024, "LDS plan of the persistent filter");
 template <bool FP8, bool DENSE>
 __global__ void __launch_bounds__(kGemmThreads, 1)
 k_topk_filter_run(const char* __restrict__ Xa, int a_rows, const char* __restrict__ Wl, int n, int l_begin, int d, int Bp,
@@ -332,20 +343,25 @@ k_topk_filter_run(const char* __restrict__ Xa, int a_rows, const char* __restric
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave >> 1, wn = wave & 1;
   const int tiles_b = (Bp + 255) >> 8, ntiles = ((n + 255) >> 8) * tiles_b;
-  const int G = (int)gridDim.x, w0 = (int)blockIdx.x;
+  const int G = (int)gridDim.x, w0 = xcd_logical_id((int)blockIdx.x, (int)gridDim.x);   // consecutive w0 share an XCD (and a label tile)
   if (w0 >= ntiles) return;
-  const int mine = (ntiles - w0 + G - 1) / G;                          // this workgroup's tiles
+  const int mine = (ntiles - w0 + G - 1) / G;                          // this workgroup's tiles: w0, w0 + G, ...
+  const bool agg = !DENSE && G % tiles_b == 0;                         // one batch tile for all of them: passes collect in LDS
   const size_t rowb = (size_t)d * (FP8 ? 1 : 2);
   const int nk = (int)(rowb >> 7);
   const bool paged = cur_sc != nullptr;
-  constexpr int kSide = 3 * 256 * 4;                                   // [thresholds | cursor scores | cursor ids] of 256 rows
-  char* side = smem + logits_mask_offset<256>();
-  static_assert(2 * kSide <= 256 * 8 * 4, "the two side buffers take the place of the training kernel's mask");
+  constexpr int kSide = kTopkSide;
+  char* side = smem + kWideRingBytes;                                  // behind the ring
   auto tile_of = [&](int t, int& b0, int& l0) {
-    const int wg = xcd_logical_id(w0 + t * G, ntiles);
+    const int wg = w0 + t * G;
     l0 = (wg / tiles_b) << 8;
     b0 = (wg % tiles_b) << 8;
   };
+  char* lists = side + 2 * kSide;                                      // [256 rows][kTopkLdsCap] (score, id) pairs, then 256 counters
+  if (agg) {
+    for (int i = tid; i < 256; i += kGemmThreads) reinterpret_cast<int*>(lists + 256 * kTopkLdsCap * 8)[i] = 0;
+    barrier_lds();
+  }
   auto dma_rows = [&](const void* src, char* dst) {                    // 256 consecutive 4-byte values -> LDS, issued by one wave
     const char* g = reinterpret_cast<const char*>(src);
     uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)g), hi = __builtin_amdgcn_readfirstlane((uint32_t)((uintptr_t)g >> 32));
@@ -382,12 +398,24 @@ k_topk_filter_run(const char* __restrict__ Xa, int a_rows, const char* __restric
         // lane's four scores of this sample skips the rest for the whole wave nine times out of ten
         const float zmax = fmaxf(fmaxf(acc[i][0][v], acc[i][1][v]), fmaxf(acc[i][2][v], acc[i][3][v]));
         if (__builtin_amdgcn_ballot_w64(zmax > th) == 0ull) continue;
+        // everything the rare branch needs is formed inside it, from an opaque copy of the lane index: nothing of it
+        // is held in registers through the product
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        const int bb = wm * 64 + 32 * i + acc_row(v, ln);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const int l = l0 + wn * 128 + 32 * j + (lane & 31);
+          const int l = l0 + wn * 128 + 32 * j + (ln & 31);
           const float z = acc[i][j][v];
-          if (l < n && z > th && (!paged || topk_after(z, l_begin + l, cs_s[b], ci_s[b]))) {
-            const int row = b0 + b;
+          if (l < n && z > th && (!paged || topk_after(z, l_begin + l, cs_s[bb], ci_s[bb]))) {
+            const int row = b0 + bb;
+            if (agg) {
+              const int ls = atomicAdd(reinterpret_cast<int*>(lists + 256 * kTopkLdsCap * 8) + bb, 1);
+              if (ls < kTopkLdsCap) {
+                *reinterpret_cast<int2*>(lists + (bb * kTopkLdsCap + ls) * 8) = make_int2(__float_as_int(z), l_begin + l);
+                continue;
+              }
+            }
             const int slot = atomicAdd(&cnt[(size_t)row * kTopkCntStride], 1);
             if (slot < kTopkCand) {
               cand_sc[(size_t)row * kTopkCand + slot] = z;
@@ -484,6 +512,26 @@ k_topk_filter_run(const char* __restrict__ Xa, int a_rows, const char* __restric
         logits_slab_product<FP8, 4>(sa, sb, q0 >> 1, wm, wn, lane, acc);
         if (q1 == 4 && sl == nk - 1) { if constexpr (DENSE) filter_dense(t); else filter(t); }
       });
+  if (agg) {
+    barrier_lds();                                                     // every wave's LDS appends are in
+    int b0, l0;
+    tile_of(0, b0, l0);
+    for (int r = tid; r < 256; r += kGemmThreads) {
+      const int c = min(reinterpret_cast<const int*>(lists + 256 * kTopkLdsCap * 8)[r], kTopkLdsCap);
+      if (c == 0) continue;
+      const int row = b0 + r;
+      const int base = atomicAdd(&cnt[(size_t)row * kTopkCntStride], c);
+      for (int e = 0; e < c; ++e) {
+        const int2 en = *reinterpret_cast<const int2*>(lists + (r * kTopkLdsCap + e) * 8);
+        if (base + e < kTopkCand) {
+          cand_sc[(size_t)row * kTopkCand + base + e] = __int_as_float(en.x);
+          cand_id[(size_t)row * kTopkCand + base + e] = en.y;
+        } else {
+          ovf[row] = 1;
+        }
+      }
+    }
+  }
 }
 
 // Per row: sort the candidates, keep the k best at the front of the list, raise the threshold.
@@ -598,10 +646,12 @@ inline int topk_run(hipStream_t st, bool fp8, const char* Xa, int a_rows, const 
       const int grid = (n + 255) / 256 * tiles_b256;
       const char* Wl = W + (size_t)begin * rowb;
       const bool first = begin == 0;
+      // persistent levels: at most one workgroup per CU, a multiple of the batch tiles when there are enough of them
+      const int run_grid = grid <= 256 ? grid : (tiles_b256 <= 256 ? 256 - 256 % tiles_b256 : 256);
 #define ELMO_TOPK_FIRST(F) \
   k_topk_first<F><<<grid, kGemmThreads, logits_smem<256>(), st>>>(Xa, a_rows, Wl, n, (int)begin, d, Bp, B, cand_sc, cand_id, cs, ci)
 #define ELMO_TOPK_FILTER_RUN(F, DE) \
-  k_topk_filter_run<F, DE><<<std::min(grid, 256), kGemmThreads, logits_smem<256>(), st>>>(Xa, a_rows, Wl, n, (int)begin, d, Bp, tau, cnt, ovf, cand_sc, cand_id, cs, ci)
+  k_topk_filter_run<F, DE><<<run_grid, kGemmThreads, kTopkRunSmem, st>>>(Xa, a_rows, Wl, n, (int)begin, d, Bp, tau, cnt, ovf, cand_sc, cand_id, cs, ci)
       // expected passes per row among a wave's 128 labels of this level: k (growth - 1) 128 / n
       const bool dense = (int64_t)k * (kTopkGrowth - 1) * 128 >= n;
       if (fp8 && first) ELMO_TOPK_FIRST(true);

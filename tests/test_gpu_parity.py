@@ -867,6 +867,21 @@ def test_topk_one_slab_per_tile_and_several_batch_tiles(b, fmt):
         _check_topk(b, case.head, case.W0, X, k, fmt)
 
 
+def test_topk_passes_collected_per_workgroup_over_several_label_tiles(b):
+    """Three batch tiles (600 queries) and a level of 96 label tiles: more tiles than one workgroup per
+    CU, so every workgroup of that level walks two label tiles of one batch tile (a grid of 255, the
+    multiple of three below 256) and hands the passes it collected in LDS to the rows' lists at its
+    end; with k = 20 few scores pass per row, with k = 60 (the largest k for which that level still
+    takes the sparse form) a few rows fill their eight LDS entries and append the rest directly.  Both
+    against the oracle's full sort."""
+    L, d, B = 40000 + 3, 128, 600
+    case = Case(b, L, d, o.E4M3, 8192, 0, B, w_std=0.05, seed=29)
+    X = synth.make_x(np.random.default_rng(6), B, d)
+    for k in (20, 60):
+        say(f"[topk-collect] k={k}")
+        _check_topk(b, case.head, case.W0, X, k, o.E4M3)
+
+
 @pytest.mark.parametrize("fmt,L,B,ks", [(o.E4M3, 3000 + 17, 70, (129, 300, 500)), (o.BF16, 300, 9, (256, 300)), (o.E4M3, 131, 3, (131,))])
 def test_topk_beyond_one_page(b, fmt, L, B, ks):
     """k above 128 comes in pages of 128 entries, every page one more sweep that admits only what
