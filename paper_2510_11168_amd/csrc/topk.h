@@ -1,7 +1,7 @@
 // Top-k scoring over all labels (the top_k of the paper's P@k definition) for gfx950.
 //
 // The [B, L] score matrix is never formed.  Main path: the labels are visited in levels of
-// geometrically growing size (the first 2048, then each level takes the labels seen so far from
+// geometrically growing size (the first 1024, then each level takes the labels seen so far from
 // N to 4 N).  A level computes its logits tile by tile on the matrix cores exactly as the
 // training step does (E4M3 x E4M3 or BF16 x BF16, FP32 accumulation) and appends every score that
 // beats the row's threshold -- the k-th best score over all earlier levels -- to the row's
@@ -42,7 +42,7 @@ constexpr int kTopkCand = 4096;                    // candidate list length per 
 constexpr int kTopkCntStride = 32;                 // ints between two rows' candidate counters: one 128-byte line each, so that the
                                                    // atomic additions of different rows do not queue up on the same few lines
 constexpr int kTopkGrowth = 4;                     // labels seen after a level / labels seen before it
-constexpr int kTopkLevel0 = 2048;                  // labels of the first level
+constexpr int kTopkLevel0 = 1024;                  // labels of the first level
 constexpr int kTopkRows = 64;                       // query rows per workgroup
 constexpr int kTopkZP = 132;                        // floats per staged row
 constexpr int kTopkLP = 129;                        // list pitch (odd: one row per thread, no bank clash)

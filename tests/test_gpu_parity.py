@@ -856,9 +856,9 @@ def test_topk_small_brute_force(b, fmt):
 def test_topk_one_slab_per_tile_and_several_batch_tiles(b, fmt):
     """d = 128: an E4M3 tile is a single 128-byte K slab, so the kernel that keeps its ring running from
     tile to tile changes tile at every slab (thresholds of the next tile's rows fetched a tile ahead);
-    300 queries are two batch tiles, the second ragged; 9000 + 5 labels are the first level, three
-    more levels (one of them with the aggregated appends) and a ragged last label tile; k = 100 and a
-    second page (k = 130)."""
+    300 queries are two batch tiles, the second ragged; 9000 + 5 labels are the first level, two
+    more levels (both in the form for levels where many scores pass) and a ragged last label tile;
+    k = 100 and a second page (k = 130)."""
     L, d, B = 9000 + 5, 128, 300
     case = Case(b, L, d, fmt, 4096, 0, B, w_std=0.05, seed=23)
     X = synth.make_x(np.random.default_rng(5), B, d)
@@ -868,9 +868,9 @@ def test_topk_one_slab_per_tile_and_several_batch_tiles(b, fmt):
 
 
 def test_topk_passes_collected_per_workgroup_over_several_label_tiles(b):
-    """Three batch tiles (600 queries) and a level of 96 label tiles: more tiles than one workgroup per
-    CU, so every workgroup of that level walks two label tiles of one batch tile (a grid of 255, the
-    multiple of three below 256) and hands the passes it collected in LDS to the rows' lists at its
+    """Three batch tiles (600 queries) and a last level of 93 label tiles: more tiles than one workgroup
+    per CU, so the workgroups of that level walk one or two label tiles of one batch tile (a grid of 255,
+    the multiple of three below 256) and hands the passes it collected in LDS to the rows' lists at its
     end; with k = 20 few scores pass per row, with k = 60 (the largest k for which that level still
     takes the sparse form) a few rows fill their eight LDS entries and append the rest directly.  Both
     against the oracle's full sort."""
